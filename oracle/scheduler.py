@@ -1,0 +1,172 @@
+"""Integer model of the fused stage's bookkeeping.  TEST INFRASTRUCTURE ONLY.
+
+The paper fixes the events (Section 4): samples leave the generation stage one by one as
+they reach their termination point; once the number of samples still in generation falls
+below the trigger R_t (Section 4.2, "Migration triggering"), finished samples flow to the
+inference stage as they complete (Section 4.2, end), and the KV-cache budget C bounds how
+many long samples an instance may hold (Section 4.2, "Migration destination", second
+constraint).  It does not fix an engine's slot order, page order or batch boundaries; the
+rules below are this build's reading, stated so that every integer is determined:
+
+* Samples are ids 0..N-1; the waiting queue is FIFO.  Sample i reserves
+  ceil((P_i + max_new_i) / page) pages.  At the top of a step the head of the queue is
+  admitted while the reservation fits the pool and the active array has room; the first
+  sample that does not fit blocks those behind it.
+* The free list is a stack that first issues pages 0, 1, 2, ...  A sample takes a page
+  exactly when it is about to write a position that is a multiple of the page size.
+  Newcomers take their prompt pages in position order, newcomers in id order, before the
+  step's decode growth, which goes in slot order.
+* A newcomer is prefilled (its first output token), joins the END of the active array,
+  and takes part in the same step's decode unless already at its target length.  A sample
+  of length L costs one prefill and L-1 decode inputs; its last token is never fed back.
+* retire(): scan slots in order; a sample whose generated length equals its target
+  leaves; its pages go back in reverse page-table order; survivors keep their order.
+* Scoring batches: after each step's retire, if scoring is enabled (fused mode and
+  remaining = waiting + active < R_t, or generation is over) the un-scored part of the
+  retired FIFO is cut, from its head, into consecutive batches each reaching at least
+  `score_chunk_tokens` prompt+response tokens; when generation is over the remainder is
+  flushed as a last, smaller batch.  Sequential mode (fused = 0) applies the same cut only
+  after the last step.
+"""
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+
+@dataclass
+class StepInfo:
+    step: int
+    n_admitted: int
+    n_prefill_tokens: int
+    n_decoded: int
+    n_active: int
+
+
+class SchedulerModel:
+    def __init__(self, prompt_lens: Sequence[int], max_new: Sequence[int],
+                 target_len: Sequence[int], pool_pages: int, page_tokens: int = 16,
+                 max_active: Optional[int] = None):
+        self.N = len(prompt_lens)
+        self.P = [int(p) for p in prompt_lens]
+        self.max_new = [int(m) for m in max_new]
+        self.target = [int(t) for t in target_len]
+        assert all(1 <= t <= m for t, m in zip(self.target, self.max_new))
+        self.page = int(page_tokens)
+        self.pool_pages = int(pool_pages)
+        self.max_active = self.N if max_active is None else int(max_active)
+        self.reserve = [-(-(p + m) // self.page) for p, m in zip(self.P, self.max_new)]
+        if any(r > self.pool_pages for r in self.reserve):
+            raise MemoryError("a sample's reservation exceeds the pool")
+        self.waiting = list(range(self.N))           # head at index 0
+        self.active: List[int] = []                  # slot order
+        self.ctx = [0] * self.N                      # tokens whose K/V are cached
+        self.gen_len = [0] * self.N
+        self.pages: List[List[int]] = [[] for _ in range(self.N)]
+        self.free = list(range(self.pool_pages - 1, -1, -1))   # pop() issues 0, 1, 2, ...
+        self.reserved = 0
+        self.retired: List[int] = []
+        self.n_scored = 0                            # retired[:n_scored] are in some batch
+        self.batches: List[List[int]] = []
+        self.batch_step: List[int] = []              # step after which each batch closed
+        self.step = 0
+        self.admit_step = [-1] * self.N
+
+    # ----------------------------------------------------------------- generation
+    def _write_position(self, i: int):
+        """Sample i is about to write K/V at position ctx[i]."""
+        if self.ctx[i] % self.page == 0:
+            self.pages[i].append(self.free.pop())
+        self.ctx[i] += 1
+
+    def generate_step(self) -> StepInfo:
+        newcomers = []
+        while (self.waiting and len(self.active) + len(newcomers) < self.max_active
+               and self.reserved + self.reserve[self.waiting[0]] <= self.pool_pages):
+            i = self.waiting.pop(0)
+            self.reserved += self.reserve[i]
+            newcomers.append(i)
+        for i in newcomers:                          # prefill: prompt positions, y_1
+            for _ in range(self.P[i]):
+                self._write_position(i)
+            self.gen_len[i] = 1
+            self.admit_step[i] = self.step
+            self.active.append(i)
+        n_dec = 0
+        for i in self.active:                        # decode: feed the last token
+            if self.gen_len[i] < self.target[i]:
+                self._write_position(i)
+                self.gen_len[i] += 1
+                n_dec += 1
+        info = StepInfo(self.step, len(newcomers), sum(self.P[i] for i in newcomers), n_dec,
+                        len(self.active))
+        self.step += 1
+        return info
+
+    def retire(self) -> List[int]:
+        out, keep = [], []
+        for i in self.active:
+            if self.gen_len[i] == self.target[i]:
+                for pg in reversed(self.pages[i]):
+                    self.free.append(pg)
+                self.pages[i] = []
+                self.reserved -= self.reserve[i]
+                self.retired.append(i)
+                out.append(i)
+            else:
+                keep.append(i)
+        self.active = keep
+        return out
+
+    def generation_done(self) -> bool:
+        return not self.waiting and not self.active
+
+    # -------------------------------------------------------------------- scoring
+    def seq_tokens(self, i: int) -> int:
+        return self.P[i] + self.target[i]
+
+    def form_batches(self, chunk_tokens: int) -> List[List[int]]:
+        """Cut the un-scored FIFO into batches of >= chunk_tokens; flush when generation is
+        over.  Returns the batches closed by this call."""
+        chunk = max(1, int(chunk_tokens))
+        new = []
+        while True:
+            k, tok = self.n_scored, 0
+            while k < len(self.retired) and tok < chunk:
+                tok += self.seq_tokens(self.retired[k])
+                k += 1
+            if tok >= chunk or (self.generation_done() and k > self.n_scored):
+                new.append(self.retired[self.n_scored:k])
+                self.n_scored = k
+            else:
+                break
+        for b in new:
+            self.batches.append(b)
+            self.batch_step.append(self.step - 1)
+        return new
+
+    def run_stage(self, fused: bool, R_t: int, chunk_tokens: int):
+        """Whole stage.  Returns the per-step trace [(StepInfo, retired ids, new batches)]."""
+        trace = []
+        while not self.generation_done():
+            info = self.generate_step()
+            gone = self.retire()
+            new = []
+            remaining = len(self.waiting) + len(self.active)
+            if (fused and remaining < R_t) or self.generation_done():
+                new = self.form_batches(chunk_tokens)
+            trace.append((info, gone, new))
+        return trace
+
+    # ------------------------------------------------------------------- snapshot
+    def snapshot(self) -> dict:
+        return {
+            "step": self.step,
+            "n_waiting": len(self.waiting),
+            "active": list(self.active),
+            "ctx": list(self.ctx),
+            "gen_len": list(self.gen_len),
+            "pages": [list(p) for p in self.pages],
+            "free": list(self.free),
+            "reserved": self.reserved,
+            "retired": list(self.retired),
+            "batches": [list(b) for b in self.batches],
+        }

@@ -1,0 +1,117 @@
+"""Pins for oracle/scheduler.py: a three-sample run worked out by hand, and brute-force
+invariants on random workloads."""
+import numpy as np
+import pytest
+
+from oracle.scheduler import SchedulerModel
+
+
+def _hand_model():
+    # page = 4 tokens, pool = 6 pages.  (P, max_new, L): s0 (5,3,3)  s1 (3,5,2)  s2 (6,6,4)
+    # reservations ceil((P+max_new)/4) = 2, 2, 3  -> s2 must wait for a retirement.
+    return SchedulerModel([5, 3, 6], [3, 5, 6], [3, 2, 4], pool_pages=6, page_tokens=4)
+
+
+def test_hand_worked_three_samples():
+    m = _hand_model()
+    # step 0: admit s0, s1 (2+2 <= 6; s2 would make 7).  Prefill s0 writes 0..4 -> pages 0,1;
+    # s1 writes 0..2 -> page 2.  Decode: s0 writes 5, s1 writes 3; both now have 2 tokens.
+    i0 = m.generate_step()
+    assert (i0.n_admitted, i0.n_prefill_tokens, i0.n_decoded, i0.n_active) == (2, 8, 2, 2)
+    assert m.pages[:2] == [[0, 1], [2]] and m.ctx == [6, 4, 0] and m.gen_len == [2, 2, 0]
+    assert m.retire() == [1]                       # s1 reached L = 2; page 2 returns
+    assert m.free == [5, 4, 3, 2] and m.reserved == 2 and m.active == [0]
+    # step 1: s2 fits now (2+3).  Its prompt 0..5 -> pages 2 (re-issued), 3.  Decode: s0
+    # writes 6 (gen 3 = L), s2 writes 6.
+    i1 = m.generate_step()
+    assert (i1.n_admitted, i1.n_prefill_tokens, i1.n_decoded, i1.n_active) == (1, 6, 2, 2)
+    assert m.pages[2] == [2, 3] and m.ctx == [7, 4, 7] and m.active == [0, 2]
+    assert m.retire() == [0]                       # pages 1 then 0 go back: 0 is issued next
+    assert m.free == [5, 4, 1, 0] and m.reserved == 3
+    # step 2: s2 writes 7.  step 3: s2 writes 8 -> new page (0); gen 4 = L.
+    assert m.generate_step().n_decoded == 1 and m.retire() == []
+    assert m.generate_step().n_decoded == 1
+    assert m.pages[2] == [2, 3, 0] and m.ctx[2] == 9
+    assert m.retire() == [2]
+    assert m.free == [5, 4, 1, 0, 3, 2] and m.reserved == 0
+    assert m.retired == [1, 0, 2] and m.generation_done() and m.step == 4
+    assert m.admit_step == [0, 0, 1]
+
+
+@pytest.mark.parametrize("fused,R_t,chunk,want,want_steps", [
+    (True, 4, 10, [[1, 0], [2]], [1, 3]),     # 5 tok after step 0; 5+8 >= 10 after step 1
+    (True, 2, 10, [[1, 0], [2]], [1, 3]),     # remaining (1 waiting + 1 active) < 2 only after step 1
+    (True, 1, 10, [[1, 0], [2]], [3, 3]),     # remaining < 1 only when generation is over
+    (False, 4, 10, [[1, 0], [2]], [3, 3]),    # sequential: same cut, all after the last step
+    (True, 4, 1, [[1], [0], [2]], [0, 1, 3]),  # chunk 1: every sample alone, as it retires
+    (True, 4, 100, [[1, 0, 2]], [3]),         # never reaches the chunk: flushed at the end
+])
+def test_hand_worked_batches(fused, R_t, chunk, want, want_steps):
+    m = _hand_model()
+    trace = m.run_stage(fused, R_t, chunk)
+    assert len(trace) == 4
+    assert m.batches == want and m.batch_step == want_steps
+    assert [len(t[2]) for t in trace].count(0) == 4 - len(set(want_steps))
+
+
+def _check_invariants(m: SchedulerModel):
+    owned = [p for pl in m.pages for p in pl]
+    assert len(owned) == len(set(owned))                         # a page has one owner
+    assert sorted(owned + m.free) == list(range(m.pool_pages))   # free + owned = pool
+    for i in range(m.N):
+        assert len(m.pages[i]) == (-(-m.ctx[i] // m.page) if i in m.active else 0)
+    assert m.active == sorted(m.active)                          # admission order = id order
+    assert m.reserved == sum(m.reserve[i] for i in m.active) <= m.pool_pages
+    assert len(m.active) <= m.max_active
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_invariants_random(seed):
+    r = np.random.default_rng(seed)
+    N = int(r.integers(1, 40))
+    P = r.integers(1, 70, N)
+    L = np.minimum(np.floor(4 * r.uniform(1e-3, 1, N) ** (-1 / 1.2)), 150).astype(int)
+    max_new = L + r.integers(0, 20, N) if seed % 2 else np.full(N, 150)
+    page = int(r.choice([4, 16]))
+    need = max(-(-(int(p) + int(mn)) // page) for p, mn in zip(P, max_new))
+    pool = int(need * r.choice([1, 2, 5]))
+    m = SchedulerModel(P, max_new, L, pool, page, max_active=int(r.choice([3, N])))
+    chunk = int(r.choice([1, 64, 400]))
+    R_t = int(r.integers(0, N + 2))
+    finish = {}
+    while not m.generation_done():
+        info = m.generate_step()
+        _check_invariants(m)
+        for i in m.retire():
+            finish[i] = info.step
+        _check_invariants(m)
+        if len(m.waiting) + len(m.active) < R_t or m.generation_done():
+            m.form_batches(chunk)
+    assert sorted(m.retired) == list(range(N)) and len(m.free) == pool and m.reserved == 0
+    for i in range(N):                    # prefill and the first decode share the admit step
+        assert finish[i] == m.admit_step[i] + max(int(L[i]) - 2, 0)
+        assert m.gen_len[i] == L[i] and m.ctx[i] == P[i] + L[i] - 1
+    assert m.step == max(finish.values()) + 1
+    assert [i for b in m.batches for i in b] == m.retired        # batches tile the FIFO in order
+    for b in m.batches[:-1]:
+        tok = [m.seq_tokens(i) for i in b]
+        assert sum(tok) >= chunk and sum(tok[:-1]) < chunk       # minimal prefix reaching the chunk
+    # waiting samples are admitted in order
+    adm = [m.admit_step[i] for i in range(N)]
+    assert adm == sorted(adm)
+
+
+def test_oversized_sample_is_rejected():
+    with pytest.raises(MemoryError):
+        SchedulerModel([100], [100], [5], pool_pages=3, page_tokens=16)
+
+
+def test_fused_and_sequential_score_the_same_samples():
+    """Section 4.1: fusion re-times sample-level subtasks; the set of scored samples and each
+    sample's own inputs do not change."""
+    P, L = [7, 9, 30, 4, 4, 18], [3, 40, 2, 9, 1, 5]
+    a = SchedulerModel(P, [40] * 6, L, 12, 16); a.run_stage(True, 7, 32)
+    b = SchedulerModel(P, [40] * 6, L, 12, 16); b.run_stage(False, 0, 32)
+    assert a.retired == b.retired and a.step == b.step
+    assert sorted(i for x in a.batches for i in x) == sorted(i for x in b.batches for i in x)
+    assert a.batch_step != b.batch_step
