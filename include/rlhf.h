@@ -1,0 +1,228 @@
+/*
+ * rlhf.h -- C ABI of the fused generation + inference stage for one MI355X.
+ *
+ * The stage is the one the paper's Section 2.1 defines and Section 4 fuses: the Actor
+ * generates a response for every prompt (prefill, then one token per decoding step until
+ * the termination point), and the Reference, Critic and Reward models each run a forward
+ * pass over prompt + response.  Section 4.1's observation is that the dependency between
+ * the two stages holds per sample, so a finished sample can be scored while long-tailed
+ * samples are still decoding; this library runs the two as streams on one GPU.
+ *
+ * Conventions
+ *   - Every call returns 0 (RLHF_OK) or a negative rlhf_status; rlhf_last_error() then
+ *     gives a message owned by the context.  Nothing throws or aborts across this ABI.
+ *   - "device" pointers are HIP device memory on the current device; "host" pointers are
+ *     ordinary host memory.  Weight tensors are caller-owned and BORROWED: they must stay
+ *     alive and unchanged until rlhf_destroy().  Host arrays passed to rlhf_submit() are
+ *     copied before it returns.  Result and snapshot buffers are caller-allocated host
+ *     arrays filled before the call returns.
+ *   - The library owns the paged KV pool, page tables, workspaces and (unless given) its
+ *     two HIP streams.  It allocates device memory only in rlhf_create()/rlhf_submit().
+ *   - One context may be used from one host thread at a time.
+ */
+#ifndef RLHF_H
+#define RLHF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rlhf_ctx rlhf_ctx;
+
+enum rlhf_status {
+    RLHF_OK = 0,
+    RLHF_EINVAL = -1,  /* bad argument, shape the kernels do not support, id out of range */
+    RLHF_ENOMEM = -2,  /* KV pool cannot hold a sample's reservation; allocation failed    */
+    RLHF_ESTATE = -3,  /* call out of order (e.g. scoring a sample still generating)       */
+    RLHF_EDEVICE = -4  /* a HIP call failed                                                */
+};
+
+/* The four models of Section 2.1 ("RLHF models"). */
+enum rlhf_role { RLHF_ACTOR = 0, RLHF_REF = 1, RLHF_CRITIC = 2, RLHF_REWARD = 3 };
+#define RLHF_ROLE_BIT(r) (1u << (r))
+
+enum rlhf_dtype { RLHF_FP32 = 0, RLHF_BF16 = 1 };
+
+/* Decoder shape shared by the four roles: pre-norm blocks, RMSNorm, rotary embedding on
+ * pairs (k, k + head_dim/2), grouped KV heads, SwiGLU MLP, no biases.  dtype is the
+ * storage type of matrices, activations fed to the matrix units and the KV cache; the
+ * residual stream, norms, softmax and all accumulation are float32 in either case.
+ * Requirements: head_dim in {64, 128}; d_model, ffn multiples of 8; n_q_heads a multiple
+ * of n_kv_heads. */
+typedef struct rlhf_model_cfg {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+    int32_t dtype;                 /* rlhf_dtype */
+    float rms_eps, rope_base;
+} rlhf_model_cfg;
+
+/* Engine limits.  kv_pool_bytes is the budget "C" of Section 4.2's memory constraint; a
+ * sample reserves ceil((prompt + max_new) / page_tokens) pages on admission ("M"). */
+typedef struct rlhf_engine_cfg {
+    int32_t page_tokens;           /* tokens per KV page; must be 16                          */
+    int64_t kv_pool_bytes;         /* device bytes for the paged KV pool                      */
+    int32_t max_samples;           /* upper bound on samples per rlhf_submit()                */
+    int32_t max_ctx;               /* upper bound on prompt + max_new of any sample           */
+    int32_t max_active;            /* decode batch limit (rows of the decode workspace)       */
+    int32_t max_batch_tokens;      /* rows of one prefill / scoring pass; >= max_ctx          */
+    int32_t eos_id;                /* termination token                                       */
+    int32_t stop_on_eos;           /* 1: a sample also ends when it emits eos_id (costs one
+                                      device->host copy per step); 0: length-driven only     */
+    void* decode_stream;           /* hipStream_t to use, or NULL: the library creates one    */
+    void* score_stream;            /* hipStream_t to use, or NULL                             */
+} rlhf_engine_cfg;
+
+/* One role's tensors (device pointers, element type per rlhf_model_cfg.dtype except the
+ * norm gains, which are float32).  Row-major, last index contiguous:
+ *   embed      [vocab, d_model]
+ *   wqkv       [n_layers, (n_q_heads + 2 n_kv_heads) * head_dim, d_model]  Q rows, K rows, V rows
+ *   wo         [n_layers, d_model, n_q_heads * head_dim]
+ *   w_gate_up  [n_layers, 2 * ffn, d_model]                                gate rows, up rows
+ *   w_down     [n_layers, d_model, ffn]
+ *   g_attn, g_mlp [n_layers, d_model] float32;  g_final [d_model] float32
+ *   head       ACTOR/REF: LM head [vocab, d_model]; CRITIC/REWARD: one row [1, d_model]
+ * y = W x for every matrix (rows are outputs). */
+typedef struct rlhf_weights {
+    const void* embed;
+    const void* wqkv;
+    const void* wo;
+    const void* w_gate_up;
+    const void* w_down;
+    const float* g_attn;
+    const float* g_mlp;
+    const float* g_final;
+    const void* head;
+} rlhf_weights;
+
+typedef struct rlhf_step_info {
+    int32_t step;                  /* index of the step just run (0-based)                    */
+    int32_t n_admitted;            /* samples admitted and prefilled at the top of the step   */
+    int32_t n_prefill_tokens;
+    int32_t n_decoded;             /* rows of the decode batch                                */
+    int32_t n_active;              /* active-array length after the step (before retire)      */
+} rlhf_step_info;
+
+typedef struct rlhf_stage_opts {
+    int32_t fused;                 /* 1: score retired samples on the score stream while
+                                      decoding goes on (Section 4); 0: generate everything,
+                                      then score (the serial plan of Figure 4, top)           */
+    int32_t R_t;                   /* Section 4.2 trigger: scoring is enabled once the number
+                                      of samples still in generation is below R_t.  R_t >
+                                      n_samples enables it from the first retirement          */
+    int32_t score_chunk_tokens;    /* a scoring batch closes when the queued retired samples
+                                      hold at least this many prompt+response tokens          */
+    uint32_t role_mask;            /* roles to score: bits REF, CRITIC, REWARD, and ACTOR to
+                                      re-score the Actor's log-probs by a full forward        */
+    int32_t* trace_active;         /* optional host arrays, trace_cap entries: per step the   */
+    int32_t* trace_decoded;        /*   active count after retire, the decode rows, and the   */
+    float* trace_step_ms;          /*   decode-stream time of the step (adds two events/step) */
+    int32_t trace_cap;
+} rlhf_stage_opts;
+
+typedef struct rlhf_stage_stats {
+    int32_t n_steps, n_batches;
+    int64_t generated_tokens;      /* sum of output lengths                                   */
+    int64_t scored_tokens;         /* sum of prompt+response lengths (counted once)           */
+    int64_t prefill_tokens;
+    double wall_ms;                /* host wall clock of the whole stage, device drained      */
+    double decode_stream_ms;       /* first to last work on the decode stream                 */
+    double score_stream_ms;        /* first to last work on the score stream (0 if none)      */
+    int64_t decode_weight_bytes;   /* algorithmic bytes: weights read by all decode steps     */
+    int64_t decode_kv_bytes;       /*   KV read + written by all decode steps                 */
+} rlhf_stage_stats;
+
+/* Stage outputs, in sample-id order.  Any pointer may be NULL to skip it. */
+typedef struct rlhf_results {
+    int32_t* gen_len;              /* [n]                                                     */
+    int64_t* resp_offsets;         /* [n+1] prefix sums of gen_len                            */
+    int32_t* tokens;               /* packed by resp_offsets: y_1 .. y_L of each sample       */
+    float* lp_actor;               /* packed: Actor log-prob of y_j, captured while decoding  */
+    float* lp_actor_rescored;      /* packed: the same by a scoring forward (role ACTOR)      */
+    float* lp_ref;                 /* packed: Reference log-prob of y_j                       */
+    float* values;                 /* packed: Critic value at the state before y_j            */
+    float* reward;                 /* [n] Reward model score at the last token                */
+    int64_t packed_capacity;       /* entries available in each packed array                  */
+} rlhf_results;
+
+/* Integer state for bit-exact checks of the bookkeeping. */
+typedef struct rlhf_snapshot {
+    int32_t step, n_samples, n_waiting, n_active, n_retired, n_batches, n_free;
+    int32_t reserved_pages, pool_pages, max_pages;   /* max_pages = row stride of page_table */
+    int32_t* active;               /* [cap_samples] sample ids in slot order                  */
+    int32_t* ctx;                  /* [cap_samples] tokens whose K/V are cached               */
+    int32_t* gen_len;              /* [cap_samples]                                           */
+    int32_t* n_pages;              /* [cap_samples]                                           */
+    int32_t* page_table;           /* [cap_samples * cap_max_pages]                           */
+    int32_t* free_list;            /* [cap_pool_pages] stack, top last                        */
+    int32_t* retired;              /* [cap_samples] retire order                              */
+    int32_t* batch_offsets;        /* [cap_samples + 1] batches tile `retired` in order       */
+    int32_t* batch_step;           /* [cap_samples] step after which each batch closed        */
+    int32_t cap_samples, cap_max_pages, cap_pool_pages;
+} rlhf_snapshot;
+
+/* Create a context: validates shapes, allocates the KV pool, page tables, workspaces and
+ * streams.  On failure *out is NULL and the message is available from rlhf_last_error(NULL). */
+int rlhf_create(const rlhf_model_cfg* model, const rlhf_engine_cfg* engine, rlhf_ctx** out);
+void rlhf_destroy(rlhf_ctx* ctx);
+const char* rlhf_last_error(const rlhf_ctx* ctx);
+
+/* Bind one role's weights (borrowed device pointers).  ACTOR is needed to generate; a role
+ * must be bound before it is scored. */
+int rlhf_load_weights(rlhf_ctx* ctx, int role, const rlhf_weights* w);
+
+/* Queue n samples (ids 0..n-1 in this order) and reset the stage state: empty KV pool,
+ * empty active set, no results.  Host arrays:
+ *   prompt_tokens packed by prompt_offsets[n+1]; every prompt has >= 1 token
+ *   max_new[n]      cap on output length (>= 1); drives the KV reservation
+ *   forced_len[n]   or NULL: the sample ends at exactly this output length and its last token
+ *                   is replaced by eos_id (the synthetic workloads' termination rule);
+ *                   NULL: ends at max_new (or at eos_id when stop_on_eos)
+ *   forced_tokens   or NULL: teacher forcing, packed by forced_offsets[n+1] (one entry per
+ *                   output index up to the sample's length); -1 leaves the position greedy
+ * RLHF_ENOMEM if one sample's reservation alone exceeds the pool. */
+int rlhf_submit(rlhf_ctx* ctx, int32_t n, const int32_t* prompt_tokens,
+                const int64_t* prompt_offsets, const int32_t* max_new,
+                const int32_t* forced_len, const int32_t* forced_tokens,
+                const int64_t* forced_offsets);
+
+/* One step of the generation stage (Section 2.1): admit waiting samples while their KV
+ * reservation fits, prefill them (first output token), grow page tables, then ONE decoding
+ * step over the active set: greedy token (lowest id on ties) and its Actor log-prob per
+ * sample.  Work is enqueued on the decode stream; the call does not wait for it unless
+ * stop_on_eos.  RLHF_ESTATE if nothing is waiting or active. */
+int rlhf_generate_step(rlhf_ctx* ctx, rlhf_step_info* out);
+
+/* Termination test after a step: samples that reached their length (or emitted eos_id)
+ * leave the active set in slot order, their pages return to the pool, the survivors are
+ * compacted keeping their order, and the leavers join the retired FIFO.  retired_ids (host,
+ * capacity >= active count, may be NULL) receives them. */
+int rlhf_retire(rlhf_ctx* ctx, int32_t* retired_ids, int32_t* n_retired);
+
+/* Inference stage for n retired samples as one packed batch (Section 2.1): for each role in
+ * role_mask one causal forward over prompt + response; REF/ACTOR give the log-prob of every
+ * response token, CRITIC a value per response token, REWARD one scalar at the last token.
+ * Enqueued on the score stream (on_score_stream != 0), which first waits for the decode
+ * stream's work issued so far, or on the decode stream.  Results stay on the device until
+ * rlhf_get_results(). */
+int rlhf_score(rlhf_ctx* ctx, int32_t n, const int32_t* sample_ids, uint32_t role_mask,
+               int32_t on_score_stream);
+
+/* The whole stage: loop {generate_step, retire, form scoring batches, score} until every
+ * sample is generated and scored; returns with both streams drained.  fused = 0 is the
+ * serial baseline with the same kernels and the same batch rule. */
+int rlhf_run_stage(rlhf_ctx* ctx, const rlhf_stage_opts* opts, rlhf_stage_stats* out);
+
+/* Drain both streams, then copy the stage outputs to the caller's host arrays. */
+int rlhf_get_results(rlhf_ctx* ctx, rlhf_results* out);
+
+/* Copy the integer bookkeeping state (host-side, no device work). */
+int rlhf_debug_snapshot(rlhf_ctx* ctx, rlhf_snapshot* out);
+
+/* Wait for all work enqueued so far on both streams. */
+int rlhf_sync(rlhf_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RLHF_H */

@@ -1,0 +1,50 @@
+/*
+ * rlhf_ops.h -- kernel-level entry points of the same library, for per-kernel parity tests
+ * and roofline measurements.  The stage API in rlhf.h is built from exactly these kernels.
+ *
+ * All pointers are DEVICE pointers owned by the caller; `stream` is a hipStream_t (NULL =
+ * the default stream).  Calls enqueue work and return without waiting.  Return values are
+ * rlhf_status codes (0 = OK, RLHF_EINVAL for unsupported shapes, RLHF_EDEVICE for a failed
+ * launch).  dtype is an rlhf_dtype and selects the storage type of A/W/q/k/v/out.
+ */
+#ifndef RLHF_OPS_H
+#define RLHF_OPS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Linear projection y = W x of a decoder block (the matrix work of both the memory-bound
+ * decoding phase, Section 4.2, and the prefill-like inference forward, Section 2.1):
+ * C[s][m][n] = sum over the s-th K range of A[m][k] * W[n][k].  A [M,K], W [N,K] row-major in
+ * dtype; C float32 [nsplit][M][N]; the caller sums the nsplit partial planes.  K must be a
+ * multiple of 8 (bf16) or 4 (fp32).  rlhf_op_gemm_nsplit returns the split the stage itself
+ * would choose for this shape, at most max_split. */
+int rlhf_op_gemm_nsplit(int dtype, int M, int N, int K, int max_split);
+int rlhf_op_gemm(int dtype, const void* A, const void* W, float* C, int M, int N, int K, int nsplit,
+                 void* stream);
+
+/* Decode attention of one step (Section 2.1, decoding phase): row r holds one query
+ * [n_q_heads * head_dim] and attends to the ctx_len[r] cached tokens of the sample whose
+ * page-table row is row_sample[r].  pool layout: [page][layer][K|V][kv_head][16][head_dim].
+ * part_acc / part_ml are float32 scratch of rows*n_q_heads*nsplit*head_dim and
+ * rows*n_q_heads*nsplit*2 entries (unused when nsplit == 1). */
+int rlhf_op_paged_decode_attention(int dtype, const void* q, const void* pool, const int32_t* page_table,
+                                   int pt_stride, const int32_t* row_sample, const int32_t* ctx_len,
+                                   void* out, float* part_acc, float* part_ml, int rows, int layer,
+                                   int nsplit, int n_layers, int n_q_heads, int n_kv_heads, int head_dim,
+                                   void* stream);
+
+/* Packed variable-length causal attention of the prefill / inference forward (Section 2.1):
+ * q [T, n_q_heads*head_dim], k, v [T, n_kv_heads*head_dim]; row r belongs to the sequence that
+ * starts at row row_start[r] and is its row_pos[r]-th token. */
+int rlhf_op_varlen_attention(int dtype, const void* q, const void* k, const void* v,
+                             const int32_t* row_start, const int32_t* row_pos, void* out, int rows,
+                             int n_q_heads, int n_kv_heads, int head_dim, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RLHF_OPS_H */

@@ -267,8 +267,9 @@ def greedy_generate_cached(actor: Model, prompts: List[Sequence[int]], out_lens:
 # ------------------------------------------------------------------------------ scoring
 
 def score_logprobs(model: Model, prompt: Sequence[int], response: Sequence[int]) -> np.ndarray:
-    """Actor/Reference scoring: lp[j] = log_softmax(Z[P+j-1])[y_j], j = 1..L, from one
-    causal forward over prompt + response."""
+    """Actor/Reference scoring from one causal forward over prompt + response: for
+    j = 1..L, lp[j] = log_softmax(z)[y_j] with z the logits at the position just before
+    y_j (0-based row P+j-2 of Z: the last prompt token predicts y_1)."""
     P, L = len(prompt), len(response)
     _, Z = model.forward_full(list(prompt) + list(response))
     ls = log_softmax_rows(Z[P - 1:P + L - 1])
@@ -276,7 +277,8 @@ def score_logprobs(model: Model, prompt: Sequence[int], response: Sequence[int])
 
 
 def score_values(critic: Model, prompt: Sequence[int], response: Sequence[int]) -> np.ndarray:
-    """Critic: value[j] = <w_v, H[P+j-1]>, the value of the state before y_j; j = 1..L."""
+    """Critic: value[j] = <w_v, H[row]> at the same row that predicts y_j (0-based P+j-2),
+    i.e. the value of the state before y_j is chosen; j = 1..L."""
     P, L = len(prompt), len(response)
     _, Z = critic.forward_full(list(prompt) + list(response))
     return Z[P - 1:P + L - 1, 0]

@@ -1,0 +1,305 @@
+"""ctypes binding of librlhf.so: the same names as include/rlhf.h and include/rlhf_ops.h.
+
+Argument marshalling only -- every step of the stage runs in the library's HIP kernels.
+torch is used for device memory (weights are torch tensors whose data_ptr() is borrowed by
+the library) and numpy for the host arrays the ABI fills.  There is no fallback: if the
+shared library is missing or a call fails, an exception is raised.
+"""
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librlhf.so")
+
+RLHF_OK, RLHF_EINVAL, RLHF_ENOMEM, RLHF_ESTATE, RLHF_EDEVICE = 0, -1, -2, -3, -4
+RLHF_ACTOR, RLHF_REF, RLHF_CRITIC, RLHF_REWARD = 0, 1, 2, 3
+RLHF_FP32, RLHF_BF16 = 0, 1
+_STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "ESTATE", -4: "EDEVICE"}
+
+
+def RLHF_ROLE_BIT(role: int) -> int:
+    return 1 << role
+
+
+class RlhfError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"RLHF_{_STATUS.get(code, code)}: {msg}")
+        self.code = code
+
+
+class rlhf_model_cfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim",
+                                         "ffn", "vocab", "dtype")] + [("rms_eps", C.c_float),
+                                                                      ("rope_base", C.c_float)]
+
+
+class rlhf_engine_cfg(C.Structure):
+    _fields_ = [("page_tokens", C.c_int32), ("kv_pool_bytes", C.c_int64), ("max_samples", C.c_int32),
+                ("max_ctx", C.c_int32), ("max_active", C.c_int32), ("max_batch_tokens", C.c_int32),
+                ("eos_id", C.c_int32), ("stop_on_eos", C.c_int32), ("decode_stream", C.c_void_p),
+                ("score_stream", C.c_void_p)]
+
+
+class rlhf_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("embed", "wqkv", "wo", "w_gate_up", "w_down", "g_attn", "g_mlp",
+                                          "g_final", "head")]
+
+
+class rlhf_step_info(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("step", "n_admitted", "n_prefill_tokens", "n_decoded", "n_active")]
+
+
+class rlhf_stage_opts(C.Structure):
+    _fields_ = [("fused", C.c_int32), ("R_t", C.c_int32), ("score_chunk_tokens", C.c_int32),
+                ("role_mask", C.c_uint32), ("trace_active", C.c_void_p), ("trace_decoded", C.c_void_p),
+                ("trace_step_ms", C.c_void_p), ("trace_cap", C.c_int32)]
+
+
+class rlhf_stage_stats(C.Structure):
+    _fields_ = [("n_steps", C.c_int32), ("n_batches", C.c_int32), ("generated_tokens", C.c_int64),
+                ("scored_tokens", C.c_int64), ("prefill_tokens", C.c_int64), ("wall_ms", C.c_double),
+                ("decode_stream_ms", C.c_double), ("score_stream_ms", C.c_double),
+                ("decode_weight_bytes", C.c_int64), ("decode_kv_bytes", C.c_int64)]
+
+
+class rlhf_results(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("gen_len", "resp_offsets", "tokens", "lp_actor", "lp_actor_rescored",
+                                          "lp_ref", "values", "reward")] + [("packed_capacity", C.c_int64)]
+
+
+class rlhf_snapshot(C.Structure):
+    _fields_ = ([(n, C.c_int32) for n in ("step", "n_samples", "n_waiting", "n_active", "n_retired", "n_batches",
+                                          "n_free", "reserved_pages", "pool_pages", "max_pages")]
+                + [(n, C.c_void_p) for n in ("active", "ctx", "gen_len", "n_pages", "page_table", "free_list",
+                                             "retired", "batch_offsets", "batch_step")]
+                + [(n, C.c_int32) for n in ("cap_samples", "cap_max_pages", "cap_pool_pages")])
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load librlhf.so (built in-tree by paper_2409_13221_amd.build).  Fails loudly."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2409_13221_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, u32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32
+        L.rlhf_create.argtypes = [C.POINTER(rlhf_model_cfg), C.POINTER(rlhf_engine_cfg), C.POINTER(vp)]
+        L.rlhf_destroy.argtypes = [vp]
+        L.rlhf_destroy.restype = None
+        L.rlhf_last_error.argtypes = [vp]
+        L.rlhf_last_error.restype = C.c_char_p
+        L.rlhf_load_weights.argtypes = [vp, C.c_int, C.POINTER(rlhf_weights)]
+        L.rlhf_submit.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
+        L.rlhf_generate_step.argtypes = [vp, C.POINTER(rlhf_step_info)]
+        L.rlhf_retire.argtypes = [vp, vp, C.POINTER(i32)]
+        L.rlhf_score.argtypes = [vp, i32, vp, u32, i32]
+        L.rlhf_run_stage.argtypes = [vp, C.POINTER(rlhf_stage_opts), C.POINTER(rlhf_stage_stats)]
+        L.rlhf_get_results.argtypes = [vp, C.POINTER(rlhf_results)]
+        L.rlhf_debug_snapshot.argtypes = [vp, C.POINTER(rlhf_snapshot)]
+        L.rlhf_sync.argtypes = [vp]
+        L.rlhf_op_gemm_nsplit.argtypes = [C.c_int] * 5
+        L.rlhf_op_gemm.argtypes = [C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp]
+        L.rlhf_op_paged_decode_attention.argtypes = [C.c_int, vp, vp, vp, C.c_int, vp, vp, vp, vp, vp] + [C.c_int] * 8 + [vp]
+        L.rlhf_op_varlen_attention.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp] + [C.c_int] * 4 + [vp]
+        for name in ("rlhf_create", "rlhf_load_weights", "rlhf_submit", "rlhf_generate_step", "rlhf_retire",
+                     "rlhf_score", "rlhf_run_stage", "rlhf_get_results", "rlhf_debug_snapshot", "rlhf_sync",
+                     "rlhf_op_gemm_nsplit", "rlhf_op_gemm", "rlhf_op_paged_decode_attention",
+                     "rlhf_op_varlen_attention"):
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(ctx, rc: int):
+    if rc != RLHF_OK:
+        raise RlhfError(rc, lib().rlhf_last_error(ctx).decode())
+
+
+def _np(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+# ------------------------------------------------------------------------------ stage API
+
+def model_cfg_of(m) -> rlhf_model_cfg:
+    """rlhf_model_cfg from any object with the fields of workload.ModelCfg."""
+    return rlhf_model_cfg(m.n_layers, m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn, m.vocab,
+                          RLHF_FP32 if m.dtype == "fp32" else RLHF_BF16, m.rms_eps, m.rope_base)
+
+
+def rlhf_create(model: rlhf_model_cfg, engine: rlhf_engine_cfg) -> C.c_void_p:
+    ctx = C.c_void_p()
+    rc = lib().rlhf_create(C.byref(model), C.byref(engine), C.byref(ctx))
+    _check(None, rc)
+    return ctx
+
+
+def rlhf_destroy(ctx) -> None:
+    lib().rlhf_destroy(ctx)
+
+
+def rlhf_last_error(ctx) -> str:
+    return lib().rlhf_last_error(ctx).decode()
+
+
+def rlhf_load_weights(ctx, role: int, tensors: Dict[str, "torch.Tensor"]) -> None:
+    """tensors: name -> contiguous device tensor (the layout of rlhf_weights).  The caller keeps
+    them alive until rlhf_destroy."""
+    w = rlhf_weights()
+    for name, _ in rlhf_weights._fields_:
+        t = tensors[name]
+        if not t.is_contiguous() or not t.is_cuda:
+            raise ValueError(f"weight {name} must be a contiguous device tensor")
+        setattr(w, name, t.data_ptr())
+    _check(ctx, lib().rlhf_load_weights(ctx, role, C.byref(w)))
+
+
+def rlhf_submit(ctx, prompt_tokens, prompt_offsets, max_new, forced_len=None, forced_tokens=None,
+                forced_offsets=None) -> None:
+    pt, po, mn = _np(prompt_tokens, np.int32), _np(prompt_offsets, np.int64), _np(max_new, np.int32)
+    fl = None if forced_len is None else _np(forced_len, np.int32)
+    ft = None if forced_tokens is None else _np(forced_tokens, np.int32)
+    fo = None if forced_offsets is None else _np(forced_offsets, np.int64)
+    _check(ctx, lib().rlhf_submit(ctx, len(mn), _p(pt), _p(po), _p(mn), _p(fl), _p(ft), _p(fo)))
+
+
+def rlhf_generate_step(ctx) -> rlhf_step_info:
+    info = rlhf_step_info()
+    _check(ctx, lib().rlhf_generate_step(ctx, C.byref(info)))
+    return info
+
+
+def rlhf_retire(ctx, capacity: int) -> np.ndarray:
+    ids = np.zeros(max(capacity, 1), np.int32)
+    n = C.c_int32()
+    _check(ctx, lib().rlhf_retire(ctx, _p(ids), C.byref(n)))
+    return ids[:n.value].copy()
+
+
+def rlhf_score(ctx, sample_ids: Sequence[int], role_mask: int, on_score_stream: bool = True) -> None:
+    ids = _np(sample_ids, np.int32)
+    _check(ctx, lib().rlhf_score(ctx, len(ids), _p(ids), role_mask, int(on_score_stream)))
+
+
+def rlhf_run_stage(ctx, fused: bool, R_t: int, score_chunk_tokens: int, role_mask: int,
+                   trace_cap: int = 0, trace_time: bool = False):
+    """Returns (rlhf_stage_stats, trace dict or None)."""
+    o = rlhf_stage_opts(int(fused), R_t, score_chunk_tokens, role_mask, None, None, None, 0)
+    tr = None
+    if trace_cap > 0:
+        tr = {"active": np.zeros(trace_cap, np.int32), "decoded": np.zeros(trace_cap, np.int32)}
+        o.trace_active, o.trace_decoded, o.trace_cap = _p(tr["active"]), _p(tr["decoded"]), trace_cap
+        if trace_time:
+            tr["step_ms"] = np.zeros(trace_cap, np.float32)
+            o.trace_step_ms = _p(tr["step_ms"])
+    st = rlhf_stage_stats()
+    _check(ctx, lib().rlhf_run_stage(ctx, C.byref(o), C.byref(st)))
+    if tr is not None:
+        tr = {k: v[:st.n_steps] for k, v in tr.items()}
+    return st, tr
+
+
+def rlhf_get_results(ctx, n: int, packed_capacity: int) -> Dict[str, np.ndarray]:
+    out = {"gen_len": np.zeros(n, np.int32), "resp_offsets": np.zeros(n + 1, np.int64),
+           "tokens": np.zeros(packed_capacity, np.int32)}
+    for k in ("lp_actor", "lp_actor_rescored", "lp_ref", "values"):
+        out[k] = np.full(packed_capacity, np.nan, np.float32)
+    out["reward"] = np.full(n, np.nan, np.float32)
+    r = rlhf_results()
+    for name, _ in rlhf_results._fields_[:-1]:
+        setattr(r, name, _p(out[name]))
+    r.packed_capacity = packed_capacity
+    _check(ctx, lib().rlhf_get_results(ctx, C.byref(r)))
+    total = int(out["resp_offsets"][-1])
+    for k in ("tokens", "lp_actor", "lp_actor_rescored", "lp_ref", "values"):
+        out[k] = out[k][:total]
+    return out
+
+
+def rlhf_debug_snapshot(ctx, cap_samples: int, cap_max_pages: int, cap_pool_pages: int) -> dict:
+    a = {k: np.full(cap_samples, -1, np.int32) for k in ("active", "ctx", "gen_len", "n_pages", "retired",
+                                                         "batch_step")}
+    a["page_table"] = np.full(cap_samples * cap_max_pages, -1, np.int32)
+    a["free_list"] = np.full(max(cap_pool_pages, 1), -1, np.int32)
+    a["batch_offsets"] = np.zeros(cap_samples + 1, np.int32)
+    s = rlhf_snapshot()
+    for k, v in a.items():
+        setattr(s, k, _p(v))
+    s.cap_samples, s.cap_max_pages, s.cap_pool_pages = cap_samples, cap_max_pages, cap_pool_pages
+    _check(ctx, lib().rlhf_debug_snapshot(ctx, C.byref(s)))
+    n = s.n_samples
+    pt = a["page_table"].reshape(cap_samples, cap_max_pages)
+    retired = a["retired"][:s.n_retired].tolist()
+    bo = a["batch_offsets"][:s.n_batches + 1].tolist()
+    return {
+        "step": s.step, "n_waiting": s.n_waiting, "reserved": s.reserved_pages, "pool_pages": s.pool_pages,
+        "active": a["active"][:s.n_active].tolist(),
+        "ctx": a["ctx"][:n].tolist(), "gen_len": a["gen_len"][:n].tolist(),
+        "pages": [pt[i, :a["n_pages"][i]].tolist() for i in range(n)],
+        "free": a["free_list"][:s.n_free].tolist(),
+        "retired": retired,
+        "batches": [retired[bo[b]:bo[b + 1]] for b in range(s.n_batches)],
+        "batch_step": a["batch_step"][:s.n_batches].tolist(),
+    }
+
+
+def rlhf_sync(ctx) -> None:
+    _check(ctx, lib().rlhf_sync(ctx))
+
+
+# ------------------------------------------------------------------------- kernel-level API
+
+def _dt(t) -> int:
+    import torch
+    return RLHF_BF16 if t.dtype == torch.bfloat16 else RLHF_FP32
+
+
+def _stream_ptr():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _op_check(rc: int, what: str):
+    if rc != RLHF_OK:
+        raise RlhfError(rc, what)
+
+
+def rlhf_op_gemm_nsplit(dtype: int, M: int, N: int, K: int, max_split: int) -> int:
+    return lib().rlhf_op_gemm_nsplit(dtype, M, N, K, max_split)
+
+
+def rlhf_op_gemm(A, W, C_out, nsplit: int) -> None:
+    """A [M,K], W [N,K] device tensors (bf16 or fp32), C_out float32 [nsplit, M, N]; on torch's
+    current stream."""
+    M, K = A.shape
+    N = W.shape[0]
+    assert W.shape[1] == K and tuple(C_out.shape) == (nsplit, M, N) and A.is_contiguous() and W.is_contiguous()
+    _op_check(lib().rlhf_op_gemm(_dt(A), A.data_ptr(), W.data_ptr(), C_out.data_ptr(), M, N, K, nsplit,
+                                 _stream_ptr()), "rlhf_op_gemm")
+
+
+def rlhf_op_paged_decode_attention(q, pool, page_table, row_sample, ctx_len, out, part_acc, part_ml, layer: int,
+                                   nsplit: int, n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int):
+    rows = q.shape[0]
+    _op_check(lib().rlhf_op_paged_decode_attention(
+        _dt(q), q.data_ptr(), pool.data_ptr(), page_table.data_ptr(), page_table.shape[1], row_sample.data_ptr(),
+        ctx_len.data_ptr(), out.data_ptr(), part_acc.data_ptr() if part_acc is not None else None,
+        part_ml.data_ptr() if part_ml is not None else None, rows, layer, nsplit, n_layers, n_q_heads,
+        n_kv_heads, head_dim, _stream_ptr()), "rlhf_op_paged_decode_attention")
+
+
+def rlhf_op_varlen_attention(q, k, v, row_start, row_pos, out, n_q_heads: int, n_kv_heads: int, head_dim: int):
+    _op_check(lib().rlhf_op_varlen_attention(_dt(q), q.data_ptr(), k.data_ptr(), v.data_ptr(), row_start.data_ptr(),
+                                             row_pos.data_ptr(), out.data_ptr(), q.shape[0], n_q_heads, n_kv_heads,
+                                             head_dim, _stream_ptr()), "rlhf_op_varlen_attention")

@@ -1,0 +1,352 @@
+// Attention kernels.
+//
+// Decode (the memory-bound phase of Section 2.2 / 4.2): one query per active sample against
+// that sample's paged K/V.  A workgroup owns (sample, KV head, split); its four waves take the
+// pages of the split round-robin.  A page's K tile ([page_tokens][hd], contiguous) is read
+// with 16-byte loads, consecutive lanes on consecutive chunks; a lane holds 8 dims of one
+// token, the q.k dot product is finished with xor-shuffles inside the hd/8-lane group, and
+// the softmax runs online in float.  Each lane accumulates p*V for its own tokens; lanes are
+// merged by shuffles at the end, waves through LDS, splits by a small merge kernel (LSE
+// merge), so that a few long samples still spread over the whole chip.
+//
+// Prefill / scoring v1 uses the same inner loop over 16-token tiles of contiguous K/V (one
+// workgroup per query row and KV head).
+#include "common.cuh"
+#include "kernels.h"
+
+namespace rlhf {
+
+constexpr int kPT = 16;  // tokens per page / tile
+
+template <typename T> struct Chunk;           // 8 elements of T held raw
+template <> struct Chunk<bf16_t> { uint4 r; };
+template <> struct Chunk<float> { float4 a, b; };
+
+template <typename T> __device__ __forceinline__ Chunk<T> ld_chunk(const T* p);
+template <> __device__ __forceinline__ Chunk<bf16_t> ld_chunk<bf16_t>(const bf16_t* p) {
+    Chunk<bf16_t> c; c.r = *reinterpret_cast<const uint4*>(p); return c;
+}
+template <> __device__ __forceinline__ Chunk<float> ld_chunk<float>(const float* p) {
+    Chunk<float> c;
+    c.a = *reinterpret_cast<const float4*>(p);
+    c.b = *reinterpret_cast<const float4*>(p + 4);
+    return c;
+}
+template <typename T> __device__ __forceinline__ void unpack(const Chunk<T>& c, float (&o)[8]);
+template <> __device__ __forceinline__ void unpack<bf16_t>(const Chunk<bf16_t>& c, float (&o)[8]) {
+    o[0] = __uint_as_float(c.r.x << 16); o[1] = __uint_as_float(c.r.x & 0xFFFF0000u);
+    o[2] = __uint_as_float(c.r.y << 16); o[3] = __uint_as_float(c.r.y & 0xFFFF0000u);
+    o[4] = __uint_as_float(c.r.z << 16); o[5] = __uint_as_float(c.r.z & 0xFFFF0000u);
+    o[6] = __uint_as_float(c.r.w << 16); o[7] = __uint_as_float(c.r.w & 0xFFFF0000u);
+}
+template <> __device__ __forceinline__ void unpack<float>(const Chunk<float>& c, float (&o)[8]) {
+    o[0] = c.a.x; o[1] = c.a.y; o[2] = c.a.z; o[3] = c.a.w;
+    o[4] = c.b.x; o[5] = c.b.y; o[6] = c.b.z; o[7] = c.b.w;
+}
+
+// Per-lane running softmax state for one query head.
+struct HeadState {
+    float m, l;
+    float acc[8];
+};
+
+// Process one tile of up to 16 tokens for G query heads.  HD/8 lanes share a token (each 8
+// dims); TPP tokens per pass; PASSES passes cover the tile.
+//   kt, vt : tile bases (token 0, dim 0) with token stride `tstride` elements
+//   n_valid: tokens of this tile that exist (1..16)
+template <typename T, int HD, int G>
+__device__ __forceinline__ void attend_tile(const T* __restrict__ kt, const T* __restrict__ vt,
+                                            size_t tstride, int n_valid, const float (&q)[G][8],
+                                            HeadState (&st)[G], int lane) {
+    constexpr int CPT = HD / 8, TPP = 64 / CPT, PASSES = kPT / TPP;
+    const int dc = lane % CPT, tsub = lane / CPT;
+    Chunk<T> kc[PASSES], vc[PASSES];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int tok = p * TPP + tsub;
+        const int tk = tok < n_valid ? tok : 0;   // clamp: keep the load in bounds, mask below
+        kc[p] = ld_chunk<T>(kt + (size_t)tk * tstride + dc * 8);
+        vc[p] = ld_chunk<T>(vt + (size_t)tk * tstride + dc * 8);
+    }
+    float s[G][PASSES];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        float kf[8];
+        unpack<T>(kc[p], kf);
+        const bool valid = (p * TPP + tsub) < n_valid;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float d = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) d += q[g][e] * kf[e];
+#pragma unroll
+            for (int o = 1; o < CPT; o <<= 1) d += __shfl_xor(d, o, kWave);
+            s[g][p] = valid ? d : -INFINITY;
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        float mx = s[g][0];
+#pragma unroll
+        for (int p = 1; p < PASSES; ++p) mx = fmaxf(mx, s[g][p]);
+#pragma unroll
+        for (int o = CPT; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, kWave));
+        const float m_new = fmaxf(st[g].m, mx);            // finite: token 0 of a tile is valid
+        const float alpha = __expf(st[g].m - m_new);       // exp(-inf) = 0 on the first tile
+        st[g].m = m_new;
+        st[g].l *= alpha;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st[g].acc[e] *= alpha;
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) s[g][p] = __expf(s[g][p] - m_new);
+    }
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        float vf[8];
+        unpack<T>(vc[p], vf);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            st[g].l += s[g][p];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st[g].acc[e] += s[g][p] * vf[e];
+        }
+    }
+}
+
+// Merge lanes (token sub-groups) of a wave, then the four waves through LDS.  On return,
+// threads with (wave 0 .. ) hold nothing special: results are in sm/sl/sacc for all G heads:
+//   sm[g], sl[g], sacc[g][HD] = block-wide max, sum, un-normalised accumulator.
+template <int HD, int G>
+__device__ __forceinline__ void block_merge(HeadState (&st)[G], int lane, int wave, float* s_m,
+                                            float* s_l, float* s_acc /*[4][G][HD]*/) {
+    constexpr int CPT = HD / 8;
+    const int dc = lane % CPT;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        // every lane of the wave already shares m; l and acc are per token sub-group
+        float l = st[g].l;
+#pragma unroll
+        for (int o = CPT; o < 64; o <<= 1) l += __shfl_xor(l, o, kWave);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float a = st[g].acc[e];
+#pragma unroll
+            for (int o = CPT; o < 64; o <<= 1) a += __shfl_xor(a, o, kWave);
+            if (lane < CPT) s_acc[(wave * G + g) * HD + dc * 8 + e] = a;
+        }
+        if (lane == 0) { s_m[wave * G + g] = st[g].m; s_l[wave * G + g] = l; }
+    }
+    __syncthreads();
+}
+
+template <typename T, int HD, int G>
+__global__ __launch_bounds__(256) void k_decode_attn(const T* __restrict__ q,
+                                                     const T* __restrict__ pool,
+                                                     const int* __restrict__ page_table,
+                                                     int pt_stride,
+                                                     const int* __restrict__ row_sample,
+                                                     const int* __restrict__ ctx_len,
+                                                     T* __restrict__ out, float* __restrict__ part_acc,
+                                                     float* __restrict__ part_ml, int layer,
+                                                     int nsplit, int n_layers, int Hkv) {
+    __shared__ float s_m[4 * G], s_l[4 * G];
+    __shared__ float s_acc[4 * G * HD];
+    const int r = blockIdx.x, kh = blockIdx.y, split = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int Hq = Hkv * G;
+    const int ctx = ctx_len[r];
+    const int n_pages = (ctx + kPT - 1) / kPT;
+    const int pps = (n_pages + nsplit - 1) / nsplit;
+    const int pb = split * pps, pe = min(n_pages, pb + pps);
+    const int* pt = page_table + (size_t)row_sample[r] * pt_stride;
+    constexpr int CPT = HD / 8;
+    const int dc = lane % CPT;
+    const float scale = rsqrtf((float)HD);
+
+    float qf[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        load8<T>(q + ((size_t)r * Hq + kh * G + g) * HD + dc * 8, qf[g]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[g][e] *= scale;
+    }
+    HeadState st[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        st[g].m = -INFINITY; st[g].l = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st[g].acc[e] = 0.f;
+    }
+    const size_t page_elems = (size_t)n_layers * 2 * Hkv * kPT * HD;
+    const size_t head_off = ((size_t)layer * 2 * Hkv + kh) * kPT * HD;
+    const size_t v_off = (size_t)Hkv * kPT * HD;
+    for (int pi = pb + wave; pi < pe; pi += 4) {
+        const int page = pt[pi];
+        const T* kt = pool + (size_t)page * page_elems + head_off;
+        const int n_valid = min(kPT, ctx - pi * kPT);
+        attend_tile<T, HD, G>(kt, kt + v_off, (size_t)HD, n_valid, qf, st, lane);
+    }
+    block_merge<HD, G>(st, lane, wave, s_m, s_l, s_acc);
+
+    for (int i = threadIdx.x; i < G * HD; i += 256) {
+        const int g = i / HD, e = i - g * HD;
+        float mt = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mt = fmaxf(mt, s_m[w * G + g]);
+        float lt = 0.f, at = 0.f;
+        if (mt > -INFINITY) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float f = __expf(s_m[w * G + g] - mt);
+                lt += s_l[w * G + g] * f;
+                at += s_acc[(w * G + g) * HD + e] * f;
+            }
+        }
+        const int h = kh * G + g;
+        if (nsplit == 1) {
+            out[((size_t)r * Hq + h) * HD + e] = from_f32<T>(at / lt);
+        } else {
+            const size_t slot = ((size_t)r * Hq + h) * nsplit + split;
+            part_acc[slot * HD + e] = at;
+            if (e == 0) { part_ml[slot * 2] = mt; part_ml[slot * 2 + 1] = lt; }
+        }
+    }
+}
+
+// LSE merge of the split partials: one block per (row, head), HD threads.
+template <typename T>
+__global__ void k_attn_merge(const float* __restrict__ part_acc, const float* __restrict__ part_ml,
+                             T* __restrict__ out, int nsplit, int HD) {
+    const size_t rh = blockIdx.x;
+    const int e = threadIdx.x;
+    float mt = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) mt = fmaxf(mt, part_ml[(rh * nsplit + s) * 2]);
+    float lt = 0.f, at = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+        const float m = part_ml[(rh * nsplit + s) * 2];
+        if (m == -INFINITY) continue;
+        const float f = __expf(m - mt);
+        lt += part_ml[(rh * nsplit + s) * 2 + 1] * f;
+        at += part_acc[(rh * nsplit + s) * HD + e] * f;
+    }
+    out[rh * HD + e] = from_f32<T>(at / lt);
+}
+
+template <typename T, int HD, int G>
+static hipError_t decode_launch(hipStream_t st, const void* q, const void* pool,
+                                const int* page_table, int pt_stride, const int* row_sample,
+                                const int* ctx_len, void* out, float* part_acc, float* part_ml,
+                                int rows, int layer, int nsplit, const Dims& dm) {
+    dim3 grid(rows, dm.n_kv_heads, nsplit);
+    k_decode_attn<T, HD, G><<<grid, 256, 0, st>>>((const T*)q, (const T*)pool, page_table, pt_stride,
+                                                  row_sample, ctx_len, (T*)out, part_acc, part_ml,
+                                                  layer, nsplit, dm.n_layers, dm.n_kv_heads);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || nsplit == 1) return e;
+    k_attn_merge<T><<<rows * dm.n_q_heads, HD, 0, st>>>(part_acc, part_ml, (T*)out, nsplit, HD);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_attn(hipStream_t st, int dtype, const void* q, const void* pool,
+                              const int* page_table, int pt_stride, const int* row_sample,
+                              const int* ctx_len, void* out, float* part_acc, float* part_ml,
+                              int rows, int layer, int nsplit, const Dims& dm) {
+    if (rows <= 0) return hipSuccess;
+    if (dm.page_tokens != kPT || nsplit < 1) return hipErrorInvalidValue;
+    const int G = dm.n_q_heads / dm.n_kv_heads, hd = dm.head_dim;
+#define RLHF_DEC(TT, HD_, G_)                                                                     \
+    return decode_launch<TT, HD_, G_>(st, q, pool, page_table, pt_stride, row_sample, ctx_len, out, \
+                                      part_acc, part_ml, rows, layer, nsplit, dm)
+    if (dtype == kBF16) {
+        if (hd == 128 && G == 1) RLHF_DEC(bf16_t, 128, 1);
+        if (hd == 128 && G == 8) RLHF_DEC(bf16_t, 128, 8);
+        if (hd == 64 && G == 1) RLHF_DEC(bf16_t, 64, 1);
+    } else {
+        if (hd == 128 && G == 1) RLHF_DEC(float, 128, 1);
+        if (hd == 64 && G == 1) RLHF_DEC(float, 64, 1);
+    }
+#undef RLHF_DEC
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------- prefill / scoring (v1)
+template <typename T, int HD, int G>
+__global__ __launch_bounds__(256) void k_prefill_attn(const T* __restrict__ q,
+                                                      const T* __restrict__ k,
+                                                      const T* __restrict__ v,
+                                                      const int* __restrict__ row_start,
+                                                      const int* __restrict__ row_pos,
+                                                      T* __restrict__ out, int Hkv) {
+    __shared__ float s_m[4 * G], s_l[4 * G];
+    __shared__ float s_acc[4 * G * HD];
+    const int r = blockIdx.x, kh = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int Hq = Hkv * G;
+    const int ctx = row_pos[r] + 1;
+    const size_t start = row_start[r];
+    constexpr int CPT = HD / 8;
+    const int dc = lane % CPT;
+    const float scale = rsqrtf((float)HD);
+    float qf[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        load8<T>(q + ((size_t)r * Hq + kh * G + g) * HD + dc * 8, qf[g]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[g][e] *= scale;
+    }
+    HeadState st[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        st[g].m = -INFINITY; st[g].l = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st[g].acc[e] = 0.f;
+    }
+    const size_t tstride = (size_t)Hkv * HD;
+    const int n_tiles = (ctx + kPT - 1) / kPT;
+    for (int ti = wave; ti < n_tiles; ti += 4) {
+        const size_t base = (start + (size_t)ti * kPT) * tstride + (size_t)kh * HD;
+        attend_tile<T, HD, G>(k + base, v + base, tstride, min(kPT, ctx - ti * kPT), qf, st, lane);
+    }
+    block_merge<HD, G>(st, lane, wave, s_m, s_l, s_acc);
+    for (int i = threadIdx.x; i < G * HD; i += 256) {
+        const int g = i / HD, e = i - g * HD;
+        float mt = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mt = fmaxf(mt, s_m[w * G + g]);
+        float lt = 0.f, at = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float f = __expf(s_m[w * G + g] - mt);
+            lt += s_l[w * G + g] * f;
+            at += s_acc[(w * G + g) * HD + e] * f;
+        }
+        out[((size_t)r * Hq + kh * G + g) * HD + e] = from_f32<T>(at / lt);
+    }
+}
+
+hipError_t launch_prefill_attn(hipStream_t st, int dtype, const void* q, const void* k,
+                               const void* v, const int* row_start, const int* row_pos, void* out,
+                               int rows, const Dims& dm) {
+    if (rows <= 0) return hipSuccess;
+    const int G = dm.n_q_heads / dm.n_kv_heads, hd = dm.head_dim;
+    dim3 grid(rows, dm.n_kv_heads);
+#define RLHF_PRE(TT, HD_, G_)                                                                      \
+    do {                                                                                           \
+        k_prefill_attn<TT, HD_, G_><<<grid, 256, 0, st>>>((const TT*)q, (const TT*)k, (const TT*)v, \
+                                                          row_start, row_pos, (TT*)out,            \
+                                                          dm.n_kv_heads);                          \
+        return hipGetLastError();                                                                  \
+    } while (0)
+    if (dtype == kBF16) {
+        if (hd == 128 && G == 1) RLHF_PRE(bf16_t, 128, 1);
+        if (hd == 128 && G == 8) RLHF_PRE(bf16_t, 128, 8);
+        if (hd == 64 && G == 1) RLHF_PRE(bf16_t, 64, 1);
+    } else {
+        if (hd == 128 && G == 1) RLHF_PRE(float, 128, 1);
+        if (hd == 64 && G == 1) RLHF_PRE(float, 64, 1);
+    }
+#undef RLHF_PRE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace rlhf

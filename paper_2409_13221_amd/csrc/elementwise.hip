@@ -1,0 +1,368 @@
+// Row-wise and elementwise kernels of the decoder forward: embedding gather, RMSNorm (fused
+// with the residual add of split-K partials), rotary + KV-cache append, SwiGLU, the greedy
+// pick / log-softmax gather over the vocabulary, and the value / reward head.
+// All are HBM-bound; each reads its input once and writes its output once.
+#include "common.cuh"
+#include "kernels.h"
+
+namespace rlhf {
+
+size_t pool_page_elems(const Dims& dm) {
+    return (size_t)dm.n_layers * 2 * dm.n_kv_heads * dm.page_tokens * dm.head_dim;
+}
+
+// ------------------------------------------------------------------------------- embedding
+template <typename T>
+__global__ __launch_bounds__(256) void k_embed(const int* __restrict__ tokens,
+                                               const int* __restrict__ tok_idx,
+                                               const T* __restrict__ table, float* __restrict__ h,
+                                               int d, int vocab) {
+    const int r = blockIdx.x;
+    int tok = tokens[tok_idx[r]];
+    tok = min(max(tok, 0), vocab - 1);
+    const T* src = table + (size_t)tok * d;
+    float* dst = h + (size_t)r * d;
+    for (int i = threadIdx.x * 8; i < d; i += 256 * 8) {
+        float v[8];
+        load8<T>(src + i, v);
+        store8<float>(dst + i, v);
+    }
+}
+
+hipError_t launch_embed(hipStream_t st, int dtype, const int* tokens, const int* tok_idx,
+                        const void* table, float* h, int rows, int d, int vocab) {
+    if (rows <= 0) return hipSuccess;
+    if (dtype == kBF16)
+        k_embed<bf16_t><<<rows, 256, 0, st>>>(tokens, tok_idx, (const bf16_t*)table, h, d, vocab);
+    else
+        k_embed<float><<<rows, 256, 0, st>>>(tokens, tok_idx, (const float*)table, h, d, vocab);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------- RMSNorm
+// One block per output row.  d <= 256 * 8 * kRmsMaxIter.
+constexpr int kRmsMaxIter = 4;
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_rmsnorm(float* __restrict__ h, const float* __restrict__ part,
+                                                 int nsplit, size_t sstride,
+                                                 const int* __restrict__ row_idx,
+                                                 const float* __restrict__ g, T* __restrict__ xn,
+                                                 int d, float eps) {
+    __shared__ float red[16];
+    const int r = blockIdx.x;
+    const int src = row_idx ? row_idx[r] : r;
+    float* hrow = h + (size_t)src * d;
+    float v[kRmsMaxIter][8];
+    float ss = 0.f;
+#pragma unroll
+    for (int it = 0; it < kRmsMaxIter; ++it) {
+        const int i = (it * 256 + threadIdx.x) * 8;
+        if (i < d) {
+            load8<float>(hrow + i, v[it]);
+            for (int s = 0; s < nsplit; ++s) {
+                float p[8];
+                load8<float>(part + s * sstride + (size_t)src * d + i, p);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[it][e] += p[e];
+            }
+            if (nsplit > 0 && !row_idx) store8<float>(hrow + i, v[it]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += v[it][e] * v[it][e];
+        }
+    }
+    const float tot = block_sum(ss, red);
+    const float inv = rsqrtf(tot / (float)d + eps);
+#pragma unroll
+    for (int it = 0; it < kRmsMaxIter; ++it) {
+        const int i = (it * 256 + threadIdx.x) * 8;
+        if (i < d) {
+            float gg[8], o[8];
+            load8<float>(g + i, gg);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = v[it][e] * inv * gg[e];
+            store8<T>(xn + (size_t)r * d + i, o);
+        }
+    }
+}
+
+hipError_t launch_rmsnorm(hipStream_t st, int dtype, float* h, const float* part, int nsplit,
+                          size_t sstride, const int* row_idx, const float* g, void* xn, int rows,
+                          int d, float eps) {
+    if (rows <= 0) return hipSuccess;
+    if (d > 256 * 8 * kRmsMaxIter || d % 8) return hipErrorInvalidValue;
+    if (dtype == kBF16)
+        k_rmsnorm<bf16_t><<<rows, 256, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (bf16_t*)xn, d, eps);
+    else
+        k_rmsnorm<float><<<rows, 256, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (float*)xn, d, eps);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- rotary + KV-cache append
+// rope_table: [max_pos][hd/2][2] = (cos, sin) of pos * base^(-2k/hd), computed in double on
+// the host.  Pair (k, k + hd/2) is rotated.
+template <typename T>
+__global__ __launch_bounds__(256) void k_rope_kv(const float* __restrict__ qkv, int nsplit,
+                                                 size_t sstride, const int* __restrict__ pos,
+                                                 const int* __restrict__ kv_dst,
+                                                 const float* __restrict__ rope_table,
+                                                 T* __restrict__ q_out, T* __restrict__ k_out,
+                                                 T* __restrict__ v_out, T* __restrict__ pool,
+                                                 int layer, Dims dm) {
+    const int r = blockIdx.x;
+    const int hd = dm.head_dim, half = hd >> 1;
+    const int Hq = dm.n_q_heads, Hkv = dm.n_kv_heads;
+    const int qkv_w = (Hq + 2 * Hkv) * hd;
+    const float* x = qkv + (size_t)r * qkv_w;
+    const float* tab = rope_table + (size_t)pos[r] * hd;  // hd/2 pairs of (cos, sin)
+    const int slot = (pool && kv_dst) ? kv_dst[r] : -1;
+    T* pk = nullptr;
+    T* pv = nullptr;
+    if (slot >= 0) {
+        const int pt = dm.page_tokens;
+        const size_t page = slot / pt, off = slot % pt;
+        const size_t layer_base = (page * dm.n_layers + layer) * 2 * (size_t)Hkv * pt * hd;
+        pk = pool + layer_base + off * hd;                        // + kh * pt * hd + e
+        pv = pool + layer_base + (size_t)Hkv * pt * hd + off * hd;
+    }
+    const int n_rot = (Hq + Hkv) * half;
+    for (int i = threadIdx.x; i < n_rot; i += 256) {
+        const int hh = i / half, k = i - hh * half;
+        const int col = hh * hd + k;
+        float a = x[col], b = x[col + half];
+        for (int s = 1; s < nsplit; ++s) {
+            a += x[s * sstride + col];
+            b += x[s * sstride + col + half];
+        }
+        const float c = tab[2 * k], sn = tab[2 * k + 1];
+        const T ra = from_f32<T>(a * c - b * sn), rb = from_f32<T>(a * sn + b * c);
+        if (hh < Hq) {
+            q_out[(size_t)r * Hq * hd + col] = ra;
+            q_out[(size_t)r * Hq * hd + col + half] = rb;
+        } else {
+            const int kh = hh - Hq;
+            if (k_out) {
+                k_out[(size_t)r * Hkv * hd + kh * hd + k] = ra;
+                k_out[(size_t)r * Hkv * hd + kh * hd + k + half] = rb;
+            }
+            if (pk) {
+                pk[(size_t)kh * dm.page_tokens * hd + k] = ra;
+                pk[(size_t)kh * dm.page_tokens * hd + k + half] = rb;
+            }
+        }
+    }
+    const int vbase = (Hq + Hkv) * hd;
+    for (int i = threadIdx.x; i < Hkv * hd; i += 256) {
+        float a = x[vbase + i];
+        for (int s = 1; s < nsplit; ++s) a += x[s * sstride + vbase + i];
+        const T t = from_f32<T>(a);
+        if (v_out) v_out[(size_t)r * Hkv * hd + i] = t;
+        if (pv) {
+            const int kh = i / hd, e = i - kh * hd;
+            pv[(size_t)kh * dm.page_tokens * hd + e] = t;
+        }
+    }
+}
+
+hipError_t launch_rope_kv(hipStream_t st, int dtype, const float* qkv, int nsplit, size_t sstride,
+                          const int* pos, const int* kv_dst, const float* rope_table, void* q_out,
+                          void* k_out, void* v_out, void* pool, int layer, int rows,
+                          const Dims& dm) {
+    if (rows <= 0) return hipSuccess;
+    if (dtype == kBF16)
+        k_rope_kv<bf16_t><<<rows, 256, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
+                                                (bf16_t*)q_out, (bf16_t*)k_out, (bf16_t*)v_out,
+                                                (bf16_t*)pool, layer, dm);
+    else
+        k_rope_kv<float><<<rows, 256, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
+                                               (float*)q_out, (float*)k_out, (float*)v_out,
+                                               (float*)pool, layer, dm);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------- SwiGLU
+// gu rows are [gate (ffn) | up (ffn)]; act = silu(gate) * up.
+template <typename T>
+__global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ gu, int nsplit,
+                                                size_t sstride, T* __restrict__ act, int rows,
+                                                int ffn) {
+    const size_t per_row = (size_t)(ffn >> 3);
+    const size_t total = (size_t)rows * per_row;
+    for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < total;
+         idx += (size_t)gridDim.x * 256) {
+        const size_t r = idx / per_row;
+        const int c = (int)(idx - r * per_row) * 8;
+        const float* row = gu + r * (size_t)(2 * ffn);
+        float g[8], u[8], o[8];
+        load8<float>(row + c, g);
+        load8<float>(row + ffn + c, u);
+        for (int s = 1; s < nsplit; ++s) {
+            float pg[8], pu[8];
+            load8<float>(row + s * sstride + c, pg);
+            load8<float>(row + s * sstride + ffn + c, pu);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { g[e] += pg[e]; u[e] += pu[e]; }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = g[e] / (1.f + __expf(-g[e])) * u[e];
+        store8<T>(act + r * (size_t)ffn + c, o);
+    }
+}
+
+hipError_t launch_swiglu(hipStream_t st, int dtype, const float* gu, int nsplit, size_t sstride,
+                         void* act, int rows, int ffn) {
+    if (rows <= 0) return hipSuccess;
+    if (ffn % 8) return hipErrorInvalidValue;
+    const size_t total = (size_t)rows * (ffn / 8);
+    const int grid = (int)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
+    if (dtype == kBF16)
+        k_swiglu<bf16_t><<<grid, 256, 0, st>>>(gu, nsplit, sstride, (bf16_t*)act, rows, ffn);
+    else
+        k_swiglu<float><<<grid, 256, 0, st>>>(gu, nsplit, sstride, (float*)act, rows, ffn);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------- greedy pick / log-softmax gather
+__device__ __forceinline__ float logit_at(const float* row, int nsplit, size_t sstride, int i) {
+    float z = row[i];
+    for (int s = 1; s < nsplit; ++s) z += row[s * sstride + i];
+    return z;
+}
+
+// Block-wide (max value, lowest index attaining it) and sum of exp(z - max).
+__device__ __forceinline__ void row_softmax_stats(const float* row, int nsplit, size_t sstride,
+                                                  int vocab, float& out_max, int& out_arg,
+                                                  float& out_sum) {
+    __shared__ float s_val[4];
+    __shared__ int s_idx[4];
+    __shared__ float s_red[16];
+    float best = -INFINITY;
+    int arg = 0x7FFFFFFF;
+    for (int i = threadIdx.x; i < vocab; i += 256) {
+        const float z = logit_at(row, nsplit, sstride, i);
+        if (z > best) { best = z; arg = i; }   // ascending i: the first maximum is kept
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(best, o, kWave);
+        const int oi = __shfl_xor(arg, o, kWave);
+        if (ov > best || (ov == best && oi < arg)) { best = ov; arg = oi; }
+    }
+    if ((threadIdx.x & 63) == 0) { s_val[threadIdx.x >> 6] = best; s_idx[threadIdx.x >> 6] = arg; }
+    __syncthreads();
+    best = s_val[0]; arg = s_idx[0];
+    for (int w = 1; w < 4; ++w)
+        if (s_val[w] > best || (s_val[w] == best && s_idx[w] < arg)) { best = s_val[w]; arg = s_idx[w]; }
+    float se = 0.f;
+    for (int i = threadIdx.x; i < vocab; i += 256)
+        se += expf(logit_at(row, nsplit, sstride, i) - best);
+    out_sum = block_sum(se, s_red);
+    out_max = best;
+    out_arg = arg;
+}
+
+__global__ __launch_bounds__(256) void k_pick(const float* __restrict__ logits, int nsplit,
+                                              size_t sstride, int vocab,
+                                              const int* __restrict__ forced,
+                                              int* __restrict__ tokens,
+                                              const int* __restrict__ tok_dst,
+                                              float* __restrict__ lp, const int* __restrict__ lp_dst,
+                                              int* __restrict__ picked) {
+    const int r = blockIdx.x;
+    const float* row = logits + (size_t)r * vocab;
+    float mx, se;
+    int arg;
+    row_softmax_stats(row, nsplit, sstride, vocab, mx, arg, se);
+    if (threadIdx.x == 0) {
+        int y = arg;
+        const int f = forced ? forced[r] : -1;
+        if (f >= 0 && f < vocab) y = f;
+        const float z = logit_at(row, nsplit, sstride, y);
+        tokens[tok_dst[r]] = y;
+        lp[lp_dst[r]] = z - mx - logf(se);
+        if (picked) picked[r] = y;
+    }
+}
+
+hipError_t launch_pick(hipStream_t st, const float* logits, int nsplit, size_t sstride, int rows,
+                       int vocab, const int* forced, int* tokens, const int* tok_dst, float* lp,
+                       const int* lp_dst, int* picked) {
+    if (rows <= 0) return hipSuccess;
+    k_pick<<<rows, 256, 0, st>>>(logits, nsplit, sstride, vocab, forced, tokens, tok_dst, lp, lp_dst,
+                                 picked);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void k_gather_lp(const float* __restrict__ logits, int nsplit,
+                                                   size_t sstride, int vocab,
+                                                   const int* __restrict__ tokens,
+                                                   const int* __restrict__ target_idx,
+                                                   float* __restrict__ out,
+                                                   const int* __restrict__ out_dst) {
+    const int r = blockIdx.x;
+    const float* row = logits + (size_t)r * vocab;
+    float mx, se;
+    int arg;
+    row_softmax_stats(row, nsplit, sstride, vocab, mx, arg, se);
+    if (threadIdx.x == 0) {
+        int y = tokens[target_idx[r]];
+        y = min(max(y, 0), vocab - 1);
+        out[out_dst[r]] = logit_at(row, nsplit, sstride, y) - mx - logf(se);
+    }
+}
+
+hipError_t launch_gather_lp(hipStream_t st, const float* logits, int nsplit, size_t sstride,
+                            int rows, int vocab, const int* tokens, const int* target_idx,
+                            float* out, const int* out_dst) {
+    if (rows <= 0) return hipSuccess;
+    k_gather_lp<<<rows, 256, 0, st>>>(logits, nsplit, sstride, vocab, tokens, target_idx, out,
+                                      out_dst);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------- value / reward head
+// One wave per row: out[out_dst[r]] = <xn[r], w>.
+template <typename T>
+__global__ __launch_bounds__(256) void k_head_dot(const T* __restrict__ xn, const T* __restrict__ w,
+                                                  int rows, int d, float* __restrict__ out,
+                                                  const int* __restrict__ out_dst) {
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int lane = threadIdx.x & 63;
+    float acc = 0.f;
+    for (int i = lane * 8; i < d; i += 64 * 8) {
+        float a[8], b[8];
+        load8<T>(xn + (size_t)r * d + i, a);
+        load8<T>(w + i, b);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc += a[e] * b[e];
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) out[out_dst[r]] = acc;
+}
+
+hipError_t launch_head_dot(hipStream_t st, int dtype, const void* xn, const void* w, int rows,
+                           int d, float* out, const int* out_dst) {
+    if (rows <= 0) return hipSuccess;
+    const int grid = (rows + 3) / 4;
+    if (dtype == kBF16)
+        k_head_dot<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)xn, (const bf16_t*)w, rows, d, out, out_dst);
+    else
+        k_head_dot<float><<<grid, 256, 0, st>>>((const float*)xn, (const float*)w, rows, d, out, out_dst);
+    return hipGetLastError();
+}
+
+// -------------------------------------------------------------------------- small scatter
+__global__ void k_scatter_int(int* __restrict__ dst, const int* __restrict__ idx,
+                              const int* __restrict__ val, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[idx[i]] = val[i];
+}
+
+hipError_t launch_scatter_int(hipStream_t st, int* dst, const int* idx, const int* val, int n) {
+    if (n <= 0) return hipSuccess;
+    k_scatter_int<<<(n + 255) / 256, 256, 0, st>>>(dst, idx, val, n);
+    return hipGetLastError();
+}
+
+}  // namespace rlhf

@@ -1,0 +1,1132 @@
+// Host side of the fused generation + inference stage: the C ABI of include/rlhf.h, the
+// continuous-batching bookkeeping (admission against the KV budget, page tables, retirement,
+// scoring-batch formation) and the launch sequences of the decode step and of the prefill /
+// scoring forward.  All arithmetic of the method runs in the HIP kernels declared in
+// kernels.h; this file only decides what to launch, on which stream, over which rows.
+#include "../../include/rlhf.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace rlhf;
+
+namespace {
+
+thread_local char g_create_error[512] = "";
+
+struct RoleWeights {
+    bool bound = false;
+    rlhf_weights w{};
+};
+
+// Pinned host staging + one device arena for small per-pass integer metadata.  The host runs
+// ahead of the device, so host slots form a ring guarded by events; the device arena is
+// rewritten by a stream-ordered copy, after the kernels of the previous pass on that stream.
+struct MetaRing {
+    static constexpr int kSlots = 8;
+    int* host[kSlots] = {};
+    hipEvent_t ev[kSlots] = {};
+    bool used[kSlots] = {};
+    int* dev = nullptr;
+    size_t cap = 0;
+    int next = 0;
+
+    hipError_t init(size_t cap_ints) {
+        cap = cap_ints;
+        hipError_t e = hipMalloc((void**)&dev, cap * sizeof(int));
+        if (e != hipSuccess) return e;
+        for (int i = 0; i < kSlots; ++i) {
+            e = hipHostMalloc((void**)&host[i], cap * sizeof(int), hipHostMallocDefault);
+            if (e != hipSuccess) return e;
+            e = hipEventCreateWithFlags(&ev[i], hipEventDisableTiming);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    void destroy() {
+        for (int i = 0; i < kSlots; ++i) {
+            if (host[i]) (void)hipHostFree(host[i]);
+            if (ev[i]) (void)hipEventDestroy(ev[i]);
+        }
+        if (dev) (void)hipFree(dev);
+    }
+    hipError_t begin(int** out) {
+        if (used[next]) {
+            hipError_t e = hipEventSynchronize(ev[next]);
+            if (e != hipSuccess) return e;
+        }
+        *out = host[next];
+        return hipSuccess;
+    }
+    hipError_t commit(hipStream_t st, size_t n_ints) {
+        hipError_t e = hipMemcpyAsync(dev, host[next], n_ints * sizeof(int), hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) return e;
+        e = hipEventRecord(ev[next], st);
+        used[next] = true;
+        next = (next + 1) % kSlots;
+        return e;
+    }
+};
+
+struct Workspace {
+    int rows_cap = 0;
+    float* h = nullptr;       // [rows, d] residual stream (float)
+    void* xn = nullptr;       // [rows, d] normed activations (storage type)
+    float* part = nullptr;    // split-K partial outputs of the GEMM in flight
+    size_t part_cap = 0;      // floats
+    void* q = nullptr;        // [rows, Hq*hd]
+    void* k = nullptr;        // [rows, Hkv*hd] (batch passes)
+    void* v = nullptr;
+    void* attn = nullptr;     // [rows, Hq*hd]
+    void* act = nullptr;      // [rows, ffn]
+    void* xsel = nullptr;     // [rows, d] final-norm rows selected for the head
+    float* logits = nullptr;  // [logit_rows, vocab] (batch passes; decode uses `part`)
+    int logit_rows = 0;
+    float* attn_acc = nullptr;  // decode split-KV partials
+    float* attn_ml = nullptr;
+    size_t attn_slots = 0;
+    std::vector<void*> owned;
+};
+
+struct Sample {
+    int P = 0, max_new = 0, target = 0, reserve = 0;
+    int ctx = 0, gen_len = 0, admit_step = -1;
+    bool has_forced_len = false, finished = false, retired = false;
+    std::vector<int> pages;
+};
+
+}  // namespace
+
+struct rlhf_ctx {
+    rlhf_model_cfg mc{};
+    rlhf_engine_cfg ec{};
+    Dims dm{};
+    int dtype = 0, esz = 2;
+    int max_pages = 0, pool_pages = 0;
+    char err[512] = "";
+
+    hipStream_t sd = nullptr, ss = nullptr;
+    bool own_sd = false, own_ss = false;
+    hipEvent_t ev_dep = nullptr;                       // decode -> score dependency
+    hipEvent_t ev_d0 = nullptr, ev_d1 = nullptr, ev_s0 = nullptr, ev_s1 = nullptr;
+    std::vector<hipEvent_t> step_events;
+
+    RoleWeights roles[4];
+
+    void* pool = nullptr;
+    int* d_page_table = nullptr;   // [max_samples, max_pages]
+    int* d_tokens = nullptr;       // [max_samples, max_ctx]   prompt + response
+    float* d_lp_actor = nullptr;   // [max_samples, max_ctx]   indexed by output index j-1
+    float* d_lp_rescored = nullptr;
+    float* d_lp_ref = nullptr;
+    float* d_values = nullptr;
+    float* d_reward = nullptr;     // [max_samples]
+    float* d_rope = nullptr;       // [max_ctx, hd/2, 2]
+    int* d_picked = nullptr;       // [max_active] tokens of the last pick (stop_on_eos)
+    int* h_picked = nullptr;       // pinned
+
+    Workspace ws_dec, ws_pre, ws_score;
+    MetaRing meta_dec, meta_pre, meta_score;
+
+    // ---- stage state (host integers)
+    int N = 0;
+    std::vector<Sample> smp;
+    std::vector<int> h_prompt;            // packed prompts
+    std::vector<int64_t> h_prompt_off;
+    std::vector<int> h_forced;            // [N * max_ctx] imposed token per output index, -1 = free
+    std::deque<int> waiting;
+    std::vector<int> active;
+    std::vector<int> free_list;
+    int reserved = 0;
+    std::vector<int> retired;
+    size_t n_scored = 0;
+    std::vector<int> batch_offsets{0};
+    std::vector<int> batch_step;
+    int step = 0;
+    bool score_used = false;
+    int64_t acc_weight_bytes = 0, acc_kv_bytes = 0, acc_prefill_tokens = 0;
+
+    int fail(int code, const char* fmt, ...) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(err, sizeof err, fmt, ap);
+        va_end(ap);
+        return code;
+    }
+};
+
+#define HIPCK(ctx, call)                                                                       \
+    do {                                                                                       \
+        hipError_t e_ = (call);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return (ctx)->fail(RLHF_EDEVICE, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), \
+                               __FILE__, __LINE__);                                            \
+    } while (0)
+
+namespace {
+
+template <typename T>
+hipError_t dev_alloc(Workspace* ws, T** p, size_t n_bytes) {
+    void* q = nullptr;
+    hipError_t e = hipMalloc(&q, n_bytes ? n_bytes : 256);
+    if (e == hipSuccess) {
+        *p = (T*)q;
+        if (ws) ws->owned.push_back(q);
+    }
+    return e;
+}
+
+int alloc_workspace(rlhf_ctx* c, Workspace& ws, int rows, bool decode) {
+    const rlhf_model_cfg& m = c->mc;
+    const size_t d = m.d_model, qd = (size_t)m.n_q_heads * m.head_dim, kvd = (size_t)m.n_kv_heads * m.head_dim;
+    const size_t qkv_w = qd + 2 * kvd, f = m.ffn, V = m.vocab, es = c->esz;
+    ws.rows_cap = rows;
+    const size_t widest = std::max({qkv_w, 2 * f, d});
+    if (decode) {
+        // room for split-K partials of few-row GEMMs and for [rows, vocab] logits
+        ws.part_cap = std::max((size_t)rows * std::max(widest, V) * 2, (size_t)16 * 16 * std::max(widest, V));
+        ws.attn_slots = std::max((size_t)rows * m.n_q_heads, (size_t)16384);
+    } else {
+        ws.part_cap = (size_t)rows * widest;
+        ws.logit_rows = std::min(rows, 2048);
+    }
+    HIPCK(c, dev_alloc(&ws, &ws.h, rows * d * 4));
+    HIPCK(c, dev_alloc(&ws, (char**)&ws.xn, rows * d * es));
+    HIPCK(c, dev_alloc(&ws, &ws.part, ws.part_cap * 4));
+    HIPCK(c, dev_alloc(&ws, (char**)&ws.q, rows * qd * es));
+    HIPCK(c, dev_alloc(&ws, (char**)&ws.attn, rows * qd * es));
+    HIPCK(c, dev_alloc(&ws, (char**)&ws.act, rows * f * es));
+    HIPCK(c, dev_alloc(&ws, (char**)&ws.xsel, rows * d * es));
+    if (decode) {
+        HIPCK(c, dev_alloc(&ws, &ws.attn_acc, ws.attn_slots * m.head_dim * 4));
+        HIPCK(c, dev_alloc(&ws, &ws.attn_ml, ws.attn_slots * 2 * 4));
+    } else {
+        HIPCK(c, dev_alloc(&ws, (char**)&ws.k, rows * kvd * es));
+        HIPCK(c, dev_alloc(&ws, (char**)&ws.v, rows * kvd * es));
+        HIPCK(c, dev_alloc(&ws, &ws.logits, (size_t)ws.logit_rows * V * 4));
+    }
+    return RLHF_OK;
+}
+
+void free_workspace(Workspace& ws) {
+    for (void* p : ws.owned) (void)hipFree(p);
+    ws.owned.clear();
+}
+
+const char* layer_ptr(const void* base, int layer, size_t rows, size_t cols, int esz) {
+    return (const char*)base + (size_t)layer * rows * cols * esz;
+}
+
+int nsplit_for(const rlhf_ctx* c, const Workspace& ws, int M, int N, int K) {
+    const size_t per = (size_t)M * N;
+    int cap = (int)std::min<size_t>(16, per ? ws.part_cap / per : 1);
+    if (cap < 1) cap = 1;
+    return gemm_choose_nsplit(c->dtype, M, N, K, cap);
+}
+
+enum AttnMode { kAttnDecode, kAttnBatch };
+
+struct PassMeta {         // device pointers into a MetaRing arena
+    const int* tok_idx = nullptr;
+    const int* pos = nullptr;
+    const int* kv_dst = nullptr;       // NULL: no pool writes
+    const int* row_sample = nullptr;   // decode
+    const int* ctx_len = nullptr;      // decode
+    const int* row_start = nullptr;    // batch
+};
+
+// Embedding and all decoder layers over `rows` rows.  On return ws.h holds the residual
+// stream except for the last down-projection, whose split-K partials are still in ws.part:
+// (*pend_ns, *pend_stride) describe them for the final norm.
+int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weights& w, int rows,
+                   const PassMeta& pm, AttnMode mode, int attn_nsplit, int* pend_ns,
+                   size_t* pend_stride) {
+    const rlhf_model_cfg& m = c->mc;
+    const int d = m.d_model, qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
+    const int qkv_w = qd + 2 * kvd, f = m.ffn, es = c->esz, dt = c->dtype;
+    HIPCK(c, launch_embed(st, dt, c->d_tokens, pm.tok_idx, w.embed, ws.h, rows, d, m.vocab));
+    int pns = 0;
+    size_t pstride = 0;
+    for (int l = 0; l < m.n_layers; ++l) {
+        HIPCK(c, launch_rmsnorm(st, dt, ws.h, ws.part, pns, pstride, nullptr, w.g_attn + (size_t)l * d,
+                                ws.xn, rows, d, m.rms_eps));
+        int ns = nsplit_for(c, ws, rows, qkv_w, d);
+        HIPCK(c, launch_gemm(st, dt, ws.xn, layer_ptr(w.wqkv, l, qkv_w, d, es), ws.part, rows, qkv_w, d, ns));
+        HIPCK(c, launch_rope_kv(st, dt, ws.part, ns, (size_t)rows * qkv_w, pm.pos, pm.kv_dst, c->d_rope,
+                                ws.q, mode == kAttnBatch ? ws.k : nullptr,
+                                mode == kAttnBatch ? ws.v : nullptr, pm.kv_dst ? c->pool : nullptr, l,
+                                rows, c->dm));
+        if (mode == kAttnDecode) {
+            HIPCK(c, launch_decode_attn(st, dt, ws.q, c->pool, c->d_page_table, c->max_pages,
+                                        pm.row_sample, pm.ctx_len, ws.attn, ws.attn_acc, ws.attn_ml,
+                                        rows, l, attn_nsplit, c->dm));
+        } else {
+            HIPCK(c, launch_prefill_attn(st, dt, ws.q, ws.k, ws.v, pm.row_start, pm.pos, ws.attn, rows,
+                                         c->dm));
+        }
+        ns = nsplit_for(c, ws, rows, d, qd);
+        HIPCK(c, launch_gemm(st, dt, ws.attn, layer_ptr(w.wo, l, d, qd, es), ws.part, rows, d, qd, ns));
+        HIPCK(c, launch_rmsnorm(st, dt, ws.h, ws.part, ns, (size_t)rows * d, nullptr,
+                                w.g_mlp + (size_t)l * d, ws.xn, rows, d, m.rms_eps));
+        ns = nsplit_for(c, ws, rows, 2 * f, d);
+        HIPCK(c, launch_gemm(st, dt, ws.xn, layer_ptr(w.w_gate_up, l, 2 * (size_t)f, d, es), ws.part, rows,
+                             2 * f, d, ns));
+        HIPCK(c, launch_swiglu(st, dt, ws.part, ns, (size_t)rows * 2 * f, ws.act, rows, f));
+        pns = nsplit_for(c, ws, rows, d, f);
+        pstride = (size_t)rows * d;
+        HIPCK(c, launch_gemm(st, dt, ws.act, layer_ptr(w.w_down, l, d, f, es), ws.part, rows, d, f, pns));
+    }
+    *pend_ns = pns;
+    *pend_stride = pstride;
+    return RLHF_OK;
+}
+
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+}  // namespace
+
+// =========================================================================== create/destroy
+
+extern "C" const char* rlhf_last_error(const rlhf_ctx* ctx) { return ctx ? ctx->err : g_create_error; }
+
+extern "C" void rlhf_destroy(rlhf_ctx* c) {
+    if (!c) return;
+    if (c->sd) (void)hipStreamSynchronize(c->sd);
+    if (c->ss) (void)hipStreamSynchronize(c->ss);
+    free_workspace(c->ws_dec);
+    free_workspace(c->ws_pre);
+    free_workspace(c->ws_score);
+    c->meta_dec.destroy();
+    c->meta_pre.destroy();
+    c->meta_score.destroy();
+    void* bufs[] = {c->pool, c->d_page_table, c->d_tokens, c->d_lp_actor, c->d_lp_rescored, c->d_lp_ref,
+                    c->d_values, c->d_reward, c->d_rope, c->d_picked};
+    for (void* p : bufs)
+        if (p) (void)hipFree(p);
+    if (c->h_picked) (void)hipHostFree(c->h_picked);
+    hipEvent_t evs[] = {c->ev_dep, c->ev_d0, c->ev_d1, c->ev_s0, c->ev_s1};
+    for (hipEvent_t e : evs)
+        if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->step_events) (void)hipEventDestroy(e);
+    if (c->own_sd && c->sd) (void)hipStreamDestroy(c->sd);
+    if (c->own_ss && c->ss) (void)hipStreamDestroy(c->ss);
+    delete c;
+}
+
+static int create_impl(rlhf_ctx* c) {
+    const rlhf_model_cfg& m = c->mc;
+    const rlhf_engine_cfg& e = c->ec;
+    if (m.n_layers < 0 || m.d_model <= 0 || m.n_q_heads <= 0 || m.n_kv_heads <= 0 || m.ffn <= 0 || m.vocab <= 1)
+        return c->fail(RLHF_EINVAL, "model dimensions must be positive");
+    if (m.dtype != RLHF_FP32 && m.dtype != RLHF_BF16) return c->fail(RLHF_EINVAL, "dtype must be FP32 or BF16");
+    if (m.d_model % 8 || m.ffn % 8 || m.d_model > 8192)
+        return c->fail(RLHF_EINVAL, "d_model and ffn must be multiples of 8, d_model <= 8192");
+    if (m.n_q_heads % m.n_kv_heads) return c->fail(RLHF_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
+    const int G = m.n_q_heads / m.n_kv_heads;
+    const bool attn_ok = (m.head_dim == 128 && (G == 1 || (G == 8 && m.dtype == RLHF_BF16))) ||
+                         (m.head_dim == 64 && G == 1);
+    if (!attn_ok)
+        return c->fail(RLHF_EINVAL, "unsupported attention shape: head_dim %d, group %d (have 128x{1,8}, 64x1)",
+                       m.head_dim, G);
+    if (e.page_tokens != 16) return c->fail(RLHF_EINVAL, "page_tokens must be 16");
+    if (e.max_samples <= 0 || e.max_ctx <= 1 || e.max_active <= 0 || e.max_batch_tokens < e.max_ctx)
+        return c->fail(RLHF_EINVAL, "engine limits: need max_samples, max_active > 0, max_batch_tokens >= max_ctx > 1");
+    if (e.eos_id < 0 || e.eos_id >= m.vocab) return c->fail(RLHF_EINVAL, "eos_id out of range");
+    if (!(m.rms_eps >= 0.f) || !(m.rope_base > 1.f)) return c->fail(RLHF_EINVAL, "rms_eps / rope_base");
+
+    c->dtype = m.dtype == RLHF_BF16 ? kBF16 : kF32;
+    c->esz = m.dtype == RLHF_BF16 ? 2 : 4;
+    c->dm = Dims{m.n_layers, m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn, m.vocab, e.page_tokens};
+    c->max_pages = ceil_div(e.max_ctx, e.page_tokens);
+    const size_t page_bytes = std::max<size_t>(pool_page_elems(c->dm) * c->esz, 1);
+    const int64_t pages = e.kv_pool_bytes / (int64_t)page_bytes;
+    if (pages < 1 || pages > (int64_t)1 << 27)
+        return c->fail(RLHF_ENOMEM, "kv_pool_bytes %lld holds %lld pages of %zu bytes",
+                       (long long)e.kv_pool_bytes, (long long)pages, page_bytes);
+    c->pool_pages = (int)pages;
+
+    if (e.decode_stream) c->sd = (hipStream_t)e.decode_stream;
+    else { HIPCK(c, hipStreamCreateWithFlags(&c->sd, hipStreamNonBlocking)); c->own_sd = true; }
+    if (e.score_stream) c->ss = (hipStream_t)e.score_stream;
+    else { HIPCK(c, hipStreamCreateWithFlags(&c->ss, hipStreamNonBlocking)); c->own_ss = true; }
+    HIPCK(c, hipEventCreateWithFlags(&c->ev_dep, hipEventDisableTiming));
+    HIPCK(c, hipEventCreate(&c->ev_d0));
+    HIPCK(c, hipEventCreate(&c->ev_d1));
+    HIPCK(c, hipEventCreate(&c->ev_s0));
+    HIPCK(c, hipEventCreate(&c->ev_s1));
+
+    const size_t ns = e.max_samples, mc = e.max_ctx;
+    HIPCK(c, hipMalloc(&c->pool, (size_t)c->pool_pages * page_bytes));
+    HIPCK(c, hipMalloc((void**)&c->d_page_table, ns * c->max_pages * sizeof(int)));
+    HIPCK(c, hipMalloc((void**)&c->d_tokens, ns * mc * sizeof(int)));
+    HIPCK(c, hipMalloc((void**)&c->d_lp_actor, ns * mc * 4));
+    HIPCK(c, hipMalloc((void**)&c->d_lp_rescored, ns * mc * 4));
+    HIPCK(c, hipMalloc((void**)&c->d_lp_ref, ns * mc * 4));
+    HIPCK(c, hipMalloc((void**)&c->d_values, ns * mc * 4));
+    HIPCK(c, hipMalloc((void**)&c->d_reward, ns * 4));
+    HIPCK(c, hipMalloc((void**)&c->d_picked, (size_t)e.max_active * sizeof(int)));
+    HIPCK(c, hipHostMalloc((void**)&c->h_picked, (size_t)e.max_active * sizeof(int), hipHostMallocDefault));
+    HIPCK(c, hipMemset(c->d_page_table, 0, ns * c->max_pages * sizeof(int)));
+
+    {   // rotary table in double, stored as float (cos, sin) per (position, pair)
+        const int half = m.head_dim / 2;
+        std::vector<float> tab((size_t)e.max_ctx * m.head_dim);
+        for (int p = 0; p < e.max_ctx; ++p)
+            for (int k = 0; k < half; ++k) {
+                const double ang = (double)p * std::pow((double)m.rope_base, -2.0 * k / m.head_dim);
+                tab[((size_t)p * half + k) * 2] = (float)std::cos(ang);
+                tab[((size_t)p * half + k) * 2 + 1] = (float)std::sin(ang);
+            }
+        HIPCK(c, hipMalloc((void**)&c->d_rope, tab.size() * 4));
+        HIPCK(c, hipMemcpy(c->d_rope, tab.data(), tab.size() * 4, hipMemcpyHostToDevice));
+    }
+
+    int rc;
+    if ((rc = alloc_workspace(c, c->ws_dec, e.max_active, true))) return rc;
+    if ((rc = alloc_workspace(c, c->ws_pre, e.max_batch_tokens, false))) return rc;
+    if ((rc = alloc_workspace(c, c->ws_score, e.max_batch_tokens, false))) return rc;
+    HIPCK(c, c->meta_dec.init((size_t)e.max_active * 10 + (size_t)e.max_active * 2 + 64));
+    // prefill metadata also carries the page-table updates of the admitted prompts
+    HIPCK(c, c->meta_pre.init((size_t)e.max_batch_tokens * 8 + (size_t)e.max_samples * 8 +
+                              2 * ((size_t)e.max_batch_tokens / e.page_tokens + e.max_samples) + 64));
+    HIPCK(c, c->meta_score.init((size_t)e.max_batch_tokens * 8 + (size_t)e.max_samples * 4 + 64));
+    return RLHF_OK;
+}
+
+extern "C" int rlhf_create(const rlhf_model_cfg* model, const rlhf_engine_cfg* engine, rlhf_ctx** out) {
+    if (out) *out = nullptr;
+    if (!model || !engine || !out) {
+        snprintf(g_create_error, sizeof g_create_error, "rlhf_create: NULL argument");
+        return RLHF_EINVAL;
+    }
+    rlhf_ctx* c = new rlhf_ctx();
+    c->mc = *model;
+    c->ec = *engine;
+    const int rc = create_impl(c);
+    if (rc != RLHF_OK) {
+        snprintf(g_create_error, sizeof g_create_error, "%s", c->err);
+        rlhf_destroy(c);
+        return rc;
+    }
+    *out = c;
+    return RLHF_OK;
+}
+
+extern "C" int rlhf_load_weights(rlhf_ctx* c, int role, const rlhf_weights* w) {
+    if (!c) return RLHF_EINVAL;
+    if (role < 0 || role > 3 || !w) return c->fail(RLHF_EINVAL, "rlhf_load_weights: bad role or NULL weights");
+    if (!w->embed || !w->g_final || !w->head ||
+        (c->mc.n_layers > 0 && (!w->wqkv || !w->wo || !w->w_gate_up || !w->w_down || !w->g_attn || !w->g_mlp)))
+        return c->fail(RLHF_EINVAL, "rlhf_load_weights: NULL tensor");
+    const void* ptrs[] = {w->embed, w->wqkv, w->wo, w->w_gate_up, w->w_down, w->g_attn, w->g_mlp, w->g_final, w->head};
+    for (const void* p : ptrs)
+        if (p && ((uintptr_t)p & 15)) return c->fail(RLHF_EINVAL, "rlhf_load_weights: tensors must be 16-byte aligned");
+    c->roles[role].w = *w;
+    c->roles[role].bound = true;
+    return RLHF_OK;
+}
+
+extern "C" int rlhf_sync(rlhf_ctx* c) {
+    if (!c) return RLHF_EINVAL;
+    HIPCK(c, hipStreamSynchronize(c->sd));
+    HIPCK(c, hipStreamSynchronize(c->ss));
+    return RLHF_OK;
+}
+
+// =================================================================================== submit
+
+extern "C" int rlhf_submit(rlhf_ctx* c, int32_t n, const int32_t* prompt_tokens,
+                           const int64_t* prompt_offsets, const int32_t* max_new,
+                           const int32_t* forced_len, const int32_t* forced_tokens,
+                           const int64_t* forced_offsets) {
+    if (!c) return RLHF_EINVAL;
+    if (n < 0 || n > c->ec.max_samples) return c->fail(RLHF_EINVAL, "rlhf_submit: n = %d outside [0, %d]", n, c->ec.max_samples);
+    if (n > 0 && (!prompt_tokens || !prompt_offsets || !max_new)) return c->fail(RLHF_EINVAL, "rlhf_submit: NULL array");
+    if (forced_tokens && !forced_offsets) return c->fail(RLHF_EINVAL, "rlhf_submit: forced_tokens without forced_offsets");
+    const int mc = c->ec.max_ctx, pt = c->ec.page_tokens;
+    std::vector<Sample> smp(n);
+    for (int i = 0; i < n; ++i) {
+        const int64_t P = prompt_offsets[i + 1] - prompt_offsets[i];
+        if (P < 1 || max_new[i] < 1 || P + max_new[i] > mc)
+            return c->fail(RLHF_EINVAL, "rlhf_submit: sample %d has prompt %lld, max_new %d (need >= 1, sum <= max_ctx %d)",
+                           i, (long long)P, max_new[i], mc);
+        Sample& s = smp[i];
+        s.P = (int)P;
+        s.max_new = max_new[i];
+        s.target = max_new[i];
+        if (forced_len) {
+            if (forced_len[i] < 1 || forced_len[i] > max_new[i])
+                return c->fail(RLHF_EINVAL, "rlhf_submit: forced_len[%d] = %d outside [1, max_new]", i, forced_len[i]);
+            s.target = forced_len[i];
+            s.has_forced_len = true;
+        }
+        s.reserve = ceil_div(s.P + s.max_new, pt);
+        if (s.reserve > c->pool_pages)
+            return c->fail(RLHF_ENOMEM, "rlhf_submit: sample %d reserves %d pages, the pool has %d", i, s.reserve, c->pool_pages);
+        for (int64_t k = prompt_offsets[i]; k < prompt_offsets[i + 1]; ++k)
+            if (prompt_tokens[k] < 0 || prompt_tokens[k] >= c->mc.vocab)
+                return c->fail(RLHF_EINVAL, "rlhf_submit: token %d of sample %d out of range", prompt_tokens[k], i);
+        if (forced_tokens) {
+            const int64_t fl = forced_offsets[i + 1] - forced_offsets[i];
+            if (fl < 0 || fl > s.max_new) return c->fail(RLHF_EINVAL, "rlhf_submit: forced_offsets of sample %d", i);
+            for (int64_t k = forced_offsets[i]; k < forced_offsets[i + 1]; ++k)
+                if (forced_tokens[k] >= c->mc.vocab) return c->fail(RLHF_EINVAL, "rlhf_submit: forced token out of range");
+        }
+    }
+    int rc = rlhf_sync(c);
+    if (rc) return rc;
+
+    c->N = n;
+    c->smp.swap(smp);
+    c->h_prompt.assign(prompt_tokens, prompt_tokens + (n ? prompt_offsets[n] : 0));
+    c->h_prompt_off.assign(prompt_offsets, prompt_offsets + (n ? n + 1 : 0));
+    c->h_forced.assign((size_t)n * mc, -1);
+    std::vector<int> tok((size_t)n * mc, 0);
+    for (int i = 0; i < n; ++i) {
+        Sample& s = c->smp[i];
+        std::copy(prompt_tokens + prompt_offsets[i], prompt_tokens + prompt_offsets[i + 1], tok.begin() + (size_t)i * mc);
+        if (forced_tokens)
+            for (int64_t k = forced_offsets[i]; k < forced_offsets[i + 1]; ++k)
+                c->h_forced[(size_t)i * mc + (k - forced_offsets[i])] = forced_tokens[k] < 0 ? -1 : forced_tokens[k];
+        if (s.has_forced_len) c->h_forced[(size_t)i * mc + s.target - 1] = c->ec.eos_id;
+    }
+    if (n) HIPCK(c, hipMemcpy(c->d_tokens, tok.data(), tok.size() * sizeof(int), hipMemcpyHostToDevice));
+    c->waiting.clear();
+    for (int i = 0; i < n; ++i) c->waiting.push_back(i);
+    c->active.clear();
+    c->free_list.resize(c->pool_pages);
+    for (int p = 0; p < c->pool_pages; ++p) c->free_list[p] = c->pool_pages - 1 - p;   // pop_back issues 0, 1, 2, ...
+    c->reserved = 0;
+    c->retired.clear();
+    c->n_scored = 0;
+    c->batch_offsets.assign(1, 0);
+    c->batch_step.clear();
+    c->step = 0;
+    c->score_used = false;
+    c->acc_weight_bytes = c->acc_kv_bytes = c->acc_prefill_tokens = 0;
+    return RLHF_OK;
+}
+
+// ============================================================================ generate step
+
+namespace {
+
+int take_page(rlhf_ctx* c, Sample& s) {
+    const int pg = c->free_list.back();
+    c->free_list.pop_back();
+    s.pages.push_back(pg);
+    return pg;
+}
+
+// Imposed token at output index j (1-based) of sample i, or -1.
+int forced_at(const rlhf_ctx* c, int i, int j) { return c->h_forced[(size_t)i * c->ec.max_ctx + (j - 1)]; }
+
+// Head over selected rows of a batch pass: logits in row chunks, then pick / gather.
+struct HeadPlan {
+    int n_sel = 0;
+    const int* sel_rows = nullptr;     // device: rows of the pass whose hidden state feeds the head
+    // pick (prefill): per selected row
+    const int* forced = nullptr;
+    const int* tok_dst = nullptr;
+    const int* lp_dst = nullptr;
+    // gather (scoring log-probs): per selected row
+    const int* target_idx = nullptr;
+    const int* out_dst = nullptr;
+    float* out = nullptr;
+};
+
+int lm_head_chunks(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weights& w, const HeadPlan& hp,
+                   bool pick) {
+    const rlhf_model_cfg& m = c->mc;
+    const int d = m.d_model, V = m.vocab;
+    for (int r0 = 0; r0 < hp.n_sel; r0 += ws.logit_rows) {
+        const int nr = std::min(ws.logit_rows, hp.n_sel - r0);
+        const char* x = (const char*)ws.xsel + (size_t)r0 * d * c->esz;
+        HIPCK(c, launch_gemm(st, c->dtype, x, w.head, ws.logits, nr, V, d, 1));
+        if (pick)
+            HIPCK(c, launch_pick(st, ws.logits, 1, 0, nr, V, hp.forced + r0, c->d_tokens, hp.tok_dst + r0,
+                                 c->d_lp_actor, hp.lp_dst + r0, nullptr));
+        else
+            HIPCK(c, launch_gather_lp(st, ws.logits, 1, 0, nr, V, c->d_tokens, hp.target_idx + r0, hp.out,
+                                      hp.out_dst + r0));
+    }
+    return RLHF_OK;
+}
+
+// Prefill of newly admitted samples [group], whose prompts total `T` rows <= max_batch_tokens.
+int prefill_group(rlhf_ctx* c, const std::vector<int>& group, int T) {
+    const int mc = c->ec.max_ctx, pt = c->ec.page_tokens, n = (int)group.size();
+    int* hm;
+    HIPCK(c, c->meta_pre.begin(&hm));
+    // layout: tok_idx[T] pos[T] row_start[T] kv_dst[T] | sel[n] forced[n] tok_dst[n] lp_dst[n] | upd_idx[U] upd_val[U]
+    int* tok_idx = hm;
+    int* pos = hm + T;
+    int* row_start = hm + 2 * T;
+    int* kv_dst = hm + 3 * T;
+    int* sel = hm + 4 * T;
+    int* forced = sel + n;
+    int* tok_dst = forced + n;
+    int* lp_dst = tok_dst + n;
+    int* upd = lp_dst + n;
+    std::vector<int> upd_idx, upd_val;
+    int row = 0;
+    for (int gi = 0; gi < n; ++gi) {
+        const int i = group[gi];
+        Sample& s = c->smp[i];
+        const int start = row;
+        for (int p = 0; p < s.P; ++p, ++row) {
+            if (p % pt == 0) {
+                const int pg = take_page(c, s);
+                upd_idx.push_back(i * c->max_pages + p / pt);
+                upd_val.push_back(pg);
+            }
+            tok_idx[row] = i * mc + p;
+            pos[row] = p;
+            row_start[row] = start;
+            kv_dst[row] = s.pages[p / pt] * pt + p % pt;
+        }
+        s.ctx = s.P;
+        s.gen_len = 1;
+        s.admit_step = c->step;
+        sel[gi] = row - 1;
+        forced[gi] = forced_at(c, i, 1);
+        tok_dst[gi] = i * mc + s.P;
+        lp_dst[gi] = i * mc + 0;
+    }
+    const int U = (int)upd_idx.size();
+    std::copy(upd_idx.begin(), upd_idx.end(), upd);
+    std::copy(upd_val.begin(), upd_val.end(), upd + U);
+    const size_t n_ints = (size_t)4 * T + 4 * n + 2 * U;
+    if (n_ints > c->meta_pre.cap) return c->fail(RLHF_EINVAL, "internal: prefill metadata overflow");
+    HIPCK(c, c->meta_pre.commit(c->sd, n_ints));
+    const int* dm_ = c->meta_pre.dev;
+    HIPCK(c, launch_scatter_int(c->sd, c->d_page_table, dm_ + 4 * T + 4 * n, dm_ + 4 * T + 4 * n + U, U));
+
+    PassMeta pm;
+    pm.tok_idx = dm_;
+    pm.pos = dm_ + T;
+    pm.row_start = dm_ + 2 * T;
+    pm.kv_dst = dm_ + 3 * T;
+    const rlhf_weights& w = c->roles[RLHF_ACTOR].w;
+    Workspace& ws = c->ws_pre;
+    int pns;
+    size_t pstride;
+    int rc = forward_layers(c, c->sd, ws, w, T, pm, kAttnBatch, 1, &pns, &pstride);
+    if (rc) return rc;
+    HIPCK(c, launch_rmsnorm(c->sd, c->dtype, ws.h, ws.part, pns, pstride, dm_ + 4 * T, w.g_final, ws.xsel, n,
+                            c->mc.d_model, c->mc.rms_eps));
+    HeadPlan hp;
+    hp.n_sel = n;
+    hp.forced = dm_ + 4 * T + n;
+    hp.tok_dst = dm_ + 4 * T + 2 * n;
+    hp.lp_dst = dm_ + 4 * T + 3 * n;
+    rc = lm_head_chunks(c, c->sd, ws, w, hp, true);
+    if (rc) return rc;
+    c->acc_prefill_tokens += T;
+    return RLHF_OK;
+}
+
+int decode_rows(rlhf_ctx* c, const std::vector<int>& rows_ids) {
+    const int R = (int)rows_ids.size();
+    const int mc = c->ec.max_ctx, pt = c->ec.page_tokens;
+    int* hm;
+    HIPCK(c, c->meta_dec.begin(&hm));
+    // layout: tok_idx pos kv_dst row_sample ctx_len tok_dst lp_dst forced (R each) | upd_idx[U] upd_val[U]
+    int* a[8];
+    for (int k = 0; k < 8; ++k) a[k] = hm + k * R;
+    int* upd = hm + 8 * R;
+    int U = 0;
+    int64_t kv_tokens = 0;
+    int max_ctx_len = 0;
+    for (int r = 0; r < R; ++r) {
+        const int i = rows_ids[r];
+        Sample& s = c->smp[i];
+        const int p = s.ctx;                 // position being written
+        if (p % pt == 0) {
+            const int pg = take_page(c, s);
+            upd[U] = i * c->max_pages + p / pt;
+            upd[R + U] = pg;                 // provisional slot; compacted below
+            ++U;
+        }
+        a[0][r] = i * mc + p;
+        a[1][r] = p;
+        a[2][r] = s.pages[p / pt] * pt + p % pt;
+        a[3][r] = i;
+        a[4][r] = p + 1;
+        a[5][r] = i * mc + p + 1;
+        a[6][r] = i * mc + (p + 1 - s.P);
+        a[7][r] = forced_at(c, i, p + 2 - s.P);
+        s.ctx = p + 1;
+        s.gen_len += 1;
+        kv_tokens += p + 2;                  // p+1 keys read, one written
+        max_ctx_len = std::max(max_ctx_len, p + 1);
+    }
+    for (int u = 0; u < U; ++u) upd[U + u] = upd[R + u];
+    HIPCK(c, c->meta_dec.commit(c->sd, (size_t)8 * R + 2 * U));
+    const int* dmeta = c->meta_dec.dev;
+    HIPCK(c, launch_scatter_int(c->sd, c->d_page_table, dmeta + 8 * R, dmeta + 8 * R + U, U));
+
+    PassMeta pm;
+    pm.tok_idx = dmeta;
+    pm.pos = dmeta + R;
+    pm.kv_dst = dmeta + 2 * R;
+    pm.row_sample = dmeta + 3 * R;
+    pm.ctx_len = dmeta + 4 * R;
+    // split long contexts so that a handful of samples still fills the chip
+    Workspace& ws = c->ws_dec;
+    const int blocks = R * c->mc.n_kv_heads;
+    int asplit = std::max(1, 1024 / std::max(blocks, 1));
+    asplit = std::min(asplit, std::max(1, ceil_div(max_ctx_len, pt) / 8));
+    asplit = std::min<int>(asplit, 32);
+    asplit = (int)std::min<size_t>(asplit, ws.attn_slots / ((size_t)R * c->mc.n_q_heads));
+    if (asplit < 1) asplit = 1;
+
+    const rlhf_weights& w = c->roles[RLHF_ACTOR].w;
+    int pns;
+    size_t pstride;
+    int rc = forward_layers(c, c->sd, ws, w, R, pm, kAttnDecode, asplit, &pns, &pstride);
+    if (rc) return rc;
+    const int d = c->mc.d_model, V = c->mc.vocab;
+    HIPCK(c, launch_rmsnorm(c->sd, c->dtype, ws.h, ws.part, pns, pstride, nullptr, w.g_final, ws.xsel, R, d,
+                            c->mc.rms_eps));
+    const int ns = nsplit_for(c, ws, R, V, d);
+    HIPCK(c, launch_gemm(c->sd, c->dtype, ws.xsel, w.head, ws.part, R, V, d, ns));
+    HIPCK(c, launch_pick(c->sd, ws.part, ns, (size_t)R * V, R, V, dmeta + 7 * R, c->d_tokens, dmeta + 5 * R,
+                         c->d_lp_actor, dmeta + 6 * R, c->d_picked));
+    // algorithmic bytes of this step
+    const rlhf_model_cfg& m = c->mc;
+    const int64_t qd = (int64_t)m.n_q_heads * m.head_dim, kvd = (int64_t)m.n_kv_heads * m.head_dim;
+    const int64_t per_layer = (qd + 2 * kvd) * m.d_model + m.d_model * qd + 3LL * m.d_model * m.ffn;
+    c->acc_weight_bytes += (m.n_layers * per_layer + (int64_t)m.vocab * m.d_model) * c->esz;
+    c->acc_kv_bytes += kv_tokens * 2 * m.n_layers * kvd * c->esz;
+    return RLHF_OK;
+}
+
+// stop_on_eos: fetch the tokens just picked for `ids` (pick order) and mark finished samples.
+int check_eos(rlhf_ctx* c, const std::vector<int>& ids, const int* d_src) {
+    if (!c->ec.stop_on_eos || ids.empty()) return RLHF_OK;
+    HIPCK(c, hipMemcpyAsync(c->h_picked, d_src, ids.size() * sizeof(int), hipMemcpyDeviceToHost, c->sd));
+    HIPCK(c, hipStreamSynchronize(c->sd));
+    for (size_t r = 0; r < ids.size(); ++r)
+        if (c->h_picked[r] == c->ec.eos_id) c->smp[ids[r]].finished = true;
+    return RLHF_OK;
+}
+
+bool sample_done(const Sample& s) { return s.finished || s.gen_len >= s.target; }
+
+}  // namespace
+
+extern "C" int rlhf_generate_step(rlhf_ctx* c, rlhf_step_info* out) {
+    if (!c) return RLHF_EINVAL;
+    if (!c->roles[RLHF_ACTOR].bound) return c->fail(RLHF_ESTATE, "rlhf_generate_step: Actor weights not loaded");
+    if (c->waiting.empty() && c->active.empty()) return c->fail(RLHF_ESTATE, "rlhf_generate_step: nothing to generate");
+    // admission: FIFO, reservation must fit, first misfit blocks the queue
+    std::vector<int> newcomers;
+    while (!c->waiting.empty() && (int)(c->active.size() + newcomers.size()) < c->ec.max_active) {
+        const int i = c->waiting.front();
+        if (c->reserved + c->smp[i].reserve > c->pool_pages) break;
+        c->waiting.pop_front();
+        c->reserved += c->smp[i].reserve;
+        newcomers.push_back(i);
+    }
+    int n_prefill = 0;
+    // prefill in groups that fit one batch pass
+    size_t g0 = 0;
+    while (g0 < newcomers.size()) {
+        std::vector<int> group;
+        int T = 0;
+        size_t g1 = g0;
+        while (g1 < newcomers.size() && T + c->smp[newcomers[g1]].P <= c->ec.max_batch_tokens) {
+            T += c->smp[newcomers[g1]].P;
+            group.push_back(newcomers[g1]);
+            ++g1;
+        }
+        int rc = prefill_group(c, group, T);
+        if (rc) return rc;
+        if (c->ec.stop_on_eos) {
+            // picked tokens of a prefill are not in d_picked; read them from the token buffer
+            for (int i : group) {
+                int y;
+                HIPCK(c, hipMemcpyAsync(&y, c->d_tokens + (size_t)i * c->ec.max_ctx + c->smp[i].P, sizeof(int),
+                                        hipMemcpyDeviceToHost, c->sd));
+                HIPCK(c, hipStreamSynchronize(c->sd));
+                if (y == c->ec.eos_id) c->smp[i].finished = true;
+            }
+        }
+        n_prefill += T;
+        g0 = g1;
+    }
+    for (int i : newcomers) c->active.push_back(i);
+    std::vector<int> rows;
+    for (int i : c->active)
+        if (!sample_done(c->smp[i])) rows.push_back(i);
+    if (!rows.empty()) {
+        int rc = decode_rows(c, rows);
+        if (rc) return rc;
+        rc = check_eos(c, rows, c->d_picked);
+        if (rc) return rc;
+    }
+    if (out) {
+        out->step = c->step;
+        out->n_admitted = (int)newcomers.size();
+        out->n_prefill_tokens = n_prefill;
+        out->n_decoded = (int)rows.size();
+        out->n_active = (int)c->active.size();
+    }
+    c->step += 1;
+    return RLHF_OK;
+}
+
+extern "C" int rlhf_retire(rlhf_ctx* c, int32_t* retired_ids, int32_t* n_retired) {
+    if (!c) return RLHF_EINVAL;
+    int n = 0;
+    std::vector<int> keep;
+    keep.reserve(c->active.size());
+    for (int i : c->active) {
+        Sample& s = c->smp[i];
+        if (sample_done(s)) {
+            for (auto it = s.pages.rbegin(); it != s.pages.rend(); ++it) c->free_list.push_back(*it);
+            s.pages.clear();
+            c->reserved -= s.reserve;
+            s.retired = true;
+            c->retired.push_back(i);
+            if (retired_ids) retired_ids[n] = i;
+            ++n;
+        } else {
+            keep.push_back(i);
+        }
+    }
+    c->active.swap(keep);
+    if (n_retired) *n_retired = n;
+    return RLHF_OK;
+}
+
+// ================================================================================== scoring
+
+namespace {
+
+// One packed pass over samples ids[lo, hi) (total T rows) for one role.
+int score_pass(rlhf_ctx* c, hipStream_t st, MetaRing& meta, Workspace& ws, const int* ids, int n, int T, int role) {
+    const int mc = c->ec.max_ctx;
+    int* hm;
+    HIPCK(c, meta.begin(&hm));
+    int n_sel = 0;
+    for (int k = 0; k < n; ++k) n_sel += role == RLHF_REWARD ? 1 : c->smp[ids[k]].gen_len;
+    // layout: tok_idx[T] pos[T] row_start[T] | sel[n_sel] target_idx[n_sel] out_dst[n_sel]
+    int* tok_idx = hm;
+    int* pos = hm + T;
+    int* row_start = hm + 2 * T;
+    int* sel = hm + 3 * T;
+    int* target = sel + n_sel;
+    int* out_dst = target + n_sel;
+    if ((size_t)3 * T + 3 * n_sel > meta.cap) return c->fail(RLHF_EINVAL, "internal: scoring metadata overflow");
+    int row = 0, si = 0;
+    for (int k = 0; k < n; ++k) {
+        const int i = ids[k];
+        const Sample& s = c->smp[i];
+        const int Ti = s.P + s.gen_len, start = row;
+        for (int p = 0; p < Ti; ++p, ++row) {
+            tok_idx[row] = i * mc + p;
+            pos[row] = p;
+            row_start[row] = start;
+        }
+        if (role == RLHF_REWARD) {
+            sel[si] = start + Ti - 1;
+            target[si] = 0;
+            out_dst[si] = i;
+            ++si;
+        } else {
+            for (int j = 1; j <= s.gen_len; ++j, ++si) {
+                sel[si] = start + s.P + j - 2;          // the position that predicts y_j (0-based)
+                target[si] = i * mc + s.P + j - 1;      // y_j itself sits one position later
+                out_dst[si] = i * mc + j - 1;
+            }
+        }
+    }
+    HIPCK(c, meta.commit(st, (size_t)3 * T + 3 * n_sel));
+    const int* dmeta = meta.dev;
+    PassMeta pm;
+    pm.tok_idx = dmeta;
+    pm.pos = dmeta + T;
+    pm.row_start = dmeta + 2 * T;
+    const rlhf_weights& w = c->roles[role].w;
+    int pns;
+    size_t pstride;
+    int rc = forward_layers(c, st, ws, w, T, pm, kAttnBatch, 1, &pns, &pstride);
+    if (rc) return rc;
+    const int d = c->mc.d_model;
+    // selected rows may exceed the workspace rows only if n_sel > T, which cannot happen
+    HIPCK(c, launch_rmsnorm(st, c->dtype, ws.h, ws.part, pns, pstride, dmeta + 3 * T, w.g_final, ws.xsel, n_sel, d,
+                            c->mc.rms_eps));
+    if (role == RLHF_CRITIC)
+        HIPCK(c, launch_head_dot(st, c->dtype, ws.xsel, w.head, n_sel, d, c->d_values, dmeta + 3 * T + 2 * n_sel));
+    else if (role == RLHF_REWARD)
+        HIPCK(c, launch_head_dot(st, c->dtype, ws.xsel, w.head, n_sel, d, c->d_reward, dmeta + 3 * T + 2 * n_sel));
+    else {
+        HeadPlan hp;
+        hp.n_sel = n_sel;
+        hp.target_idx = dmeta + 3 * T + n_sel;
+        hp.out_dst = dmeta + 3 * T + 2 * n_sel;
+        hp.out = role == RLHF_REF ? c->d_lp_ref : c->d_lp_rescored;
+        rc = lm_head_chunks(c, st, ws, w, hp, false);
+        if (rc) return rc;
+    }
+    return RLHF_OK;
+}
+
+int score_ids(rlhf_ctx* c, const int* ids, int n, uint32_t role_mask, bool on_score_stream) {
+    if (n <= 0) return RLHF_OK;
+    for (int role = 0; role < 4; ++role)
+        if ((role_mask & RLHF_ROLE_BIT(role)) && !c->roles[role].bound)
+            return c->fail(RLHF_ESTATE, "rlhf_score: role %d has no weights", role);
+    for (int k = 0; k < n; ++k) {
+        if (ids[k] < 0 || ids[k] >= c->N) return c->fail(RLHF_EINVAL, "rlhf_score: sample id %d out of range", ids[k]);
+        if (!sample_done(c->smp[ids[k]]) || c->smp[ids[k]].gen_len < 1)
+            return c->fail(RLHF_ESTATE, "rlhf_score: sample %d is still generating", ids[k]);
+    }
+    hipStream_t st = on_score_stream ? c->ss : c->sd;
+    Workspace& ws = on_score_stream ? c->ws_score : c->ws_pre;
+    MetaRing& meta = on_score_stream ? c->meta_score : c->meta_pre;
+    if (on_score_stream) {
+        // the tokens being scored were written by work already enqueued on the decode stream
+        HIPCK(c, hipEventRecord(c->ev_dep, c->sd));
+        HIPCK(c, hipStreamWaitEvent(c->ss, c->ev_dep, 0));
+        if (!c->score_used) {
+            HIPCK(c, hipEventRecord(c->ev_s0, c->ss));
+            c->score_used = true;
+        }
+    }
+    // sub-passes bounded by the workspace rows; a sample is never split
+    int lo = 0;
+    while (lo < n) {
+        int hi = lo, T = 0;
+        while (hi < n && T + c->smp[ids[hi]].P + c->smp[ids[hi]].gen_len <= c->ec.max_batch_tokens) {
+            T += c->smp[ids[hi]].P + c->smp[ids[hi]].gen_len;
+            ++hi;
+        }
+        for (int role = 0; role < 4; ++role)
+            if (role_mask & RLHF_ROLE_BIT(role)) {
+                int rc = score_pass(c, st, meta, ws, ids + lo, hi - lo, T, role);
+                if (rc) return rc;
+            }
+        lo = hi;
+    }
+    return RLHF_OK;
+}
+
+// Cut the un-scored part of the retired FIFO into batches of >= chunk tokens; flush the rest
+// when generation is over.  Returns the number of batches closed.
+int form_batches(rlhf_ctx* c, int chunk_tokens) {
+    const int chunk = std::max(1, chunk_tokens);
+    const bool done = c->waiting.empty() && c->active.empty();
+    int closed = 0;
+    for (;;) {
+        size_t k = c->n_scored;
+        long tok = 0;
+        while (k < c->retired.size() && tok < chunk) {
+            const Sample& s = c->smp[c->retired[k]];
+            tok += s.P + s.gen_len;
+            ++k;
+        }
+        if (tok >= chunk || (done && k > c->n_scored)) {
+            c->n_scored = k;
+            c->batch_offsets.push_back((int)k);
+            c->batch_step.push_back(c->step - 1);
+            ++closed;
+        } else {
+            break;
+        }
+    }
+    return closed;
+}
+
+}  // namespace
+
+extern "C" int rlhf_score(rlhf_ctx* c, int32_t n, const int32_t* sample_ids, uint32_t role_mask,
+                          int32_t on_score_stream) {
+    if (!c) return RLHF_EINVAL;
+    if (n < 0 || (n > 0 && !sample_ids)) return c->fail(RLHF_EINVAL, "rlhf_score: bad arguments");
+    if (role_mask & ~0xFu) return c->fail(RLHF_EINVAL, "rlhf_score: unknown role bits");
+    return score_ids(c, sample_ids, n, role_mask, on_score_stream != 0);
+}
+
+// ================================================================================ run stage
+
+extern "C" int rlhf_run_stage(rlhf_ctx* c, const rlhf_stage_opts* o, rlhf_stage_stats* out) {
+    if (!c) return RLHF_EINVAL;
+    if (!o) return c->fail(RLHF_EINVAL, "rlhf_run_stage: NULL options");
+    if (c->step != 0 || !c->retired.empty()) return c->fail(RLHF_ESTATE, "rlhf_run_stage: call rlhf_submit first");
+    if (o->role_mask & ~0xFu) return c->fail(RLHF_EINVAL, "rlhf_run_stage: unknown role bits");
+    const bool timing = o->trace_step_ms && o->trace_cap > 0;
+    int rc = rlhf_sync(c);
+    if (rc) return rc;
+    const auto t0 = std::chrono::steady_clock::now();
+    HIPCK(c, hipEventRecord(c->ev_d0, c->sd));
+    const size_t first_batch = c->batch_step.size();
+    int n_steps = 0;
+    auto run_new_batches = [&](int closed) -> int {
+        const size_t nb = c->batch_step.size();
+        for (size_t b = nb - closed; b < nb; ++b) {
+            const int lo = c->batch_offsets[b], hi = c->batch_offsets[b + 1];
+            int r = score_ids(c, c->retired.data() + lo, hi - lo, o->role_mask, o->fused != 0);
+            if (r) return r;
+        }
+        return RLHF_OK;
+    };
+    while (!c->waiting.empty() || !c->active.empty()) {
+        if (timing && n_steps < o->trace_cap) {
+            while ((int)c->step_events.size() < 2 * (n_steps + 1)) {
+                hipEvent_t e;
+                HIPCK(c, hipEventCreate(&e));
+                c->step_events.push_back(e);
+            }
+            HIPCK(c, hipEventRecord(c->step_events[2 * n_steps], c->sd));
+        }
+        rlhf_step_info info;
+        rc = rlhf_generate_step(c, &info);
+        if (rc) return rc;
+        if (timing && n_steps < o->trace_cap) HIPCK(c, hipEventRecord(c->step_events[2 * n_steps + 1], c->sd));
+        int nret;
+        rc = rlhf_retire(c, nullptr, &nret);
+        if (rc) return rc;
+        if (n_steps < o->trace_cap) {
+            if (o->trace_active) o->trace_active[n_steps] = (int)c->active.size();
+            if (o->trace_decoded) o->trace_decoded[n_steps] = info.n_decoded;
+        }
+        ++n_steps;
+        const int remaining = (int)(c->waiting.size() + c->active.size());
+        if (o->fused && remaining > 0 && remaining < o->R_t) {
+            rc = run_new_batches(form_batches(c, o->score_chunk_tokens));
+            if (rc) return rc;
+        }
+    }
+    HIPCK(c, hipEventRecord(c->ev_d1, c->sd));
+    rc = run_new_batches(form_batches(c, o->score_chunk_tokens));   // generation is over: flush
+    if (rc) return rc;
+    if (c->score_used) HIPCK(c, hipEventRecord(c->ev_s1, c->ss));
+    else HIPCK(c, hipEventRecord(c->ev_d1, c->sd));                  // serial scoring ran on the decode stream
+    rc = rlhf_sync(c);
+    if (rc) return rc;
+    const auto t1 = std::chrono::steady_clock::now();
+    if (timing)
+        for (int s = 0; s < std::min(n_steps, o->trace_cap); ++s)
+            HIPCK(c, hipEventElapsedTime(&o->trace_step_ms[s], c->step_events[2 * s], c->step_events[2 * s + 1]));
+    if (out) {
+        memset(out, 0, sizeof *out);
+        out->n_steps = n_steps;
+        out->n_batches = (int)(c->batch_step.size() - first_batch);
+        for (const Sample& s : c->smp) {
+            out->generated_tokens += s.gen_len;
+            out->scored_tokens += s.P + s.gen_len;
+        }
+        out->prefill_tokens = c->acc_prefill_tokens;
+        out->wall_ms = std::chrono::duration<double, std::milli>(t1 - t0).count();
+        float ms = 0.f;
+        HIPCK(c, hipEventElapsedTime(&ms, c->ev_d0, c->ev_d1));
+        out->decode_stream_ms = ms;
+        if (c->score_used) {
+            HIPCK(c, hipEventElapsedTime(&ms, c->ev_s0, c->ev_s1));
+            out->score_stream_ms = ms;
+        }
+        out->decode_weight_bytes = c->acc_weight_bytes;
+        out->decode_kv_bytes = c->acc_kv_bytes;
+    }
+    return RLHF_OK;
+}
+
+// ======================================================================== results / snapshot
+
+extern "C" int rlhf_get_results(rlhf_ctx* c, rlhf_results* out) {
+    if (!c) return RLHF_EINVAL;
+    if (!out) return c->fail(RLHF_EINVAL, "rlhf_get_results: NULL");
+    int rc = rlhf_sync(c);
+    if (rc) return rc;
+    const int n = c->N, mc = c->ec.max_ctx;
+    int64_t total = 0;
+    for (int i = 0; i < n; ++i) total += c->smp[i].gen_len;
+    const bool packed = out->tokens || out->lp_actor || out->lp_actor_rescored || out->lp_ref || out->values;
+    if (packed && out->packed_capacity < total)
+        return c->fail(RLHF_EINVAL, "rlhf_get_results: packed_capacity %lld < %lld", (long long)out->packed_capacity, (long long)total);
+    if (out->gen_len)
+        for (int i = 0; i < n; ++i) out->gen_len[i] = c->smp[i].gen_len;
+    if (out->resp_offsets) {
+        out->resp_offsets[0] = 0;
+        for (int i = 0; i < n; ++i) out->resp_offsets[i + 1] = out->resp_offsets[i] + c->smp[i].gen_len;
+    }
+    std::vector<float> buf;
+    auto fetch_packed = [&](const float* dsrc, float* dst) -> int {
+        if (!dst || n == 0) return RLHF_OK;
+        buf.resize((size_t)n * mc);
+        HIPCK(c, hipMemcpy(buf.data(), dsrc, buf.size() * 4, hipMemcpyDeviceToHost));
+        int64_t o = 0;
+        for (int i = 0; i < n; ++i) {
+            std::copy(buf.begin() + (size_t)i * mc, buf.begin() + (size_t)i * mc + c->smp[i].gen_len, dst + o);
+            o += c->smp[i].gen_len;
+        }
+        return RLHF_OK;
+    };
+    if ((rc = fetch_packed(c->d_lp_actor, out->lp_actor))) return rc;
+    if ((rc = fetch_packed(c->d_lp_rescored, out->lp_actor_rescored))) return rc;
+    if ((rc = fetch_packed(c->d_lp_ref, out->lp_ref))) return rc;
+    if ((rc = fetch_packed(c->d_values, out->values))) return rc;
+    if (out->tokens && n) {
+        std::vector<int> tb((size_t)n * mc);
+        HIPCK(c, hipMemcpy(tb.data(), c->d_tokens, tb.size() * sizeof(int), hipMemcpyDeviceToHost));
+        int64_t o = 0;
+        for (int i = 0; i < n; ++i) {
+            const Sample& s = c->smp[i];
+            std::copy(tb.begin() + (size_t)i * mc + s.P, tb.begin() + (size_t)i * mc + s.P + s.gen_len, out->tokens + o);
+            o += s.gen_len;
+        }
+    }
+    if (out->reward && n) HIPCK(c, hipMemcpy(out->reward, c->d_reward, (size_t)n * 4, hipMemcpyDeviceToHost));
+    return RLHF_OK;
+}
+
+extern "C" int rlhf_debug_snapshot(rlhf_ctx* c, rlhf_snapshot* o) {
+    if (!c) return RLHF_EINVAL;
+    if (!o) return c->fail(RLHF_EINVAL, "rlhf_debug_snapshot: NULL");
+    const int n = c->N;
+    o->step = c->step;
+    o->n_samples = n;
+    o->n_waiting = (int)c->waiting.size();
+    o->n_active = (int)c->active.size();
+    o->n_retired = (int)c->retired.size();
+    o->n_batches = (int)c->batch_step.size();
+    o->n_free = (int)c->free_list.size();
+    o->reserved_pages = c->reserved;
+    o->pool_pages = c->pool_pages;
+    o->max_pages = c->max_pages;
+    if (o->cap_samples < n || o->cap_max_pages < c->max_pages ||
+        (o->free_list && o->cap_pool_pages < c->pool_pages))
+        return c->fail(RLHF_EINVAL, "rlhf_debug_snapshot: capacities too small (need %d samples, %d pages/sample, %d pool pages)",
+                       n, c->max_pages, c->pool_pages);
+    if (o->active) std::copy(c->active.begin(), c->active.end(), o->active);
+    for (int i = 0; i < n; ++i) {
+        const Sample& s = c->smp[i];
+        if (o->ctx) o->ctx[i] = s.ctx;
+        if (o->gen_len) o->gen_len[i] = s.gen_len;
+        if (o->n_pages) o->n_pages[i] = (int)s.pages.size();
+        if (o->page_table) {
+            int* row = o->page_table + (size_t)i * o->cap_max_pages;
+            std::fill(row, row + o->cap_max_pages, -1);
+            std::copy(s.pages.begin(), s.pages.end(), row);
+        }
+    }
+    if (o->free_list) std::copy(c->free_list.begin(), c->free_list.end(), o->free_list);
+    if (o->retired) std::copy(c->retired.begin(), c->retired.end(), o->retired);
+    if (o->batch_offsets) std::copy(c->batch_offsets.begin(), c->batch_offsets.end(), o->batch_offsets);
+    if (o->batch_step) std::copy(c->batch_step.begin(), c->batch_step.end(), o->batch_step);
+    return RLHF_OK;
+}

@@ -1,0 +1,257 @@
+// C[m][n] = sum_k A[m][k] * W[n][k]   (activations times a row-major weight matrix, y = W x)
+//
+// bf16: LDS-tiled MFMA kernel (v_mfma_f32_16x16x32_bf16, float accumulate).  One template
+// serves the decode regime (few rows: the weight matrix streams from HBM once, split along K
+// so that enough workgroups are in flight to saturate bandwidth) and the prefill / scoring
+// regime (thousands of rows: compute-bound 128x128 tiles).  Global loads are 16 bytes per lane,
+// consecutive lanes along K; tiles sit in LDS with an XOR swizzle of the 16-byte chunk index
+// so that the MFMA-fragment reads (16 rows x one chunk per quarter wave) spread over the banks.
+// Split-K partials are written to separate buffers and summed by the consumer kernel, which
+// keeps the result deterministic (no float atomics).
+//
+// fp32: a plain LDS-tiled kernel for the float configuration (small model; not tuned).
+#include "common.cuh"
+#include "kernels.h"
+
+namespace rlhf {
+
+constexpr int kTK = 64;  // K extent of one LDS tile (bf16 elements): 8 chunks of 16 bytes per row
+
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+
+// TM x TN output tile per workgroup of 4 waves arranged WM x WN; each wave owns
+// (TM/WM) x (TN/WN), built from 16x16 MFMA fragments.
+template <int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
+                                                   const bf16_t* __restrict__ W,
+                                                   float* __restrict__ C, int M, int N, int K,
+                                                   int kchunk, int tiles_n) {
+    static_assert(WM * WN == 4, "four waves");
+    constexpr int FM = TM / WM / 16, FN = TN / WN / 16;
+    constexpr int A_CH = TM * 8, B_CH = TN * 8;          // 16-byte chunks per tile
+    constexpr int A_IT = (A_CH + 255) / 256, B_IT = (B_CH + 255) / 256;
+    __shared__ __attribute__((aligned(16))) bf16_t sA[2][TM * kTK];
+    __shared__ __attribute__((aligned(16))) bf16_t sB[2][TN * kTK];
+
+    const int tile = blockIdx.x;
+    const int tm = tile / tiles_n, tn = tile - tm * tiles_n;
+    const int m0 = tm * TM, n0 = tn * TN;
+    const int split = blockIdx.y;
+    const int kbeg = split * kchunk;
+    const int kend = min(K, kbeg + kchunk);
+    const int nk = (kend - kbeg + kTK - 1) / kTK;
+
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int wm = w / WN, wn = w - wm * WN;
+
+    uint4 ra[A_IT], rb[B_IT];
+    auto gload = [&](int kt) {
+        const int k0 = kbeg + kt * kTK;
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i) {
+            const int idx = t + i * 256;
+            const int row = idx >> 3, c = idx & 7;
+            const int gm = m0 + row, gk = k0 + c * 8;
+            ra[i] = make_uint4(0, 0, 0, 0);
+            if (idx < A_CH && gm < M && gk < kend)
+                ra[i] = *reinterpret_cast<const uint4*>(A + (size_t)gm * K + gk);
+        }
+#pragma unroll
+        for (int i = 0; i < B_IT; ++i) {
+            const int idx = t + i * 256;
+            const int row = idx >> 3, c = idx & 7;
+            const int gn = n0 + row, gk = k0 + c * 8;
+            rb[i] = make_uint4(0, 0, 0, 0);
+            if (idx < B_CH && gn < N && gk < kend)
+                rb[i] = *reinterpret_cast<const uint4*>(W + (size_t)gn * K + gk);
+        }
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i) {
+            const int idx = t + i * 256;
+            const int row = idx >> 3, c = idx & 7;
+            if (idx < A_CH)
+                *reinterpret_cast<uint4*>(&sA[buf][row * kTK + swz(row, c) * 8]) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_IT; ++i) {
+            const int idx = t + i * 256;
+            const int row = idx >> 3, c = idx & 7;
+            if (idx < B_CH)
+                *reinterpret_cast<uint4*>(&sB[buf][row * kTK + swz(row, c) * 8]) = rb[i];
+        }
+    };
+
+    f32x4_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    if (nk > 0) {
+        gload(0);
+        sstore(0);
+    }
+    __syncthreads();
+    const int fr = lane & 15, fq = lane >> 4;
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) gload(kt + 1);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            bf16x8_t fa[FM], fb[FN];
+            const int c = s * 4 + fq;
+#pragma unroll
+            for (int i = 0; i < FM; ++i) {
+                const int row = wm * (TM / WM) + i * 16 + fr;
+                fa[i] = *reinterpret_cast<const bf16x8_t*>(&sA[buf][row * kTK + swz(row, c) * 8]);
+            }
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int row = wn * (TN / WN) + j * 16 + fr;
+                fb[j] = *reinterpret_cast<const bf16x8_t*>(&sB[buf][row * kTK + swz(row, c) * 8]);
+            }
+            // weights are the MFMA "A" operand: D[i = n][j = m], so a lane ends up holding four
+            // consecutive n of one row m and stores them as one float4.
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) sstore(buf ^ 1);
+        __syncthreads();
+    }
+
+    float* Cs = C + (size_t)split * M * N;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        const int m = m0 + wm * (TM / WM) + i * 16 + fr;
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int n = n0 + wn * (TN / WN) + j * 16 + fq * 4;
+            float* dst = Cs + (size_t)m * N + n;
+            if (n + 3 < N && (N & 3) == 0) {
+                *reinterpret_cast<float4*>(dst) =
+                    make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (n + e < N) dst[e] = acc[i][j][e];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------ fp32 path
+// 64x64 tile, K step 16, 256 threads each computing a 4x4 block.
+__global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A,
+                                                  const float* __restrict__ W,
+                                                  float* __restrict__ C, int M, int N, int K,
+                                                  int kchunk, int tiles_n) {
+    __shared__ float sA[16][64 + 4];
+    __shared__ float sB[16][64 + 4];
+    const int tile = blockIdx.x;
+    const int tm = tile / tiles_n, tn = tile - tm * tiles_n;
+    const int m0 = tm * 64, n0 = tn * 64;
+    const int split = blockIdx.y;
+    const int kbeg = split * kchunk, kend = min(K, kbeg + kchunk);
+    const int t = threadIdx.x;
+    const int ty = t >> 4, tx = t & 15;        // 16 x 16 threads, 4 x 4 outputs each
+    const int lr = t >> 2, lc = (t & 3) * 4;   // loader: row 0..63, k offset 0,4,8,12
+    float acc[4][4] = {};
+    for (int k0 = kbeg; k0 < kend; k0 += 16) {
+        float4 va = make_float4(0, 0, 0, 0), vb = make_float4(0, 0, 0, 0);
+        if (m0 + lr < M && k0 + lc < kend)
+            va = *reinterpret_cast<const float4*>(A + (size_t)(m0 + lr) * K + k0 + lc);
+        if (n0 + lr < N && k0 + lc < kend)
+            vb = *reinterpret_cast<const float4*>(W + (size_t)(n0 + lr) * K + k0 + lc);
+        __syncthreads();
+        sA[lc + 0][lr] = va.x; sA[lc + 1][lr] = va.y; sA[lc + 2][lr] = va.z; sA[lc + 3][lr] = va.w;
+        sB[lc + 0][lr] = vb.x; sB[lc + 1][lr] = vb.y; sB[lc + 2][lr] = vb.z; sB[lc + 3][lr] = vb.w;
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = sA[kk][ty * 4 + i]; b[i] = sB[kk][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+        }
+    }
+    float* Cs = C + (size_t)split * M * N;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + ty * 4 + i;
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + tx * 4 + j;
+            if (n < N) Cs[(size_t)m * N + n] = acc[i][j];
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------- dispatch
+namespace {
+struct TileCfg { int tm, tn; };
+
+TileCfg pick_tile(int M) {
+    if (M <= 16) return {16, 128};
+    if (M <= 32) return {32, 128};
+    if (M <= 64) return {64, 128};
+    return {128, 128};
+}
+constexpr int kTargetBlocks = 1024;  // about four workgroups per compute unit
+}  // namespace
+
+int gemm_choose_nsplit(int dtype, int M, int N, int K, int max_split) {
+    int tm, tn, kgran;
+    if (dtype == kBF16) { TileCfg c = pick_tile(M); tm = c.tm; tn = c.tn; kgran = kTK; }
+    else { tm = 64; tn = 64; kgran = 16; }
+    const long tiles = (long)((M + tm - 1) / tm) * ((N + tn - 1) / tn);
+    int ns = (int)((kTargetBlocks + tiles - 1) / tiles);
+    const int kmax = K / (4 * kgran) > 0 ? K / (4 * kgran) : 1;   // keep >= 4 K tiles per split
+    if (ns > kmax) ns = kmax;
+    if (ns > max_split) ns = max_split;
+    if (ns < 1) ns = 1;
+    // a split that would get no K range is pointless: shrink until every split is non-empty
+    while (ns > 1) {
+        int kchunk = ((K + ns - 1) / ns + kgran - 1) / kgran * kgran;
+        if ((long)(ns - 1) * kchunk < K) break;
+        --ns;
+    }
+    return ns;
+}
+
+hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const void* W, float* C, int M,
+                       int N, int K, int nsplit) {
+    if (M <= 0 || N <= 0) return hipSuccess;
+    if (nsplit < 1 || K <= 0) return hipErrorInvalidValue;
+    if (dtype == kBF16) {
+        if (K % 8) return hipErrorInvalidValue;
+        const TileCfg c = pick_tile(M);
+        const int tiles_m = (M + c.tm - 1) / c.tm, tiles_n = (N + c.tn - 1) / c.tn;
+        const int kchunk = ((K + nsplit - 1) / nsplit + kTK - 1) / kTK * kTK;
+        dim3 grid(tiles_m * tiles_n, nsplit);
+        const bf16_t* a = (const bf16_t*)A;
+        const bf16_t* w = (const bf16_t*)W;
+        if (c.tm == 16) k_gemm_bf16<16, 128, 1, 4><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
+        else if (c.tm == 32) k_gemm_bf16<32, 128, 1, 4><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
+        else if (c.tm == 64) k_gemm_bf16<64, 128, 2, 2><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
+        else k_gemm_bf16<128, 128, 2, 2><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
+    } else {
+        if (K % 4) return hipErrorInvalidValue;
+        const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
+        const int kchunk = ((K + nsplit - 1) / nsplit + 15) / 16 * 16;
+        dim3 grid(tiles_m * tiles_n, nsplit);
+        k_gemm_f32<<<grid, 256, 0, st>>>((const float*)A, (const float*)W, C, M, N, K, kchunk, tiles_n);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace rlhf

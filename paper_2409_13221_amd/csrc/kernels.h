@@ -1,0 +1,73 @@
+// Host-callable launchers of the HIP kernels.  Every launcher validates nothing: the engine
+// checks shapes and bounds on the host before it launches (see engine.cpp).  All pointers are
+// device pointers.  "nsplit / sstride": a float input that is the sum of nsplit partial
+// buffers, partial s at x + s * sstride (split-K GEMM output consumed without a reduce pass).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace rlhf {
+
+enum DType { kF32 = 0, kBF16 = 1 };
+
+struct Dims {
+    int n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+    int page_tokens;
+};
+
+// ---- GEMM: C[s][m][n] = sum over k in split s of A[m][k] * W[n][k];  C float, split stride M*N
+int gemm_choose_nsplit(int dtype, int M, int N, int K, int max_split);
+hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const void* W, float* C, int M,
+                       int N, int K, int nsplit);
+
+// ---- elementwise / row kernels
+hipError_t launch_embed(hipStream_t st, int dtype, const int* tokens, const int* tok_idx,
+                        const void* table, float* h, int rows, int d, int vocab);
+// v = h[src] + sum partials[src];  (row_idx == NULL: src = r and h[src] = v is written back)
+// xn[r] = v * rsqrt(mean(v^2) + eps) * g
+hipError_t launch_rmsnorm(hipStream_t st, int dtype, float* h, const float* part, int nsplit,
+                          size_t sstride, const int* row_idx, const float* g, void* xn, int rows,
+                          int d, float eps);
+// Rotary on Q and K heads of qkv rows, cast to storage type.  q_out [rows, Hq*hd]; k_out/v_out
+// [rows, Hkv*hd] if non-NULL; if pool != NULL and kv_dst[r] >= 0, K/V of row r also go to
+// token slot kv_dst[r] (= page * page_tokens + offset) of `layer` in the paged pool.
+hipError_t launch_rope_kv(hipStream_t st, int dtype, const float* qkv, int nsplit, size_t sstride,
+                          const int* pos, const int* kv_dst, const float* rope_table,
+                          void* q_out, void* k_out, void* v_out, void* pool, int layer,
+                          int rows, const Dims& dm);
+hipError_t launch_swiglu(hipStream_t st, int dtype, const float* gu, int nsplit, size_t sstride,
+                         void* act, int rows, int ffn);
+// Greedy choice per logit row (lowest id on ties), optional imposed token forced[r] >= 0;
+// writes the emitted token to tokens[tok_dst[r]] and picked[r], its log-prob to lp[lp_dst[r]].
+hipError_t launch_pick(hipStream_t st, const float* logits, int nsplit, size_t sstride, int rows,
+                       int vocab, const int* forced, int* tokens, const int* tok_dst, float* lp,
+                       const int* lp_dst, int* picked);
+// lp[out_dst[r]] = log_softmax(logits[r])[tokens[target_idx[r]]]
+hipError_t launch_gather_lp(hipStream_t st, const float* logits, int nsplit, size_t sstride,
+                            int rows, int vocab, const int* tokens, const int* target_idx,
+                            float* out, const int* out_dst);
+// out[out_dst[r]] = <xn[r], w>
+hipError_t launch_head_dot(hipStream_t st, int dtype, const void* xn, const void* w, int rows,
+                           int d, float* out, const int* out_dst);
+// page_table[upd_idx[i]] = upd_val[i]
+hipError_t launch_scatter_int(hipStream_t st, int* dst, const int* idx, const int* val, int n);
+
+// ---- attention
+// Decode: one query row per active sample against its paged K/V.  q [rows, Hq*hd]; out the same.
+// row_sample[r] selects the page-table row; ctx_len[r] keys are visible.  part_* hold split
+// partials when nsplit > 1 (sizes rows*Hq*nsplit*(hd or 1)).
+hipError_t launch_decode_attn(hipStream_t st, int dtype, const void* q, const void* pool,
+                              const int* page_table, int pt_stride, const int* row_sample,
+                              const int* ctx_len, void* out, float* part_acc, float* part_ml,
+                              int rows, int layer, int nsplit, const Dims& dm);
+// Prefill / scoring: packed varlen causal attention over contiguous q [T,Hq*hd], k, v
+// [T,Hkv*hd]; row r belongs to the sequence starting at row_start[r] and sits at position
+// row_pos[r] in it (sees keys row_start[r] .. row_start[r] + row_pos[r]).
+hipError_t launch_prefill_attn(hipStream_t st, int dtype, const void* q, const void* k,
+                               const void* v, const int* row_start, const int* row_pos,
+                               void* out, int rows, const Dims& dm);
+
+size_t pool_page_elems(const Dims& dm);  // elements of one page over all layers
+
+}  // namespace rlhf

@@ -1,0 +1,53 @@
+// Kernel-level C entry points (include/rlhf_ops.h): thin argument checks around the launchers.
+#include "../../include/rlhf_ops.h"
+
+#include <hip/hip_runtime.h>
+
+#include "../../include/rlhf.h"
+#include "kernels.h"
+
+using namespace rlhf;
+
+static int status_of(hipError_t e) {
+    if (e == hipSuccess) return RLHF_OK;
+    return e == hipErrorInvalidValue ? RLHF_EINVAL : RLHF_EDEVICE;
+}
+
+extern "C" int rlhf_op_gemm_nsplit(int dtype, int M, int N, int K, int max_split) {
+    if (M <= 0 || N <= 0 || K <= 0 || max_split < 1) return 1;
+    return gemm_choose_nsplit(dtype == RLHF_BF16 ? kBF16 : kF32, M, N, K, max_split);
+}
+
+extern "C" int rlhf_op_gemm(int dtype, const void* A, const void* W, float* C, int M, int N, int K,
+                            int nsplit, void* stream) {
+    if (!A || !W || !C || M < 0 || N < 0 || K <= 0 || nsplit < 1) return RLHF_EINVAL;
+    if (dtype != RLHF_BF16 && dtype != RLHF_FP32) return RLHF_EINVAL;
+    return status_of(launch_gemm((hipStream_t)stream, dtype == RLHF_BF16 ? kBF16 : kF32, A, W, C, M, N, K, nsplit));
+}
+
+extern "C" int rlhf_op_paged_decode_attention(int dtype, const void* q, const void* pool,
+                                              const int32_t* page_table, int pt_stride,
+                                              const int32_t* row_sample, const int32_t* ctx_len, void* out,
+                                              float* part_acc, float* part_ml, int rows, int layer, int nsplit,
+                                              int n_layers, int n_q_heads, int n_kv_heads, int head_dim,
+                                              void* stream) {
+    if (!q || !pool || !page_table || !row_sample || !ctx_len || !out || rows < 0 || nsplit < 1 ||
+        layer < 0 || layer >= n_layers || n_kv_heads <= 0 || n_q_heads % n_kv_heads)
+        return RLHF_EINVAL;
+    if (nsplit > 1 && (!part_acc || !part_ml)) return RLHF_EINVAL;
+    Dims dm{n_layers, n_q_heads * head_dim, n_q_heads, n_kv_heads, head_dim, 0, 0, 16};
+    return status_of(launch_decode_attn((hipStream_t)stream, dtype == RLHF_BF16 ? kBF16 : kF32, q, pool,
+                                        page_table, pt_stride, row_sample, ctx_len, out, part_acc, part_ml,
+                                        rows, layer, nsplit, dm));
+}
+
+extern "C" int rlhf_op_varlen_attention(int dtype, const void* q, const void* k, const void* v,
+                                        const int32_t* row_start, const int32_t* row_pos, void* out,
+                                        int rows, int n_q_heads, int n_kv_heads, int head_dim, void* stream) {
+    if (!q || !k || !v || !row_start || !row_pos || !out || rows < 0 || n_kv_heads <= 0 ||
+        n_q_heads % n_kv_heads)
+        return RLHF_EINVAL;
+    Dims dm{1, n_q_heads * head_dim, n_q_heads, n_kv_heads, head_dim, 0, 0, 16};
+    return status_of(launch_prefill_attn((hipStream_t)stream, dtype == RLHF_BF16 ? kBF16 : kF32, q, k, v,
+                                         row_start, row_pos, out, rows, dm));
+}

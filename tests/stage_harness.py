@@ -1,0 +1,177 @@
+"""Shared helpers of the GPU parity tests, the smoke check and the benchmark's CPU leg:
+run the oracle on a seeded workload, run the same workload through the C ABI, compare.
+
+The oracle side decides which positions are teacher-forced: where its own top-2 logit margin
+is below MARGIN the GPU path is fed the oracle's token (and the token comparison at that
+position is vacuous), everywhere else the GPU's greedy choice must equal the oracle's.
+"""
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from oracle import transformer as OT
+from oracle.scheduler import SchedulerModel
+from workload import make_weights, make_workload
+from workload.configs import WorkloadCfg
+
+MARGIN = 1e-2
+LP_TOL = {"fp32": 1e-4, "bf16": 2e-2}
+ALL_ROLES = 0xF
+
+
+def page_bytes(cfg: WorkloadCfg, n_layers: Optional[int] = None) -> int:
+    m = cfg.model
+    ly = m.n_layers if n_layers is None else n_layers
+    return ly * 2 * m.n_kv_heads * cfg.page_tokens * m.head_dim * m.elem_bytes()
+
+
+def make_inputs(cfg: WorkloadCfg, n: Optional[int] = None, max_len: Optional[int] = None,
+                n_layers: Optional[int] = None, weight_device="cpu") -> dict:
+    wl = make_workload(cfg, n)
+    out_len = wl["out_len"] if max_len is None else np.minimum(wl["out_len"], max_len)
+    weights = [make_weights(cfg, r, device=weight_device, n_layers=n_layers) for r in range(4)]
+    return {"prompt_tokens": wl["prompt_tokens"], "prompt_offsets": wl["prompt_offsets"],
+            "out_len": out_len.astype(np.int32), "weights": weights, "n_layers": n_layers}
+
+
+def oracle_models(cfg: WorkloadCfg, inp: dict, dtype=np.float64):
+    shape = OT.Shape.of(cfg.model, inp["n_layers"])
+    return [OT.Model(shape, {k: v.float().cpu().numpy() for k, v in w.items()}, dtype) for w in inp["weights"]]
+
+
+def oracle_stage(cfg: WorkloadCfg, n: Optional[int] = None, max_len: Optional[int] = None,
+                 n_layers: Optional[int] = None, weight_device="cpu", dtype=np.float64,
+                 inp: Optional[dict] = None) -> dict:
+    """The unfused per-sample definition: greedy generation, then the three scoring forwards."""
+    inp = inp or make_inputs(cfg, n, max_len, n_layers, weight_device)
+    actor, ref, critic, reward = oracle_models(cfg, inp, dtype)
+    po = inp["prompt_offsets"]
+    prompts = [inp["prompt_tokens"][po[i]:po[i + 1]].tolist() for i in range(len(po) - 1)]
+    gen = OT.greedy_generate_cached(actor, prompts, inp["out_len"], cfg.eos_id)
+    res = dict(inp)
+    res["prompts"] = prompts
+    res["tokens"] = [g.tokens for g in gen]
+    res["lp_actor"] = [g.logprob for g in gen]
+    res["margin"] = [g.margin for g in gen]
+    res["forced"] = [np.where(g.margin < MARGIN, g.tokens, -1).astype(np.int32) for g in gen]
+    res["lp_ref"] = [OT.score_logprobs(ref, p, g.tokens.tolist()) for p, g in zip(prompts, gen)]
+    res["values"] = [OT.score_values(critic, p, g.tokens.tolist()) for p, g in zip(prompts, gen)]
+    res["reward"] = np.array([OT.score_reward(reward, p, g.tokens.tolist()) for p, g in zip(prompts, gen)])
+    return res
+
+
+class GpuStage:
+    """Context + borrowed device weights for one workload, through the Python binding."""
+
+    def __init__(self, cfg: WorkloadCfg, inp: dict, pool_pages: Optional[int] = None,
+                 max_active: Optional[int] = None, max_batch_tokens: Optional[int] = None,
+                 stop_on_eos: bool = False, max_new_cap: Optional[int] = None):
+        import paper_2409_13221_amd as R
+        self.R = R
+        self.cfg = cfg
+        self.inp = inp
+        m = cfg.model
+        ly = m.n_layers if inp["n_layers"] is None else inp["n_layers"]
+        po = inp["prompt_offsets"]
+        self.n = len(po) - 1
+        self.plen = np.diff(po).astype(np.int32)
+        self.max_new = (inp["out_len"] if max_new_cap is None else np.full(self.n, max_new_cap)).astype(np.int32)
+        self.max_ctx = int((self.plen + self.max_new).max()) + 1
+        need = int(np.ceil((self.plen + self.max_new) / cfg.page_tokens).sum())
+        self.pool_pages = need if pool_pages is None else pool_pages
+        self.max_active = self.n if max_active is None else max_active
+        mc = R.model_cfg_of(m)
+        mc.n_layers = ly
+        ec = R.rlhf_engine_cfg(cfg.page_tokens, self.pool_pages * page_bytes(cfg, ly), self.n, self.max_ctx,
+                               self.max_active,
+                               max(self.max_ctx, max_batch_tokens or 0), cfg.eos_id, int(stop_on_eos), None, None)
+        self.dev_weights = [{k: v.to("cuda").contiguous() for k, v in w.items()} for w in inp["weights"]]
+        self.ctx = R.rlhf_create(mc, ec)
+        for role, w in enumerate(self.dev_weights):
+            R.rlhf_load_weights(self.ctx, role, w)
+
+    def submit(self, forced=None, use_forced_len=True):
+        ft = fo = None
+        if forced is not None:
+            ft = np.concatenate(forced).astype(np.int32)
+            fo = np.concatenate([[0], np.cumsum([len(f) for f in forced])]).astype(np.int64)
+        self.R.rlhf_submit(self.ctx, self.inp["prompt_tokens"], self.inp["prompt_offsets"], self.max_new,
+                           self.inp["out_len"] if use_forced_len else None, ft, fo)
+
+    def snapshot(self):
+        return self.R.rlhf_debug_snapshot(self.ctx, self.n, -(-self.max_ctx // self.cfg.page_tokens),
+                                          self.pool_pages)
+
+    def results(self):
+        return self.R.rlhf_get_results(self.ctx, self.n, int(self.max_new.sum()))
+
+    def close(self):
+        if self.ctx is not None:
+            self.R.rlhf_destroy(self.ctx)
+            self.ctx = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+
+def run_gpu_stage(cfg: WorkloadCfg, ref: dict, fused: bool, R_t: int, chunk_tokens: int,
+                  role_mask: int = ALL_ROLES, **kw) -> dict:
+    with GpuStage(cfg, ref, **kw) as g:
+        g.submit(ref.get("forced"))
+        stats, trace = g.R.rlhf_run_stage(g.ctx, fused, R_t, chunk_tokens, role_mask, trace_cap=1 << 16)
+        out = g.results()
+        out["stats"], out["trace"], out["snapshot"] = stats, trace, g.snapshot()
+    return out
+
+
+def unpack(res: Dict[str, np.ndarray], key: str):
+    o = res["resp_offsets"]
+    return [res[key][o[i]:o[i + 1]] for i in range(len(o) - 1)]
+
+
+def close_rel(a, b, rel=1e-2):
+    """|a - b| <= rel * max(|b|, 0.1 rms(b)): relative, with a floor so that values that
+    happen to be near zero do not blow the ratio up."""
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    floor = 0.1 * np.sqrt(np.mean(b * b)) if b.size else 0.0
+    return np.abs(a - b) <= rel * np.maximum(np.abs(b), floor)
+
+
+def compare_stage(cfg: WorkloadCfg, ref: dict, got: dict, check_rescored: bool = True) -> dict:
+    """Token ids identical (forced positions are vacuous by construction), log-probs within the
+    dtype's tolerance, values / rewards within 1e-2 relative.  Returns the worst errors."""
+    tol = LP_TOL[cfg.model.dtype]
+    n = len(ref["tokens"])
+    assert got["gen_len"].tolist() == [len(t) for t in ref["tokens"]]
+    worst = {"lp_actor": 0.0, "lp_ref": 0.0, "lp_actor_rescored": 0.0}
+    toks, lpa, lpr, lps, val = (unpack(got, k) for k in ("tokens", "lp_actor", "lp_ref", "lp_actor_rescored", "values"))
+    all_val_ref, all_val_got = [], []
+    for i in range(n):
+        np.testing.assert_array_equal(toks[i], ref["tokens"][i], err_msg=f"tokens of sample {i}")
+        for key, arr, want in (("lp_actor", lpa[i], ref["lp_actor"][i]), ("lp_ref", lpr[i], ref["lp_ref"][i])):
+            err = float(np.max(np.abs(arr - want)))
+            worst[key] = max(worst[key], err)
+            assert err <= tol, f"{key} of sample {i}: max abs err {err} > {tol}"
+        if check_rescored:
+            err = float(np.max(np.abs(lps[i] - ref["lp_actor"][i])))
+            worst["lp_actor_rescored"] = max(worst["lp_actor_rescored"], err)
+            assert err <= tol, f"lp_actor_rescored of sample {i}: {err} > {tol}"
+        all_val_ref.append(ref["values"][i])
+        all_val_got.append(val[i])
+    vr, vg = np.concatenate(all_val_ref), np.concatenate(all_val_got)
+    ok = close_rel(vg, vr)
+    assert ok.all(), f"values: {np.sum(~ok)} of {ok.size} outside 1e-2 relative; worst abs {np.abs(vg - vr).max()}"
+    ok = close_rel(got["reward"], ref["reward"])
+    assert ok.all(), f"rewards outside 1e-2 relative: {got['reward']} vs {ref['reward']}"
+    worst["values_abs"] = float(np.abs(vg - vr).max())
+    worst["reward_abs"] = float(np.abs(got["reward"] - ref["reward"]).max())
+    return worst
+
+
+def scheduler_model_for(g: GpuStage) -> SchedulerModel:
+    return SchedulerModel(g.plen, g.max_new, g.inp["out_len"], g.pool_pages, g.cfg.page_tokens,
+                          max_active=g.max_active)

@@ -1,0 +1,121 @@
+"""Kernel-level parity through the C ABI (include/rlhf_ops.h) against the oracle's primitives
+(numpy float64 matmul; oracle.transformer.attention)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import transformer as OT
+
+pytestmark = pytest.mark.gpu
+
+
+def _R():
+    import paper_2409_13221_amd as R
+    return R
+
+
+def _bf16_round(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("M,N,K,nsplit", [
+    (1, 256, 512, 1), (5, 130, 72, 1), (16, 768, 256, 4), (17, 1376, 256, 2), (33, 200, 688, 3),
+    (64, 512, 2048, 1), (100, 4100, 328, 1), (257, 384, 1000, 2), (300, 1024, 64, 1),
+])
+def test_gemm(dtype, M, N, K, nsplit):
+    R = _R()
+    r = np.random.default_rng(M * 7 + N)
+    a, w = r.normal(size=(M, K)), r.normal(size=(N, K))
+    if dtype == "bf16":
+        A, W = _bf16_round(a).cuda(), _bf16_round(w).cuda()
+    else:
+        A, W = torch.from_numpy(a.astype(np.float32)).cuda(), torch.from_numpy(w.astype(np.float32)).cuda()
+    want = A.double().cpu().numpy() @ W.double().cpu().numpy().T
+    out = torch.full((nsplit, M, N), float("nan"), device="cuda")
+    R.rlhf_op_gemm(A, W, out, nsplit)
+    torch.cuda.synchronize()
+    got = out.double().sum(0).cpu().numpy()
+    # inputs are exact in both paths; only float32 accumulation order differs
+    np.testing.assert_allclose(got, want, rtol=0, atol=3e-5 * np.sqrt(K) * 4)
+
+
+def test_gemm_nsplit_choice_is_sane():
+    R = _R()
+    for (M, N, K) in [(1, 4096, 4096), (16, 22016, 4096), (256, 4096, 11008), (8192, 4096, 4096)]:
+        ns = R.rlhf_op_gemm_nsplit(R.RLHF_BF16, M, N, K, 16)
+        assert 1 <= ns <= 16
+        assert (ns - 1) * (-(-K // ns)) < K
+    assert R.rlhf_op_gemm_nsplit(R.RLHF_BF16, 8192, 4096, 4096, 16) == 1
+
+
+def _paged_case(seed, rows, Hq, Hkv, hd, n_layers, layer, ctx_lens, dtype):
+    r = np.random.default_rng(seed)
+    n_pages_each = [-(-c // 16) for c in ctx_lens]
+    pool_pages = sum(n_pages_each) + 3
+    perm = r.permutation(pool_pages)
+    pt_stride = max(n_pages_each) + 1
+    page_table = np.full((rows + 2, pt_stride), 0, np.int32)
+    row_sample = r.permutation(rows + 2)[:rows].astype(np.int32)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    pool = (torch.randn(pool_pages, n_layers, 2, Hkv, 16, hd) * 1.0).to(tdt)
+    q = (torch.randn(rows, Hq, hd) * 2.0).to(tdt)
+    nxt = 0
+    want = np.zeros((rows, Hq, hd))
+    for rr in range(rows):
+        pages = perm[nxt:nxt + n_pages_each[rr]]
+        nxt += n_pages_each[rr]
+        page_table[row_sample[rr], :len(pages)] = pages
+        kv = pool[pages, layer].double().numpy()                  # [np, 2, Hkv, 16, hd]
+        k = kv[:, 0].transpose(0, 2, 1, 3).reshape(-1, Hkv, hd)[:ctx_lens[rr]]
+        v = kv[:, 1].transpose(0, 2, 1, 3).reshape(-1, Hkv, hd)[:ctx_lens[rr]]
+        want[rr] = OT.attention(q[rr:rr + 1].double().numpy(), k, v, np.array([ctx_lens[rr] - 1]))[0]
+    return q, pool, page_table, row_sample, want
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,hd", [("bf16", 4, 4, 128), ("bf16", 16, 2, 128), ("bf16", 3, 3, 64),
+                                             ("fp32", 4, 4, 64), ("fp32", 2, 2, 128)])
+@pytest.mark.parametrize("nsplit", [1, 3, 8])
+def test_paged_decode_attention(dtype, Hq, Hkv, hd, nsplit):
+    R = _R()
+    ctx_lens = [1, 16, 17, 5, 250, 64, 33, 129]
+    rows, n_layers, layer = len(ctx_lens), 3, 1
+    q, pool, pt, rs, want = _paged_case(11, rows, Hq, Hkv, hd, n_layers, layer, ctx_lens, dtype)
+    qd, pd = q.cuda().reshape(rows, Hq * hd).contiguous(), pool.cuda().contiguous()
+    out = torch.zeros_like(qd)
+    pa = torch.zeros(rows * Hq * nsplit * hd, device="cuda")
+    pm = torch.zeros(rows * Hq * nsplit * 2, device="cuda")
+    R.rlhf_op_paged_decode_attention(qd, pd, torch.from_numpy(pt).cuda(), torch.from_numpy(rs).cuda(),
+                                     torch.tensor(ctx_lens, dtype=torch.int32).cuda(), out, pa, pm, layer,
+                                     nsplit, n_layers, Hq, Hkv, hd)
+    torch.cuda.synchronize()
+    got = out.double().cpu().numpy().reshape(rows, Hq, hd)
+    tol = 2e-2 if dtype == "bf16" else 2e-5       # bf16: output rounding of values of size ~1-3
+    np.testing.assert_allclose(got, want, rtol=0, atol=tol)
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,hd", [("bf16", 4, 4, 128), ("bf16", 8, 1, 128), ("bf16", 2, 2, 64),
+                                             ("fp32", 4, 4, 64)])
+def test_varlen_attention(dtype, Hq, Hkv, hd):
+    R = _R()
+    lens = [1, 7, 16, 17, 40, 3]
+    T = sum(lens)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    torch.manual_seed(3)
+    q, k, v = (torch.randn(T, Hq, hd) * 1.5).to(tdt), torch.randn(T, Hkv, hd).to(tdt), torch.randn(T, Hkv, hd).to(tdt)
+    row_start, row_pos, want = [], [], np.zeros((T, Hq, hd))
+    o = 0
+    for n in lens:
+        row_start += [o] * n
+        row_pos += list(range(n))
+        want[o:o + n] = OT.attention(q[o:o + n].double().numpy(), k[o:o + n].double().numpy(),
+                                     v[o:o + n].double().numpy(), np.arange(n))
+        o += n
+    out = torch.zeros(T, Hq * hd, dtype=tdt, device="cuda")
+    R.rlhf_op_varlen_attention(q.cuda().reshape(T, -1).contiguous(), k.cuda().reshape(T, -1).contiguous(),
+                               v.cuda().reshape(T, -1).contiguous(),
+                               torch.tensor(row_start, dtype=torch.int32).cuda(),
+                               torch.tensor(row_pos, dtype=torch.int32).cuda(), out, Hq, Hkv, hd)
+    torch.cuda.synchronize()
+    tol = 2e-2 if dtype == "bf16" else 2e-5
+    np.testing.assert_allclose(out.double().cpu().numpy().reshape(T, Hq, hd), want, rtol=0, atol=tol)
