@@ -106,7 +106,7 @@ def lib() -> C.CDLL:
         L.rlhf_sync.argtypes = [vp]
         L.rlhf_op_gemm_nsplit.argtypes = [C.c_int] * 5
         L.rlhf_op_gemm.argtypes = [C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp]
-        L.rlhf_op_paged_decode_attention.argtypes = [C.c_int, vp, vp, vp, C.c_int, vp, vp, vp, vp, vp] + [C.c_int] * 8 + [vp]
+        L.rlhf_op_paged_decode_attention.argtypes = [C.c_int, vp, vp, vp, C.c_int, vp, vp, vp, vp, vp] + [C.c_int] * 7 + [vp]
         L.rlhf_op_varlen_attention.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp] + [C.c_int] * 4 + [vp]
         for name in ("rlhf_create", "rlhf_load_weights", "rlhf_submit", "rlhf_generate_step", "rlhf_retire",
                      "rlhf_score", "rlhf_run_stage", "rlhf_get_results", "rlhf_debug_snapshot", "rlhf_sync",
