@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused generation + inference stage on one MI355X.
+
+One "step" is one whole stage over one synthetic long-tail batch: Actor prefill + decode of
+every sample, fused at sample level with the Reference / Critic / Reward scoring forwards
+(rlhf_run_stage, fused = 1).  Prints ONE JSON line:
+
+  value      (generated + scored sequence tokens) / stage time, tokens/s, inputs resident in HBM
+  roofline   the kernel class with the largest share of GPU time, its algorithmic bytes (or
+             flops) per launch over its HIP-event duration, against the MI355X peak
+  cpu_baseline  the numpy oracle timed on this machine's host cores on a bounded sample
+  plus: fused vs sequential stage time, per-class kernel figures, the long-tail phase lens.
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 7b|gpt2s|tiny|13b|70b_slice]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
+ROLE_MASK_DEFAULT = 0b1110      # Reference, Critic, Reward; Actor log-probs come from decoding
+
+# bounded oracle sample per workload: (samples, output-length cap, oracle dtype)
+CPU_SAMPLE = {"tiny": (8, 64, "float64"), "gpt2s": (4, 24, "float64"), "7b": (1, 6, "float32"),
+              "13b": (1, 4, "float32"), "70b_slice": (1, 6, "float32")}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_stage(cfg, args):
+    import torch
+
+    import paper_2409_13221_amd as R
+    from workload import make_weights, make_workload
+
+    m = cfg.model
+    t0 = time.time()
+    weights = [make_weights(cfg, r, device="cuda") for r in range(4)]
+    torch.cuda.synchronize()
+    log(f"[bench] weights for 4 roles on device in {time.time() - t0:.1f}s")
+    wl = make_workload(cfg)
+    po, out_len = wl["prompt_offsets"], wl["out_len"]
+    plen = np.diff(po).astype(np.int32)
+    n = len(plen)
+    max_new = np.full(n, cfg.length_cap, np.int32)          # reservation is for the cap, as in production
+    max_ctx = int(plen.max()) + cfg.length_cap + 1
+    page_b = m.n_layers * 2 * m.n_kv_heads * cfg.page_tokens * m.head_dim * m.elem_bytes()
+    need_pages = int(np.ceil((plen + max_new) / cfg.page_tokens).sum())
+    free_b, total_b = torch.cuda.mem_get_info()
+    max_batch_tokens = max(args.max_batch_tokens, max_ctx)
+    ws_est = 3 * max_batch_tokens * (12 * m.d_model + 8 * m.ffn + 16 * m.n_q_heads * m.head_dim) + (8 << 30)
+    pool_pages = int(min(need_pages, max(1, (free_b - ws_est) // page_b)))
+    mc = R.model_cfg_of(m)
+    ec = R.rlhf_engine_cfg(cfg.page_tokens, pool_pages * page_b, n, max_ctx, min(n, args.max_active),
+                           max_batch_tokens, cfg.eos_id, 0, None, None)
+    ctx = R.rlhf_create(mc, ec)
+    for role, w in enumerate(weights):
+        R.rlhf_load_weights(ctx, role, w)
+    log(f"[bench] {cfg.name}: {n} samples, prompts {plen.min()}..{plen.max()}, outputs mean {out_len.mean():.1f} "
+        f"max {out_len.max()}; KV pool {pool_pages} pages ({pool_pages * page_b / 2**30:.1f} GiB) of {need_pages} "
+        f"reserved at the cap; HBM free {free_b / 2**30:.0f} of {total_b / 2**30:.0f} GiB")
+    return R, ctx, weights, wl, max_new
+
+
+def run_stage(R, ctx, wl, max_new, fused, args, trace=False):
+    R.rlhf_submit(ctx, wl["prompt_tokens"], wl["prompt_offsets"], max_new, wl["out_len"])
+    n = len(max_new)
+    R_t = args.R_t if args.R_t >= 0 else n + 1
+    t0 = time.perf_counter()
+    stats, tr = R.rlhf_run_stage(ctx, fused, R_t, args.score_chunk_tokens, args.role_mask,
+                                 trace_cap=(1 << 15) if trace else 0, trace_time=trace)
+    return (time.perf_counter() - t0) * 1e3, stats, tr
+
+
+def cpu_baseline(cfg, weights):
+    """The oracle, as it stands, on a bounded sample of the same workload: generation of the
+    first few samples (output length capped) and their three scoring forwards."""
+    import threadpoolctl
+
+    from oracle import transformer as OT
+    from workload import make_workload
+
+    n, cap, dt = CPU_SAMPLE[cfg.name]
+    dtype = np.float64 if dt == "float64" else np.float32
+    wl = make_workload(cfg, n)
+    po = wl["prompt_offsets"]
+    prompts = [wl["prompt_tokens"][po[i]:po[i + 1]].tolist() for i in range(n)]
+    out_len = np.minimum(wl["out_len"], cap)
+    shape = OT.Shape.of(cfg.model)
+    elapsed, toks = 0.0, None
+    for role in range(4):
+        model = OT.Model(shape, {k: v.float().cpu().numpy() for k, v in weights[role].items()}, dtype)
+        t0 = time.perf_counter()
+        if role == 0:
+            gen = OT.greedy_generate_cached(model, prompts, out_len, cfg.eos_id)
+            toks = [g.tokens.tolist() for g in gen]
+        elif role == 1:
+            [OT.score_logprobs(model, p, y) for p, y in zip(prompts, toks)]
+        elif role == 2:
+            [OT.score_values(model, p, y) for p, y in zip(prompts, toks)]
+        else:
+            [OT.score_reward(model, p, y) for p, y in zip(prompts, toks)]
+        elapsed += time.perf_counter() - t0
+        del model
+        log(f"[bench] cpu oracle role {role} done, cumulative {elapsed:.1f}s")
+    G = int(out_len.sum())
+    S = int(sum(len(p) for p in prompts) + G)
+    threads = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
+    return {"value": (G + S) / elapsed, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {n} sample(s) of '{cfg.name}', outputs capped at {cap}: {G} generated + {S} "
+                      f"scored tokens in {elapsed:.1f}s, numpy {dt}, full depth"}
+
+
+def roofline_of(prof, dtype, traffic):
+    est = {k: (v["sampled_ms"] / v["sampled"] * v["launches"] if v["sampled"] else 0.0) for k, v in prof.items()}
+    dom = max(est, key=est.get)
+    v = prof[dom]
+    if dom in ("gemm_decode", "attn_decode"):
+        ach = v["sampled_bytes"] / (v["sampled_ms"] * 1e-3) / 1e9
+        peak, unit, bound = HBM_PEAK_GBS, "GB/s", "hbm"
+    else:
+        ach = v["sampled_flops"] / (v["sampled_ms"] * 1e-3) / 1e12
+        peak, unit, bound = MFMA_PEAK_TFLOPS[dtype], "TFLOP/s", "mfma"
+    return {"bound": bound, "kernel": dom, "achieved": round(ach, 2), "peak": peak, "unit": unit,
+            "frac": round(ach / peak, 4), "traffic": traffic,
+            "avg_launch_us": round(v["sampled_ms"] / v["sampled"] * 1e3, 2), "launches": v["launches"]}, est
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="7b")
+    ap.add_argument("--R_t", type=int, default=-1, help="scoring trigger; -1 = n_samples + 1 (always on)")
+    ap.add_argument("--score_chunk_tokens", type=int, default=4096)
+    ap.add_argument("--max_batch_tokens", type=int, default=8192)
+    ap.add_argument("--max_active", type=int, default=256)
+    ap.add_argument("--role_mask", type=int, default=ROLE_MASK_DEFAULT)
+    ap.add_argument("--sample_every", type=int, default=16)
+    ap.add_argument("--no_cpu", action="store_true")
+    ap.add_argument("--no_sequential", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the stage shards by sample across GPUs with no collective "
+              "inside it; see DESIGN.md).  Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from workload import CONFIGS
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    cfg = CONFIGS[args.config]
+    R, ctx, weights, wl, max_new = build_stage(cfg, args)
+
+    for i in range(args.warmup):
+        ms, st, _ = run_stage(R, ctx, wl, max_new, True, args)
+        log(f"[bench] warmup {i}: {ms:.1f} ms, {st.n_steps} steps, {st.n_batches} scoring batches")
+    R.rlhf_profile_begin(ctx, args.sample_every)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    times, last = [], None
+    for i in range(args.steps):
+        ms, st, tr = run_stage(R, ctx, wl, max_new, True, args, trace=(i == args.steps - 1))
+        times.append(ms)
+        last = (st, tr)
+        log(f"[bench] step {i}: {ms:.1f} ms")
+    torch.cuda.synchronize()
+    total_ms = (time.perf_counter() - t0) * 1e3
+    prof = R.rlhf_profile_end(ctx)
+    st, tr = last
+    ms_per_step = total_ms / args.steps
+    G, S = int(st.generated_tokens), int(st.scored_tokens)
+    value = (G + S) / (ms_per_step * 1e-3)
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath))
+    roof, est = roofline_of(prof, cfg.model.dtype, None)
+    if traffic and roof["kernel"] in traffic:
+        roof["traffic"] = traffic[roof["kernel"]]
+    kernels = {}
+    for k, v in prof.items():
+        if not v["sampled"]:
+            continue
+        sec = v["sampled_ms"] * 1e-3
+        kernels[k] = {"launches": v["launches"], "avg_us": round(v["sampled_ms"] / v["sampled"] * 1e3, 2),
+                      "est_total_ms": round(est[k] / args.steps, 1),
+                      "GBps": round(v["sampled_bytes"] / sec / 1e9, 1),
+                      "TFLOPs": round(v["sampled_flops"] / sec / 1e12, 2)}
+
+    # long-tail lens: steps with at most 20 % of the batch still active; decode-only steps
+    lens = {}
+    if tr is not None and "step_ms" in tr:
+        n = len(max_new)
+        dec_only = tr["prefill_tokens"] == 0
+        tail = (tr["active"] <= 0.2 * n) & dec_only
+        def gbps(mask):
+            t = float(tr["step_ms"][mask].sum())
+            return round(float(tr["step_bytes"][mask].sum()) / (t * 1e-3) / 1e9, 1) if t > 0 else None
+        lens = {"decode_steps": int(st.n_steps), "tail_steps_frac": round(float(tail.mean()), 4),
+                "tail_time_frac": round(float(tr["step_ms"][tail].sum() / max(tr["step_ms"].sum(), 1e-9)), 4),
+                "decode_hbm_GBps": gbps(dec_only), "tail_hbm_GBps": gbps(tail),
+                "decode_hbm_frac": round((gbps(dec_only) or 0) / HBM_PEAK_GBS, 4),
+                "decode_stream_ms": round(st.decode_stream_ms, 1), "score_stream_ms": round(st.score_stream_ms, 1),
+                "generated_tokens": G, "scored_tokens": S, "scoring_batches": int(st.n_batches)}
+
+    seq = None
+    if not args.no_sequential:
+        ms_seq, _, _ = run_stage(R, ctx, wl, max_new, False, args)
+        seq = {"sequential_ms": round(ms_seq, 1), "fused_ms": round(ms_per_step, 1),
+               "speedup": round(ms_seq / ms_per_step, 3)}
+        log(f"[bench] sequential generate-then-score: {ms_seq:.1f} ms")
+    R.rlhf_destroy(ctx)
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(cfg, weights)
+
+    out = {"metric": "gen+scored tokens/s per GPU (long-tail lens)", "value": round(value, 1), "unit": "tokens/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 2),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.model.dtype,
+           "data": "synthetic",
+           "config": {"workload": cfg.name, "n_samples": int(len(max_new)), "length_law": cfg.length_law,
+                      "length_params": list(cfg.length_params), "length_cap": cfg.length_cap,
+                      "score_chunk_tokens": args.score_chunk_tokens, "R_t": args.R_t, "role_mask": args.role_mask,
+                      "page_tokens": cfg.page_tokens},
+           "roofline": roof, "cpu_baseline": cpu, "fused_vs_sequential": seq, "kernels": kernels,
+           "long_tail": lens}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -47,8 +47,11 @@ enum rlhf_dtype { RLHF_FP32 = 0, RLHF_BF16 = 1 };
 
 /* Decoder shape shared by the four roles: pre-norm blocks, RMSNorm, rotary embedding on
  * pairs (k, k + head_dim/2), grouped KV heads, SwiGLU MLP, no biases.  dtype is the
- * storage type of matrices, activations fed to the matrix units and the KV cache; the
- * residual stream, norms, softmax and all accumulation are float32 in either case.
+ * storage type of the matrices and of the KV cache.  The residual stream, norms, softmax
+ * and all accumulation are float32 in either case.  With BF16, activations fed to the
+ * matrix units are bf16 in the decode step and IEEE half in prefill / scoring passes (the
+ * bf16 weights convert to half exactly inside the kernel; the 8 times finer rounding of
+ * half is what keeps values and rewards within 1e-2 of a float64 evaluation).
  * Requirements: head_dim in {64, 128}; d_model, ffn multiples of 8; n_q_heads a multiple
  * of n_kv_heads. */
 typedef struct rlhf_model_cfg {
@@ -117,6 +120,8 @@ typedef struct rlhf_stage_opts {
     int32_t* trace_active;         /* optional host arrays, trace_cap entries: per step the   */
     int32_t* trace_decoded;        /*   active count after retire, the decode rows, and the   */
     float* trace_step_ms;          /*   decode-stream time of the step (adds two events/step) */
+    int64_t* trace_step_bytes;     /*   algorithmic bytes of the step's decode (weights + KV) */
+    int32_t* trace_prefill_tokens; /*   prompt tokens prefilled at the top of the step        */
     int32_t trace_cap;
 } rlhf_stage_opts;
 
@@ -221,6 +226,25 @@ int rlhf_debug_snapshot(rlhf_ctx* ctx, rlhf_snapshot* out);
 
 /* Wait for all work enqueued so far on both streams. */
 int rlhf_sync(rlhf_ctx* ctx);
+
+/* Measurement hook (for benchmarks, not part of the method): between begin and end, every
+ * sample_every-th launch of each kernel class is bracketed by two HIP events on the stream it
+ * runs on.  Classes: 0 = projections of the decode step (weight-streaming, HBM-bound regime of
+ * Section 4.2), 1 = projections of prefill / scoring passes (Section 2.1 inference forward),
+ * 2 = paged decode attention, 3 = packed causal attention.  Bytes and flops are algorithmic:
+ * operands read once, results written once, 2 flops per multiply-add.  rlhf_profile_end drains
+ * both streams and fills out[4]. */
+typedef struct rlhf_kernel_profile {
+    int64_t launches;              /* launches of the class between begin and end             */
+    int64_t sampled;               /* of which were timed                                     */
+    double sampled_ms;             /* summed event time of the timed launches                 */
+    double sampled_bytes;          /* algorithmic bytes of the timed launches                 */
+    double sampled_flops;
+    double total_bytes;            /* algorithmic bytes of all launches                       */
+    double total_flops;
+} rlhf_kernel_profile;
+int rlhf_profile_begin(rlhf_ctx* ctx, int32_t sample_every);
+int rlhf_profile_end(rlhf_ctx* ctx, rlhf_kernel_profile* out /* [4] */);
 
 #ifdef __cplusplus
 }

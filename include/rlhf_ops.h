@@ -5,7 +5,7 @@
  * All pointers are DEVICE pointers owned by the caller; `stream` is a hipStream_t (NULL =
  * the default stream).  Calls enqueue work and return without waiting.  Return values are
  * rlhf_status codes (0 = OK, RLHF_EINVAL for unsupported shapes, RLHF_EDEVICE for a failed
- * launch).  dtype is an rlhf_dtype and selects the storage type of A/W/q/k/v/out.
+ * launch).  dtype is an rlhf_dtype: the storage type of weights and of the KV pool.
  */
 #ifndef RLHF_OPS_H
 #define RLHF_OPS_H
@@ -18,13 +18,14 @@ extern "C" {
 
 /* Linear projection y = W x of a decoder block (the matrix work of both the memory-bound
  * decoding phase, Section 4.2, and the prefill-like inference forward, Section 2.1):
- * C[s][m][n] = sum over the s-th K range of A[m][k] * W[n][k].  A [M,K], W [N,K] row-major in
- * dtype; C float32 [nsplit][M][N]; the caller sums the nsplit partial planes.  K must be a
- * multiple of 8 (bf16) or 4 (fp32).  rlhf_op_gemm_nsplit returns the split the stage itself
- * would choose for this shape, at most max_split. */
+ * C[s][m][n] = sum over the s-th K range of A[m][k] * W[n][k].  W [N,K] row-major in dtype;
+ * A [M,K] in dtype, or (act_half != 0, bf16 weights only) in IEEE half, the activation type
+ * of prefill / scoring passes; C float32 [nsplit][M][N]; the caller sums the nsplit partial
+ * planes.  K must be a multiple of 8 (bf16) or 4 (fp32).  rlhf_op_gemm_nsplit returns the
+ * split the stage itself would choose for this shape, at most max_split. */
 int rlhf_op_gemm_nsplit(int dtype, int M, int N, int K, int max_split);
-int rlhf_op_gemm(int dtype, const void* A, const void* W, float* C, int M, int N, int K, int nsplit,
-                 void* stream);
+int rlhf_op_gemm(int dtype, int act_half, const void* A, const void* W, float* C, int M, int N, int K,
+                 int nsplit, void* stream);
 
 /* Decode attention of one step (Section 2.1, decoding phase): row r holds one query
  * [n_q_heads * head_dim] and attends to the ctx_len[r] cached tokens of the sample whose
@@ -38,9 +39,10 @@ int rlhf_op_paged_decode_attention(int dtype, const void* q, const void* pool, c
                                    void* stream);
 
 /* Packed variable-length causal attention of the prefill / inference forward (Section 2.1):
- * q [T, n_q_heads*head_dim], k, v [T, n_kv_heads*head_dim]; row r belongs to the sequence that
- * starts at row row_start[r] and is its row_pos[r]-th token. */
-int rlhf_op_varlen_attention(int dtype, const void* q, const void* k, const void* v,
+ * float32 q [T, n_q_heads*head_dim], k, v [T, n_kv_heads*head_dim]; row r belongs to the
+ * sequence that starts at row row_start[r] and is its row_pos[r]-th token.  out is IEEE half
+ * (out_half != 0) or float32. */
+int rlhf_op_varlen_attention(int out_half, const float* q, const float* k, const float* v,
                              const int32_t* row_start, const int32_t* row_pos, void* out, int rows,
                              int n_q_heads, int n_kv_heads, int head_dim, void* stream);
 

@@ -55,7 +55,8 @@ class rlhf_step_info(C.Structure):
 class rlhf_stage_opts(C.Structure):
     _fields_ = [("fused", C.c_int32), ("R_t", C.c_int32), ("score_chunk_tokens", C.c_int32),
                 ("role_mask", C.c_uint32), ("trace_active", C.c_void_p), ("trace_decoded", C.c_void_p),
-                ("trace_step_ms", C.c_void_p), ("trace_cap", C.c_int32)]
+                ("trace_step_ms", C.c_void_p), ("trace_step_bytes", C.c_void_p),
+                ("trace_prefill_tokens", C.c_void_p), ("trace_cap", C.c_int32)]
 
 
 class rlhf_stage_stats(C.Structure):
@@ -77,6 +78,14 @@ class rlhf_snapshot(C.Structure):
                                              "retired", "batch_offsets", "batch_step")]
                 + [(n, C.c_int32) for n in ("cap_samples", "cap_max_pages", "cap_pool_pages")])
 
+
+class rlhf_kernel_profile(C.Structure):
+    _fields_ = [("launches", C.c_int64), ("sampled", C.c_int64), ("sampled_ms", C.c_double),
+                ("sampled_bytes", C.c_double), ("sampled_flops", C.c_double), ("total_bytes", C.c_double),
+                ("total_flops", C.c_double)]
+
+
+KERNEL_CLASSES = ("gemm_decode", "gemm_batch", "attn_decode", "attn_batch")
 
 _lib = None
 
@@ -104,12 +113,15 @@ def lib() -> C.CDLL:
         L.rlhf_get_results.argtypes = [vp, C.POINTER(rlhf_results)]
         L.rlhf_debug_snapshot.argtypes = [vp, C.POINTER(rlhf_snapshot)]
         L.rlhf_sync.argtypes = [vp]
+        L.rlhf_profile_begin.argtypes = [vp, i32]
+        L.rlhf_profile_end.argtypes = [vp, C.POINTER(rlhf_kernel_profile)]
         L.rlhf_op_gemm_nsplit.argtypes = [C.c_int] * 5
-        L.rlhf_op_gemm.argtypes = [C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp]
+        L.rlhf_op_gemm.argtypes = [C.c_int, C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp]
         L.rlhf_op_paged_decode_attention.argtypes = [C.c_int, vp, vp, vp, C.c_int, vp, vp, vp, vp, vp] + [C.c_int] * 7 + [vp]
         L.rlhf_op_varlen_attention.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp] + [C.c_int] * 4 + [vp]
         for name in ("rlhf_create", "rlhf_load_weights", "rlhf_submit", "rlhf_generate_step", "rlhf_retire",
                      "rlhf_score", "rlhf_run_stage", "rlhf_get_results", "rlhf_debug_snapshot", "rlhf_sync",
+                     "rlhf_profile_begin", "rlhf_profile_end",
                      "rlhf_op_gemm_nsplit", "rlhf_op_gemm", "rlhf_op_paged_decode_attention",
                      "rlhf_op_varlen_attention"):
             getattr(L, name).restype = C.c_int
@@ -195,11 +207,13 @@ def rlhf_score(ctx, sample_ids: Sequence[int], role_mask: int, on_score_stream: 
 def rlhf_run_stage(ctx, fused: bool, R_t: int, score_chunk_tokens: int, role_mask: int,
                    trace_cap: int = 0, trace_time: bool = False):
     """Returns (rlhf_stage_stats, trace dict or None)."""
-    o = rlhf_stage_opts(int(fused), R_t, score_chunk_tokens, role_mask, None, None, None, 0)
+    o = rlhf_stage_opts(int(fused), R_t, score_chunk_tokens, role_mask, None, None, None, None, None, 0)
     tr = None
     if trace_cap > 0:
-        tr = {"active": np.zeros(trace_cap, np.int32), "decoded": np.zeros(trace_cap, np.int32)}
+        tr = {"active": np.zeros(trace_cap, np.int32), "decoded": np.zeros(trace_cap, np.int32),
+              "step_bytes": np.zeros(trace_cap, np.int64), "prefill_tokens": np.zeros(trace_cap, np.int32)}
         o.trace_active, o.trace_decoded, o.trace_cap = _p(tr["active"]), _p(tr["decoded"]), trace_cap
+        o.trace_step_bytes, o.trace_prefill_tokens = _p(tr["step_bytes"]), _p(tr["prefill_tokens"])
         if trace_time:
             tr["step_ms"] = np.zeros(trace_cap, np.float32)
             o.trace_step_ms = _p(tr["step_ms"])
@@ -258,6 +272,17 @@ def rlhf_sync(ctx) -> None:
     _check(ctx, lib().rlhf_sync(ctx))
 
 
+def rlhf_profile_begin(ctx, sample_every: int = 1) -> None:
+    _check(ctx, lib().rlhf_profile_begin(ctx, sample_every))
+
+
+def rlhf_profile_end(ctx) -> Dict[str, dict]:
+    arr = (rlhf_kernel_profile * 4)()
+    _check(ctx, lib().rlhf_profile_end(ctx, arr))
+    return {name: {f: getattr(arr[k], f) for f, _ in rlhf_kernel_profile._fields_}
+            for k, name in enumerate(KERNEL_CLASSES)}
+
+
 # ------------------------------------------------------------------------- kernel-level API
 
 def _dt(t) -> int:
@@ -280,12 +305,15 @@ def rlhf_op_gemm_nsplit(dtype: int, M: int, N: int, K: int, max_split: int) -> i
 
 
 def rlhf_op_gemm(A, W, C_out, nsplit: int) -> None:
-    """A [M,K], W [N,K] device tensors (bf16 or fp32), C_out float32 [nsplit, M, N]; on torch's
-    current stream."""
+    """W [N,K] (bf16 or fp32), A [M,K] of W's dtype or float16 (with bf16 W), C_out float32
+    [nsplit, M, N]; on torch's current stream."""
+    import torch
     M, K = A.shape
     N = W.shape[0]
     assert W.shape[1] == K and tuple(C_out.shape) == (nsplit, M, N) and A.is_contiguous() and W.is_contiguous()
-    _op_check(lib().rlhf_op_gemm(_dt(A), A.data_ptr(), W.data_ptr(), C_out.data_ptr(), M, N, K, nsplit,
+    half = A.dtype == torch.float16
+    assert half or A.dtype == W.dtype
+    _op_check(lib().rlhf_op_gemm(_dt(W), int(half), A.data_ptr(), W.data_ptr(), C_out.data_ptr(), M, N, K, nsplit,
                                  _stream_ptr()), "rlhf_op_gemm")
 
 
@@ -300,6 +328,9 @@ def rlhf_op_paged_decode_attention(q, pool, page_table, row_sample, ctx_len, out
 
 
 def rlhf_op_varlen_attention(q, k, v, row_start, row_pos, out, n_q_heads: int, n_kv_heads: int, head_dim: int):
-    _op_check(lib().rlhf_op_varlen_attention(_dt(q), q.data_ptr(), k.data_ptr(), v.data_ptr(), row_start.data_ptr(),
+    """float32 q, k, v; out float16 or float32."""
+    import torch
+    assert q.dtype == k.dtype == v.dtype == torch.float32 and out.dtype in (torch.float16, torch.float32)
+    _op_check(lib().rlhf_op_varlen_attention(int(out.dtype == torch.float16), q.data_ptr(), k.data_ptr(), v.data_ptr(), row_start.data_ptr(),
                                              row_pos.data_ptr(), out.data_ptr(), q.shape[0], n_q_heads, n_kv_heads,
                                              head_dim, _stream_ptr()), "rlhf_op_varlen_attention")

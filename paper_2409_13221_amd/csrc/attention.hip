@@ -270,13 +270,14 @@ hipError_t launch_decode_attn(hipStream_t st, int dtype, const void* q, const vo
 }
 
 // ------------------------------------------------------------- prefill / scoring (v1)
-template <typename T, int HD, int G>
-__global__ __launch_bounds__(256) void k_prefill_attn(const T* __restrict__ q,
-                                                      const T* __restrict__ k,
-                                                      const T* __restrict__ v,
+template <typename TO, int HD, int G>
+__global__ __launch_bounds__(256) void k_prefill_attn(const float* __restrict__ q,
+                                                      const float* __restrict__ k,
+                                                      const float* __restrict__ v,
                                                       const int* __restrict__ row_start,
                                                       const int* __restrict__ row_pos,
-                                                      T* __restrict__ out, int Hkv) {
+                                                      TO* __restrict__ out, int Hkv) {
+    typedef float T;
     __shared__ float s_m[4 * G], s_l[4 * G];
     __shared__ float s_acc[4 * G * HD];
     const int r = blockIdx.x, kh = blockIdx.y;
@@ -320,28 +321,27 @@ __global__ __launch_bounds__(256) void k_prefill_attn(const T* __restrict__ q,
             lt += s_l[w * G + g] * f;
             at += s_acc[(w * G + g) * HD + e] * f;
         }
-        out[((size_t)r * Hq + kh * G + g) * HD + e] = from_f32<T>(at / lt);
+        out[((size_t)r * Hq + kh * G + g) * HD + e] = from_f32<TO>(at / lt);
     }
 }
 
-hipError_t launch_prefill_attn(hipStream_t st, int dtype, const void* q, const void* k,
-                               const void* v, const int* row_start, const int* row_pos, void* out,
+hipError_t launch_prefill_attn(hipStream_t st, int odt, const float* q, const float* k,
+                               const float* v, const int* row_start, const int* row_pos, void* out,
                                int rows, const Dims& dm) {
     if (rows <= 0) return hipSuccess;
     const int G = dm.n_q_heads / dm.n_kv_heads, hd = dm.head_dim;
     dim3 grid(rows, dm.n_kv_heads);
 #define RLHF_PRE(TT, HD_, G_)                                                                      \
     do {                                                                                           \
-        k_prefill_attn<TT, HD_, G_><<<grid, 256, 0, st>>>((const TT*)q, (const TT*)k, (const TT*)v, \
-                                                          row_start, row_pos, (TT*)out,            \
+        k_prefill_attn<TT, HD_, G_><<<grid, 256, 0, st>>>(q, k, v, row_start, row_pos, (TT*)out,   \
                                                           dm.n_kv_heads);                          \
         return hipGetLastError();                                                                  \
     } while (0)
-    if (dtype == kBF16) {
-        if (hd == 128 && G == 1) RLHF_PRE(bf16_t, 128, 1);
-        if (hd == 128 && G == 8) RLHF_PRE(bf16_t, 128, 8);
-        if (hd == 64 && G == 1) RLHF_PRE(bf16_t, 64, 1);
-    } else {
+    if (odt == kF16) {
+        if (hd == 128 && G == 1) RLHF_PRE(f16_t, 128, 1);
+        if (hd == 128 && G == 8) RLHF_PRE(f16_t, 128, 8);
+        if (hd == 64 && G == 1) RLHF_PRE(f16_t, 64, 1);
+    } else if (odt == kF32) {
         if (hd == 128 && G == 1) RLHF_PRE(float, 128, 1);
         if (hd == 64 && G == 1) RLHF_PRE(float, 64, 1);
     }

@@ -6,7 +6,10 @@
 namespace rlhf {
 
 typedef uint16_t bf16_t;  // raw bfloat16 bits
+typedef _Float16 f16_t;   // IEEE half: activations of prefill / scoring passes
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef __fp16 fp16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
@@ -27,7 +30,10 @@ template <typename T> __device__ __forceinline__ float to_f32(T x);
 template <> __device__ __forceinline__ float to_f32<float>(float x) { return x; }
 template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t x) { return bf16_to_f32(x); }
 
+template <> __device__ __forceinline__ float to_f32<f16_t>(f16_t x) { return (float)x; }
+
 template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ f16_t from_f32<f16_t>(float x) { return (f16_t)x; }
 template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return f32_to_bf16(x); }
 
@@ -47,7 +53,19 @@ template <> __device__ __forceinline__ void load8<float>(const float* p, float (
     o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
 }
 
+template <> __device__ __forceinline__ void load8<f16_t>(const f16_t* p, float (&o)[8]) {
+    f16x8_t r = *reinterpret_cast<const f16x8_t*>(p);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (float)r[e];
+}
+
 template <typename T> __device__ __forceinline__ void store8(T* p, const float (&v)[8]);
+template <> __device__ __forceinline__ void store8<f16_t>(f16_t* p, const float (&v)[8]) {
+    f16x8_t r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = (f16_t)v[e];
+    *reinterpret_cast<f16x8_t*>(p) = r;
+}
 template <> __device__ __forceinline__ void store8<bf16_t>(bf16_t* p, const float (&v)[8]) {
     uint4 r;
     r.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
@@ -59,6 +77,13 @@ template <> __device__ __forceinline__ void store8<bf16_t>(bf16_t* p, const floa
 template <> __device__ __forceinline__ void store8<float>(float* p, const float (&v)[8]) {
     *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
     *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+
+// Two packed bf16 -> two packed f16.  Exact for magnitudes in half's normal range (8 significant
+// bits fit in 11); below 2^-14 the value lands on half's subnormal grid (absolute error < 2^-24).
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t x) {
+    fp16x2_t h = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(x << 16), __uint_as_float(x & 0xFFFF0000u));
+    return *reinterpret_cast<uint32_t*>(&h);
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

@@ -86,13 +86,15 @@ __global__ __launch_bounds__(256) void k_rmsnorm(float* __restrict__ h, const fl
     }
 }
 
-hipError_t launch_rmsnorm(hipStream_t st, int dtype, float* h, const float* part, int nsplit,
+hipError_t launch_rmsnorm(hipStream_t st, int adt, float* h, const float* part, int nsplit,
                           size_t sstride, const int* row_idx, const float* g, void* xn, int rows,
                           int d, float eps) {
     if (rows <= 0) return hipSuccess;
     if (d > 256 * 8 * kRmsMaxIter || d % 8) return hipErrorInvalidValue;
-    if (dtype == kBF16)
+    if (adt == kBF16)
         k_rmsnorm<bf16_t><<<rows, 256, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (bf16_t*)xn, d, eps);
+    else if (adt == kF16)
+        k_rmsnorm<f16_t><<<rows, 256, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (f16_t*)xn, d, eps);
     else
         k_rmsnorm<float><<<rows, 256, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (float*)xn, d, eps);
     return hipGetLastError();
@@ -101,13 +103,13 @@ hipError_t launch_rmsnorm(hipStream_t st, int dtype, float* h, const float* part
 // ---------------------------------------------------------------- rotary + KV-cache append
 // rope_table: [max_pos][hd/2][2] = (cos, sin) of pos * base^(-2k/hd), computed in double on
 // the host.  Pair (k, k + hd/2) is rotated.
-template <typename T>
+template <typename T, typename TP>
 __global__ __launch_bounds__(256) void k_rope_kv(const float* __restrict__ qkv, int nsplit,
                                                  size_t sstride, const int* __restrict__ pos,
                                                  const int* __restrict__ kv_dst,
                                                  const float* __restrict__ rope_table,
                                                  T* __restrict__ q_out, T* __restrict__ k_out,
-                                                 T* __restrict__ v_out, T* __restrict__ pool,
+                                                 T* __restrict__ v_out, TP* __restrict__ pool,
                                                  int layer, Dims dm) {
     const int r = blockIdx.x;
     const int hd = dm.head_dim, half = hd >> 1;
@@ -116,8 +118,8 @@ __global__ __launch_bounds__(256) void k_rope_kv(const float* __restrict__ qkv, 
     const float* x = qkv + (size_t)r * qkv_w;
     const float* tab = rope_table + (size_t)pos[r] * hd;  // hd/2 pairs of (cos, sin)
     const int slot = (pool && kv_dst) ? kv_dst[r] : -1;
-    T* pk = nullptr;
-    T* pv = nullptr;
+    TP* pk = nullptr;
+    TP* pv = nullptr;
     if (slot >= 0) {
         const int pt = dm.page_tokens;
         const size_t page = slot / pt, off = slot % pt;
@@ -135,19 +137,19 @@ __global__ __launch_bounds__(256) void k_rope_kv(const float* __restrict__ qkv, 
             b += x[s * sstride + col + half];
         }
         const float c = tab[2 * k], sn = tab[2 * k + 1];
-        const T ra = from_f32<T>(a * c - b * sn), rb = from_f32<T>(a * sn + b * c);
+        const float fa = a * c - b * sn, fb = a * sn + b * c;
         if (hh < Hq) {
-            q_out[(size_t)r * Hq * hd + col] = ra;
-            q_out[(size_t)r * Hq * hd + col + half] = rb;
+            q_out[(size_t)r * Hq * hd + col] = from_f32<T>(fa);
+            q_out[(size_t)r * Hq * hd + col + half] = from_f32<T>(fb);
         } else {
             const int kh = hh - Hq;
             if (k_out) {
-                k_out[(size_t)r * Hkv * hd + kh * hd + k] = ra;
-                k_out[(size_t)r * Hkv * hd + kh * hd + k + half] = rb;
+                k_out[(size_t)r * Hkv * hd + kh * hd + k] = from_f32<T>(fa);
+                k_out[(size_t)r * Hkv * hd + kh * hd + k + half] = from_f32<T>(fb);
             }
             if (pk) {
-                pk[(size_t)kh * dm.page_tokens * hd + k] = ra;
-                pk[(size_t)kh * dm.page_tokens * hd + k + half] = rb;
+                pk[(size_t)kh * dm.page_tokens * hd + k] = from_f32<TP>(fa);
+                pk[(size_t)kh * dm.page_tokens * hd + k + half] = from_f32<TP>(fb);
             }
         }
     }
@@ -155,28 +157,33 @@ __global__ __launch_bounds__(256) void k_rope_kv(const float* __restrict__ qkv, 
     for (int i = threadIdx.x; i < Hkv * hd; i += 256) {
         float a = x[vbase + i];
         for (int s = 1; s < nsplit; ++s) a += x[s * sstride + vbase + i];
-        const T t = from_f32<T>(a);
-        if (v_out) v_out[(size_t)r * Hkv * hd + i] = t;
+        if (v_out) v_out[(size_t)r * Hkv * hd + i] = from_f32<T>(a);
         if (pv) {
             const int kh = i / hd, e = i - kh * hd;
-            pv[(size_t)kh * dm.page_tokens * hd + e] = t;
+            pv[(size_t)kh * dm.page_tokens * hd + e] = from_f32<TP>(a);
         }
     }
 }
 
-hipError_t launch_rope_kv(hipStream_t st, int dtype, const float* qkv, int nsplit, size_t sstride,
-                          const int* pos, const int* kv_dst, const float* rope_table, void* q_out,
-                          void* k_out, void* v_out, void* pool, int layer, int rows,
+hipError_t launch_rope_kv(hipStream_t st, int qdt, int pdt, const float* qkv, int nsplit,
+                          size_t sstride, const int* pos, const int* kv_dst, const float* rope_table,
+                          void* q_out, void* k_out, void* v_out, void* pool, int layer, int rows,
                           const Dims& dm) {
     if (rows <= 0) return hipSuccess;
-    if (dtype == kBF16)
-        k_rope_kv<bf16_t><<<rows, 256, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
-                                                (bf16_t*)q_out, (bf16_t*)k_out, (bf16_t*)v_out,
-                                                (bf16_t*)pool, layer, dm);
+    if (qdt == kBF16 && pdt == kBF16)
+        k_rope_kv<bf16_t, bf16_t><<<rows, 256, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
+                                                        (bf16_t*)q_out, (bf16_t*)k_out, (bf16_t*)v_out,
+                                                        (bf16_t*)pool, layer, dm);
+    else if (qdt == kF32 && pdt == kBF16)
+        k_rope_kv<float, bf16_t><<<rows, 256, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
+                                                       (float*)q_out, (float*)k_out, (float*)v_out,
+                                                       (bf16_t*)pool, layer, dm);
+    else if (qdt == kF32 && pdt == kF32)
+        k_rope_kv<float, float><<<rows, 256, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
+                                                      (float*)q_out, (float*)k_out, (float*)v_out,
+                                                      (float*)pool, layer, dm);
     else
-        k_rope_kv<float><<<rows, 256, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
-                                               (float*)q_out, (float*)k_out, (float*)v_out,
-                                               (float*)pool, layer, dm);
+        return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
@@ -209,14 +216,16 @@ __global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ gu, in
     }
 }
 
-hipError_t launch_swiglu(hipStream_t st, int dtype, const float* gu, int nsplit, size_t sstride,
+hipError_t launch_swiglu(hipStream_t st, int adt, const float* gu, int nsplit, size_t sstride,
                          void* act, int rows, int ffn) {
     if (rows <= 0) return hipSuccess;
     if (ffn % 8) return hipErrorInvalidValue;
     const size_t total = (size_t)rows * (ffn / 8);
     const int grid = (int)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
-    if (dtype == kBF16)
+    if (adt == kBF16)
         k_swiglu<bf16_t><<<grid, 256, 0, st>>>(gu, nsplit, sstride, (bf16_t*)act, rows, ffn);
+    else if (adt == kF16)
+        k_swiglu<f16_t><<<grid, 256, 0, st>>>(gu, nsplit, sstride, (f16_t*)act, rows, ffn);
     else
         k_swiglu<float><<<grid, 256, 0, st>>>(gu, nsplit, sstride, (float*)act, rows, ffn);
     return hipGetLastError();
@@ -322,8 +331,8 @@ hipError_t launch_gather_lp(hipStream_t st, const float* logits, int nsplit, siz
 
 // ------------------------------------------------------------------- value / reward head
 // One wave per row: out[out_dst[r]] = <xn[r], w>.
-template <typename T>
-__global__ __launch_bounds__(256) void k_head_dot(const T* __restrict__ xn, const T* __restrict__ w,
+template <typename T, typename TW>
+__global__ __launch_bounds__(256) void k_head_dot(const T* __restrict__ xn, const TW* __restrict__ w,
                                                   int rows, int d, float* __restrict__ out,
                                                   const int* __restrict__ out_dst) {
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -333,7 +342,7 @@ __global__ __launch_bounds__(256) void k_head_dot(const T* __restrict__ xn, cons
     for (int i = lane * 8; i < d; i += 64 * 8) {
         float a[8], b[8];
         load8<T>(xn + (size_t)r * d + i, a);
-        load8<T>(w + i, b);
+        load8<TW>(w + i, b);
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc += a[e] * b[e];
     }
@@ -341,14 +350,18 @@ __global__ __launch_bounds__(256) void k_head_dot(const T* __restrict__ xn, cons
     if (lane == 0) out[out_dst[r]] = acc;
 }
 
-hipError_t launch_head_dot(hipStream_t st, int dtype, const void* xn, const void* w, int rows,
-                           int d, float* out, const int* out_dst) {
+hipError_t launch_head_dot(hipStream_t st, int adt, int wdt, const void* xn, const void* w,
+                           int rows, int d, float* out, const int* out_dst) {
     if (rows <= 0) return hipSuccess;
     const int grid = (rows + 3) / 4;
-    if (dtype == kBF16)
-        k_head_dot<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)xn, (const bf16_t*)w, rows, d, out, out_dst);
+    if (adt == kBF16 && wdt == kBF16)
+        k_head_dot<bf16_t, bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)xn, (const bf16_t*)w, rows, d, out, out_dst);
+    else if (adt == kF16 && wdt == kBF16)
+        k_head_dot<f16_t, bf16_t><<<grid, 256, 0, st>>>((const f16_t*)xn, (const bf16_t*)w, rows, d, out, out_dst);
+    else if (adt == kF32 && wdt == kF32)
+        k_head_dot<float, float><<<grid, 256, 0, st>>>((const float*)xn, (const float*)w, rows, d, out, out_dst);
     else
-        k_head_dot<float><<<grid, 256, 0, st>>>((const float*)xn, (const float*)w, rows, d, out, out_dst);
+        return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

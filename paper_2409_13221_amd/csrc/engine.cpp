@@ -99,6 +99,21 @@ struct Workspace {
     std::vector<void*> owned;
 };
 
+// Optional per-kernel-class timing: every `every`-th launch of a class is bracketed by two
+// events on its stream; algorithmic bytes / flops of the sampled launches are summed beside.
+enum KClass { kGemmDecode = 0, kGemmBatch = 1, kAttnDecode = 2, kAttnBatch = 3, kClassCount = 4 };
+
+struct Profiler {
+    bool on = false;
+    int every = 1;
+    static constexpr size_t kMaxSamples = 1 << 15;
+    struct Rec { hipEvent_t a, b; int cls; double bytes, flops; };
+    std::vector<Rec> recs;                 // recs[0..n_used) are live; events are reused across runs
+    size_t n_used = 0;
+    int64_t launches[kClassCount] = {};
+    double tot_bytes[kClassCount] = {}, tot_flops[kClassCount] = {};
+};
+
 struct Sample {
     int P = 0, max_new = 0, target = 0, reserve = 0;
     int ctx = 0, gen_len = 0, admit_step = -1;
@@ -138,6 +153,7 @@ struct rlhf_ctx {
 
     Workspace ws_dec, ws_pre, ws_score;
     MetaRing meta_dec, meta_pre, meta_score;
+    Profiler prof;
 
     // ---- stage state (host integers)
     int N = 0;
@@ -176,6 +192,45 @@ struct rlhf_ctx {
 
 namespace {
 
+// Run `launch` (a callable returning hipError_t), timing it if this launch is sampled.
+template <typename F>
+hipError_t profiled(rlhf_ctx* c, hipStream_t st, int cls, double bytes, double flops, F&& launch) {
+    Profiler& p = c->prof;
+    if (!p.on) return launch();
+    const int64_t k = p.launches[cls]++;
+    p.tot_bytes[cls] += bytes;
+    p.tot_flops[cls] += flops;
+    if (k % p.every != 0 || p.n_used >= Profiler::kMaxSamples) return launch();
+    if (p.n_used == p.recs.size()) {
+        Profiler::Rec r{};
+        hipError_t e = hipEventCreate(&r.a);
+        if (e != hipSuccess) return e;
+        e = hipEventCreate(&r.b);
+        if (e != hipSuccess) return e;
+        p.recs.push_back(r);
+    }
+    Profiler::Rec& r = p.recs[p.n_used++];
+    r.cls = cls;
+    r.bytes = bytes;
+    r.flops = flops;
+    hipError_t e = hipEventRecord(r.a, st);
+    if (e != hipSuccess) return e;
+    e = launch();
+    if (e != hipSuccess) return e;
+    return hipEventRecord(r.b, st);
+}
+
+// Activation type of a pass: the decode step keeps the model's storage type; prefill / scoring
+// passes of a bf16 model feed the matrix units half-precision activations.
+int act_type(const rlhf_ctx* c, bool batch) { return (batch && c->dtype == kBF16) ? kF16 : c->dtype; }
+
+hipError_t gemm_profiled(rlhf_ctx* c, hipStream_t st, int cls, int adt, const void* A, const void* W, float* C,
+                         int M, int N, int K, int nsplit) {
+    const double bytes = ((double)N * K + (double)M * K) * c->esz + (double)M * N * 4;
+    return profiled(c, st, cls, bytes, 2.0 * M * N * K,
+                    [&] { return launch_gemm(st, c->dtype, adt, A, W, C, M, N, K, nsplit); });
+}
+
 template <typename T>
 hipError_t dev_alloc(Workspace* ws, T** p, size_t n_bytes) {
     void* q = nullptr;
@@ -204,7 +259,7 @@ int alloc_workspace(rlhf_ctx* c, Workspace& ws, int rows, bool decode) {
     HIPCK(c, dev_alloc(&ws, &ws.h, rows * d * 4));
     HIPCK(c, dev_alloc(&ws, (char**)&ws.xn, rows * d * es));
     HIPCK(c, dev_alloc(&ws, &ws.part, ws.part_cap * 4));
-    HIPCK(c, dev_alloc(&ws, (char**)&ws.q, rows * qd * es));
+    HIPCK(c, dev_alloc(&ws, (char**)&ws.q, rows * qd * (decode ? es : 4)));   // batch passes: float q/k/v
     HIPCK(c, dev_alloc(&ws, (char**)&ws.attn, rows * qd * es));
     HIPCK(c, dev_alloc(&ws, (char**)&ws.act, rows * f * es));
     HIPCK(c, dev_alloc(&ws, (char**)&ws.xsel, rows * d * es));
@@ -212,8 +267,8 @@ int alloc_workspace(rlhf_ctx* c, Workspace& ws, int rows, bool decode) {
         HIPCK(c, dev_alloc(&ws, &ws.attn_acc, ws.attn_slots * m.head_dim * 4));
         HIPCK(c, dev_alloc(&ws, &ws.attn_ml, ws.attn_slots * 2 * 4));
     } else {
-        HIPCK(c, dev_alloc(&ws, (char**)&ws.k, rows * kvd * es));
-        HIPCK(c, dev_alloc(&ws, (char**)&ws.v, rows * kvd * es));
+        HIPCK(c, dev_alloc(&ws, (char**)&ws.k, rows * kvd * 4));
+        HIPCK(c, dev_alloc(&ws, (char**)&ws.v, rows * kvd * 4));
         HIPCK(c, dev_alloc(&ws, &ws.logits, (size_t)ws.logit_rows * V * 4));
     }
     return RLHF_OK;
@@ -235,7 +290,7 @@ int nsplit_for(const rlhf_ctx* c, const Workspace& ws, int M, int N, int K) {
     return gemm_choose_nsplit(c->dtype, M, N, K, cap);
 }
 
-enum AttnMode { kAttnDecode, kAttnBatch };
+enum AttnMode { kModeDecode, kModeBatch };
 
 struct PassMeta {         // device pointers into a MetaRing arena
     const int* tok_idx = nullptr;
@@ -244,6 +299,7 @@ struct PassMeta {         // device pointers into a MetaRing arena
     const int* row_sample = nullptr;   // decode
     const int* ctx_len = nullptr;      // decode
     const int* row_start = nullptr;    // batch
+    double attn_bytes = 0, attn_flops = 0;   // algorithmic, per layer (for the profiler)
 };
 
 // Embedding and all decoder layers over `rows` rows.  On return ws.h holds the residual
@@ -255,37 +311,44 @@ int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
     const rlhf_model_cfg& m = c->mc;
     const int d = m.d_model, qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
     const int qkv_w = qd + 2 * kvd, f = m.ffn, es = c->esz, dt = c->dtype;
+    const int gcls = mode == kModeDecode ? kGemmDecode : kGemmBatch;
+    const int adt = act_type(c, mode == kModeBatch);
+    const int qdt = mode == kModeBatch ? kF32 : dt;
     HIPCK(c, launch_embed(st, dt, c->d_tokens, pm.tok_idx, w.embed, ws.h, rows, d, m.vocab));
     int pns = 0;
     size_t pstride = 0;
     for (int l = 0; l < m.n_layers; ++l) {
-        HIPCK(c, launch_rmsnorm(st, dt, ws.h, ws.part, pns, pstride, nullptr, w.g_attn + (size_t)l * d,
+        HIPCK(c, launch_rmsnorm(st, adt, ws.h, ws.part, pns, pstride, nullptr, w.g_attn + (size_t)l * d,
                                 ws.xn, rows, d, m.rms_eps));
         int ns = nsplit_for(c, ws, rows, qkv_w, d);
-        HIPCK(c, launch_gemm(st, dt, ws.xn, layer_ptr(w.wqkv, l, qkv_w, d, es), ws.part, rows, qkv_w, d, ns));
-        HIPCK(c, launch_rope_kv(st, dt, ws.part, ns, (size_t)rows * qkv_w, pm.pos, pm.kv_dst, c->d_rope,
-                                ws.q, mode == kAttnBatch ? ws.k : nullptr,
-                                mode == kAttnBatch ? ws.v : nullptr, pm.kv_dst ? c->pool : nullptr, l,
+        HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.xn, layer_ptr(w.wqkv, l, qkv_w, d, es), ws.part, rows, qkv_w, d, ns));
+        HIPCK(c, launch_rope_kv(st, qdt, dt, ws.part, ns, (size_t)rows * qkv_w, pm.pos, pm.kv_dst, c->d_rope,
+                                ws.q, mode == kModeBatch ? ws.k : nullptr,
+                                mode == kModeBatch ? ws.v : nullptr, pm.kv_dst ? c->pool : nullptr, l,
                                 rows, c->dm));
-        if (mode == kAttnDecode) {
-            HIPCK(c, launch_decode_attn(st, dt, ws.q, c->pool, c->d_page_table, c->max_pages,
-                                        pm.row_sample, pm.ctx_len, ws.attn, ws.attn_acc, ws.attn_ml,
-                                        rows, l, attn_nsplit, c->dm));
+        if (mode == kModeDecode) {
+            HIPCK(c, profiled(c, st, kAttnDecode, pm.attn_bytes, pm.attn_flops, [&] {
+                return launch_decode_attn(st, dt, ws.q, c->pool, c->d_page_table, c->max_pages, pm.row_sample,
+                                          pm.ctx_len, ws.attn, ws.attn_acc, ws.attn_ml, rows, l, attn_nsplit,
+                                          c->dm);
+            }));
         } else {
-            HIPCK(c, launch_prefill_attn(st, dt, ws.q, ws.k, ws.v, pm.row_start, pm.pos, ws.attn, rows,
-                                         c->dm));
+            HIPCK(c, profiled(c, st, kAttnBatch, pm.attn_bytes, pm.attn_flops, [&] {
+                return launch_prefill_attn(st, adt, (const float*)ws.q, (const float*)ws.k, (const float*)ws.v,
+                                           pm.row_start, pm.pos, ws.attn, rows, c->dm);
+            }));
         }
         ns = nsplit_for(c, ws, rows, d, qd);
-        HIPCK(c, launch_gemm(st, dt, ws.attn, layer_ptr(w.wo, l, d, qd, es), ws.part, rows, d, qd, ns));
-        HIPCK(c, launch_rmsnorm(st, dt, ws.h, ws.part, ns, (size_t)rows * d, nullptr,
+        HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.attn, layer_ptr(w.wo, l, d, qd, es), ws.part, rows, d, qd, ns));
+        HIPCK(c, launch_rmsnorm(st, adt, ws.h, ws.part, ns, (size_t)rows * d, nullptr,
                                 w.g_mlp + (size_t)l * d, ws.xn, rows, d, m.rms_eps));
         ns = nsplit_for(c, ws, rows, 2 * f, d);
-        HIPCK(c, launch_gemm(st, dt, ws.xn, layer_ptr(w.w_gate_up, l, 2 * (size_t)f, d, es), ws.part, rows,
-                             2 * f, d, ns));
-        HIPCK(c, launch_swiglu(st, dt, ws.part, ns, (size_t)rows * 2 * f, ws.act, rows, f));
+        HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.xn, layer_ptr(w.w_gate_up, l, 2 * (size_t)f, d, es), ws.part, rows,
+                               2 * f, d, ns));
+        HIPCK(c, launch_swiglu(st, adt, ws.part, ns, (size_t)rows * 2 * f, ws.act, rows, f));
         pns = nsplit_for(c, ws, rows, d, f);
         pstride = (size_t)rows * d;
-        HIPCK(c, launch_gemm(st, dt, ws.act, layer_ptr(w.w_down, l, d, f, es), ws.part, rows, d, f, pns));
+        HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.act, layer_ptr(w.w_down, l, d, f, es), ws.part, rows, d, f, pns));
     }
     *pend_ns = pns;
     *pend_stride = pstride;
@@ -319,6 +382,7 @@ extern "C" void rlhf_destroy(rlhf_ctx* c) {
     for (hipEvent_t e : evs)
         if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->step_events) (void)hipEventDestroy(e);
+    for (auto& r : c->prof.recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     if (c->own_sd && c->sd) (void)hipStreamDestroy(c->sd);
     if (c->own_ss && c->ss) (void)hipStreamDestroy(c->ss);
     delete c;
@@ -553,7 +617,7 @@ int lm_head_chunks(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
     for (int r0 = 0; r0 < hp.n_sel; r0 += ws.logit_rows) {
         const int nr = std::min(ws.logit_rows, hp.n_sel - r0);
         const char* x = (const char*)ws.xsel + (size_t)r0 * d * c->esz;
-        HIPCK(c, launch_gemm(st, c->dtype, x, w.head, ws.logits, nr, V, d, 1));
+        HIPCK(c, gemm_profiled(c, st, kGemmBatch, act_type(c, true), x, w.head, ws.logits, nr, V, d, 1));
         if (pick)
             HIPCK(c, launch_pick(st, ws.logits, 1, 0, nr, V, hp.forced + r0, c->d_tokens, hp.tok_dst + r0,
                                  c->d_lp_actor, hp.lp_dst + r0, nullptr));
@@ -562,6 +626,19 @@ int lm_head_chunks(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
                                       hp.out_dst + r0));
     }
     return RLHF_OK;
+}
+
+// Algorithmic cost of one layer's packed causal attention over the current lengths of `ids`.
+void batch_attn_cost(const rlhf_ctx* c, const std::vector<int>& ids, int T, PassMeta* pm) {
+    const double qd = (double)c->mc.n_q_heads * c->mc.head_dim, kvd = (double)c->mc.n_kv_heads * c->mc.head_dim;
+    double pairs = 0;
+    for (int i : ids) {
+        const Sample& s = c->smp[i];
+        const double t = s.gen_len > 0 && s.ctx >= s.P ? s.P + s.gen_len : s.P;   // scoring vs prefill
+        pairs += t * (t + 1) / 2;
+    }
+    pm->attn_flops = 4.0 * qd * pairs;
+    pm->attn_bytes = (double)T * (2 * qd + 2 * kvd) * c->esz;
 }
 
 // Prefill of newly admitted samples [group], whose prompts total `T` rows <= max_batch_tokens.
@@ -618,13 +695,14 @@ int prefill_group(rlhf_ctx* c, const std::vector<int>& group, int T) {
     pm.pos = dm_ + T;
     pm.row_start = dm_ + 2 * T;
     pm.kv_dst = dm_ + 3 * T;
+    batch_attn_cost(c, group, T, &pm);
     const rlhf_weights& w = c->roles[RLHF_ACTOR].w;
     Workspace& ws = c->ws_pre;
     int pns;
     size_t pstride;
-    int rc = forward_layers(c, c->sd, ws, w, T, pm, kAttnBatch, 1, &pns, &pstride);
+    int rc = forward_layers(c, c->sd, ws, w, T, pm, kModeBatch, 1, &pns, &pstride);
     if (rc) return rc;
-    HIPCK(c, launch_rmsnorm(c->sd, c->dtype, ws.h, ws.part, pns, pstride, dm_ + 4 * T, w.g_final, ws.xsel, n,
+    HIPCK(c, launch_rmsnorm(c->sd, act_type(c, true), ws.h, ws.part, pns, pstride, dm_ + 4 * T, w.g_final, ws.xsel, n,
                             c->mc.d_model, c->mc.rms_eps));
     HeadPlan hp;
     hp.n_sel = n;
@@ -683,6 +761,12 @@ int decode_rows(rlhf_ctx* c, const std::vector<int>& rows_ids) {
     pm.kv_dst = dmeta + 2 * R;
     pm.row_sample = dmeta + 3 * R;
     pm.ctx_len = dmeta + 4 * R;
+    {
+        const double kvd_ = (double)c->mc.n_kv_heads * c->mc.head_dim, qd_ = (double)c->mc.n_q_heads * c->mc.head_dim;
+        const double keys = (double)(kv_tokens - R);           // sum of visible keys over rows
+        pm.attn_bytes = (keys * 2 * kvd_ + 2.0 * R * qd_) * c->esz;
+        pm.attn_flops = 4.0 * keys * qd_;
+    }
     // split long contexts so that a handful of samples still fills the chip
     Workspace& ws = c->ws_dec;
     const int blocks = R * c->mc.n_kv_heads;
@@ -695,13 +779,13 @@ int decode_rows(rlhf_ctx* c, const std::vector<int>& rows_ids) {
     const rlhf_weights& w = c->roles[RLHF_ACTOR].w;
     int pns;
     size_t pstride;
-    int rc = forward_layers(c, c->sd, ws, w, R, pm, kAttnDecode, asplit, &pns, &pstride);
+    int rc = forward_layers(c, c->sd, ws, w, R, pm, kModeDecode, asplit, &pns, &pstride);
     if (rc) return rc;
     const int d = c->mc.d_model, V = c->mc.vocab;
     HIPCK(c, launch_rmsnorm(c->sd, c->dtype, ws.h, ws.part, pns, pstride, nullptr, w.g_final, ws.xsel, R, d,
                             c->mc.rms_eps));
     const int ns = nsplit_for(c, ws, R, V, d);
-    HIPCK(c, launch_gemm(c->sd, c->dtype, ws.xsel, w.head, ws.part, R, V, d, ns));
+    HIPCK(c, gemm_profiled(c, c->sd, kGemmDecode, c->dtype, ws.xsel, w.head, ws.part, R, V, d, ns));
     HIPCK(c, launch_pick(c->sd, ws.part, ns, (size_t)R * V, R, V, dmeta + 7 * R, c->d_tokens, dmeta + 5 * R,
                          c->d_lp_actor, dmeta + 6 * R, c->d_picked));
     // algorithmic bytes of this step
@@ -860,19 +944,21 @@ int score_pass(rlhf_ctx* c, hipStream_t st, MetaRing& meta, Workspace& ws, const
     pm.tok_idx = dmeta;
     pm.pos = dmeta + T;
     pm.row_start = dmeta + 2 * T;
+    batch_attn_cost(c, std::vector<int>(ids, ids + n), T, &pm);
     const rlhf_weights& w = c->roles[role].w;
     int pns;
     size_t pstride;
-    int rc = forward_layers(c, st, ws, w, T, pm, kAttnBatch, 1, &pns, &pstride);
+    int rc = forward_layers(c, st, ws, w, T, pm, kModeBatch, 1, &pns, &pstride);
     if (rc) return rc;
     const int d = c->mc.d_model;
     // selected rows may exceed the workspace rows only if n_sel > T, which cannot happen
-    HIPCK(c, launch_rmsnorm(st, c->dtype, ws.h, ws.part, pns, pstride, dmeta + 3 * T, w.g_final, ws.xsel, n_sel, d,
+    const int adt = act_type(c, true);
+    HIPCK(c, launch_rmsnorm(st, adt, ws.h, ws.part, pns, pstride, dmeta + 3 * T, w.g_final, ws.xsel, n_sel, d,
                             c->mc.rms_eps));
     if (role == RLHF_CRITIC)
-        HIPCK(c, launch_head_dot(st, c->dtype, ws.xsel, w.head, n_sel, d, c->d_values, dmeta + 3 * T + 2 * n_sel));
+        HIPCK(c, launch_head_dot(st, adt, c->dtype, ws.xsel, w.head, n_sel, d, c->d_values, dmeta + 3 * T + 2 * n_sel));
     else if (role == RLHF_REWARD)
-        HIPCK(c, launch_head_dot(st, c->dtype, ws.xsel, w.head, n_sel, d, c->d_reward, dmeta + 3 * T + 2 * n_sel));
+        HIPCK(c, launch_head_dot(st, adt, c->dtype, ws.xsel, w.head, n_sel, d, c->d_reward, dmeta + 3 * T + 2 * n_sel));
     else {
         HeadPlan hp;
         hp.n_sel = n_sel;
@@ -994,6 +1080,7 @@ extern "C" int rlhf_run_stage(rlhf_ctx* c, const rlhf_stage_opts* o, rlhf_stage_
             HIPCK(c, hipEventRecord(c->step_events[2 * n_steps], c->sd));
         }
         rlhf_step_info info;
+        const int64_t bytes_before = c->acc_weight_bytes + c->acc_kv_bytes;
         rc = rlhf_generate_step(c, &info);
         if (rc) return rc;
         if (timing && n_steps < o->trace_cap) HIPCK(c, hipEventRecord(c->step_events[2 * n_steps + 1], c->sd));
@@ -1003,6 +1090,9 @@ extern "C" int rlhf_run_stage(rlhf_ctx* c, const rlhf_stage_opts* o, rlhf_stage_
         if (n_steps < o->trace_cap) {
             if (o->trace_active) o->trace_active[n_steps] = (int)c->active.size();
             if (o->trace_decoded) o->trace_decoded[n_steps] = info.n_decoded;
+            if (o->trace_prefill_tokens) o->trace_prefill_tokens[n_steps] = info.n_prefill_tokens;
+            if (o->trace_step_bytes)
+                o->trace_step_bytes[n_steps] = c->acc_weight_bytes + c->acc_kv_bytes - bytes_before;
         }
         ++n_steps;
         const int remaining = (int)(c->waiting.size() + c->active.size());
@@ -1128,5 +1218,45 @@ extern "C" int rlhf_debug_snapshot(rlhf_ctx* c, rlhf_snapshot* o) {
     if (o->retired) std::copy(c->retired.begin(), c->retired.end(), o->retired);
     if (o->batch_offsets) std::copy(c->batch_offsets.begin(), c->batch_offsets.end(), o->batch_offsets);
     if (o->batch_step) std::copy(c->batch_step.begin(), c->batch_step.end(), o->batch_step);
+    return RLHF_OK;
+}
+
+// ================================================================================ profiling
+
+extern "C" int rlhf_profile_begin(rlhf_ctx* c, int32_t sample_every) {
+    if (!c) return RLHF_EINVAL;
+    if (sample_every < 1) return c->fail(RLHF_EINVAL, "rlhf_profile_begin: sample_every must be >= 1");
+    int rc = rlhf_sync(c);
+    if (rc) return rc;
+    Profiler& p = c->prof;
+    p.on = true;
+    p.every = sample_every;
+    p.n_used = 0;
+    for (int k = 0; k < kClassCount; ++k) { p.launches[k] = 0; p.tot_bytes[k] = p.tot_flops[k] = 0; }
+    return RLHF_OK;
+}
+
+extern "C" int rlhf_profile_end(rlhf_ctx* c, rlhf_kernel_profile* out) {
+    if (!c) return RLHF_EINVAL;
+    if (!out) return c->fail(RLHF_EINVAL, "rlhf_profile_end: NULL");
+    int rc = rlhf_sync(c);
+    if (rc) return rc;
+    Profiler& p = c->prof;
+    p.on = false;
+    for (int k = 0; k < kClassCount; ++k) {
+        memset(&out[k], 0, sizeof out[k]);
+        out[k].launches = p.launches[k];
+        out[k].total_bytes = p.tot_bytes[k];
+        out[k].total_flops = p.tot_flops[k];
+    }
+    for (size_t i = 0; i < p.n_used; ++i) {
+        float ms = 0.f;
+        HIPCK(c, hipEventElapsedTime(&ms, p.recs[i].a, p.recs[i].b));
+        rlhf_kernel_profile& o = out[p.recs[i].cls];
+        o.sampled += 1;
+        o.sampled_ms += ms;
+        o.sampled_bytes += p.recs[i].bytes;
+        o.sampled_flops += p.recs[i].flops;
+    }
     return RLHF_OK;
 }

@@ -1,6 +1,8 @@
 // C[m][n] = sum_k A[m][k] * W[n][k]   (activations times a row-major weight matrix, y = W x)
 //
-// bf16: LDS-tiled MFMA kernel (v_mfma_f32_16x16x32_bf16, float accumulate).  One template
+// bf16 weights: LDS-tiled MFMA kernel (v_mfma_f32_16x16x32_{bf16,f16}, float accumulate).
+// Activations are bf16 (decode) or half (prefill / scoring); in the second case the bf16
+// weight chunks are converted to half, exactly, between the global load and the LDS store.  One template
 // serves the decode regime (few rows: the weight matrix streams from HBM once, split along K
 // so that enough workgroups are in flight to saturate bandwidth) and the prefill / scoring
 // regime (thousands of rows: compute-bound 128x128 tiles).  Global loads are 16 bytes per lane,
@@ -21,7 +23,22 @@ __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >>
 
 // TM x TN output tile per workgroup of 4 waves arranged WM x WN; each wave owns
 // (TM/WM) x (TN/WN), built from 16x16 MFMA fragments.
-template <int TM, int TN, int WM, int WN>
+template <bool AF16> struct Mfma;
+template <> struct Mfma<false> {
+    typedef bf16x8_t frag;
+    static __device__ __forceinline__ f32x4_t run(frag a, frag b, f32x4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Mfma<true> {
+    typedef f16x8_t frag;
+    static __device__ __forceinline__ f32x4_t run(frag a, frag b, f32x4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+    }
+};
+
+// A: 16-bit activations (bf16 if !AF16, half if AF16); W: bf16.
+template <int TM, int TN, int WM, int WN, bool AF16>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
                                                    const bf16_t* __restrict__ W,
                                                    float* __restrict__ C, int M, int N, int K,
@@ -64,6 +81,10 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
             rb[i] = make_uint4(0, 0, 0, 0);
             if (idx < B_CH && gn < N && gk < kend)
                 rb[i] = *reinterpret_cast<const uint4*>(W + (size_t)gn * K + gk);
+            if (AF16) {
+                rb[i].x = bf16x2_to_f16x2(rb[i].x); rb[i].y = bf16x2_to_f16x2(rb[i].y);
+                rb[i].z = bf16x2_to_f16x2(rb[i].z); rb[i].w = bf16x2_to_f16x2(rb[i].w);
+            }
         }
     };
     auto sstore = [&](int buf) {
@@ -100,17 +121,17 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
         if (kt + 1 < nk) gload(kt + 1);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            bf16x8_t fa[FM], fb[FN];
+            typename Mfma<AF16>::frag fa[FM], fb[FN];
             const int c = s * 4 + fq;
 #pragma unroll
             for (int i = 0; i < FM; ++i) {
                 const int row = wm * (TM / WM) + i * 16 + fr;
-                fa[i] = *reinterpret_cast<const bf16x8_t*>(&sA[buf][row * kTK + swz(row, c) * 8]);
+                fa[i] = *reinterpret_cast<const typename Mfma<AF16>::frag*>(&sA[buf][row * kTK + swz(row, c) * 8]);
             }
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
                 const int row = wn * (TN / WN) + j * 16 + fr;
-                fb[j] = *reinterpret_cast<const bf16x8_t*>(&sB[buf][row * kTK + swz(row, c) * 8]);
+                fb[j] = *reinterpret_cast<const typename Mfma<AF16>::frag*>(&sB[buf][row * kTK + swz(row, c) * 8]);
             }
             // weights are the MFMA "A" operand: D[i = n][j = m], so a lane ends up holding four
             // consecutive n of one row m and stores them as one float4.
@@ -118,7 +139,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
             for (int i = 0; i < FM; ++i)
 #pragma unroll
                 for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+                    acc[i][j] = Mfma<AF16>::run(fb[j], fa[i], acc[i][j]);
         }
         if (kt + 1 < nk) sstore(buf ^ 1);
         __syncthreads();
@@ -209,9 +230,9 @@ TileCfg pick_tile(int M) {
 constexpr int kTargetBlocks = 1024;  // about four workgroups per compute unit
 }  // namespace
 
-int gemm_choose_nsplit(int dtype, int M, int N, int K, int max_split) {
+int gemm_choose_nsplit(int wdt, int M, int N, int K, int max_split) {
     int tm, tn, kgran;
-    if (dtype == kBF16) { TileCfg c = pick_tile(M); tm = c.tm; tn = c.tn; kgran = kTK; }
+    if (wdt == kBF16) { TileCfg c = pick_tile(M); tm = c.tm; tn = c.tn; kgran = kTK; }
     else { tm = 64; tn = 64; kgran = 16; }
     const long tiles = (long)((M + tm - 1) / tm) * ((N + tn - 1) / tn);
     int ns = (int)((kTargetBlocks + tiles - 1) / tiles);
@@ -228,11 +249,21 @@ int gemm_choose_nsplit(int dtype, int M, int N, int K, int max_split) {
     return ns;
 }
 
-hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const void* W, float* C, int M,
-                       int N, int K, int nsplit) {
+template <bool AF16>
+static void launch_bf16(hipStream_t st, int tm, dim3 grid, const bf16_t* a, const bf16_t* w, float* C, int M,
+                        int N, int K, int kchunk, int tiles_n) {
+    if (tm == 16) k_gemm_bf16<16, 128, 1, 4, AF16><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
+    else if (tm == 32) k_gemm_bf16<32, 128, 1, 4, AF16><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
+    else if (tm == 64) k_gemm_bf16<64, 128, 2, 2, AF16><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
+    else k_gemm_bf16<128, 128, 2, 2, AF16><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
+}
+
+hipError_t launch_gemm(hipStream_t st, int wdt, int adt, const void* A, const void* W, float* C,
+                       int M, int N, int K, int nsplit) {
     if (M <= 0 || N <= 0) return hipSuccess;
     if (nsplit < 1 || K <= 0) return hipErrorInvalidValue;
-    if (dtype == kBF16) {
+    if (wdt == kBF16) {
+        if (adt != kBF16 && adt != kF16) return hipErrorInvalidValue;
         if (K % 8) return hipErrorInvalidValue;
         const TileCfg c = pick_tile(M);
         const int tiles_m = (M + c.tm - 1) / c.tm, tiles_n = (N + c.tn - 1) / c.tn;
@@ -240,12 +271,10 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const void* W, 
         dim3 grid(tiles_m * tiles_n, nsplit);
         const bf16_t* a = (const bf16_t*)A;
         const bf16_t* w = (const bf16_t*)W;
-        if (c.tm == 16) k_gemm_bf16<16, 128, 1, 4><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
-        else if (c.tm == 32) k_gemm_bf16<32, 128, 1, 4><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
-        else if (c.tm == 64) k_gemm_bf16<64, 128, 2, 2><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
-        else k_gemm_bf16<128, 128, 2, 2><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
+        if (adt == kF16) launch_bf16<true>(st, c.tm, grid, a, w, C, M, N, K, kchunk, tiles_n);
+        else launch_bf16<false>(st, c.tm, grid, a, w, C, M, N, K, kchunk, tiles_n);
     } else {
-        if (K % 4) return hipErrorInvalidValue;
+        if (K % 4 || adt != kF32) return hipErrorInvalidValue;
         const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
         const int kchunk = ((K + nsplit - 1) / nsplit + 15) / 16 * 16;
         dim3 grid(tiles_m * tiles_n, nsplit);

@@ -9,7 +9,11 @@
 
 namespace rlhf {
 
-enum DType { kF32 = 0, kBF16 = 1 };
+// Storage types.  Weights and the KV pool are kF32 or kBF16.  Activations fed to the matrix
+// units are kF32 (float model), kBF16 (decode step of a bf16 model) or kF16 (prefill / scoring
+// passes of a bf16 model: half-precision activations keep 11 significant bits, and the bf16
+// weights convert to half exactly on their way into LDS).
+enum DType { kF32 = 0, kBF16 = 1, kF16 = 2 };
 
 struct Dims {
     int n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
@@ -17,26 +21,28 @@ struct Dims {
 };
 
 // ---- GEMM: C[s][m][n] = sum over k in split s of A[m][k] * W[n][k];  C float, split stride M*N
-int gemm_choose_nsplit(int dtype, int M, int N, int K, int max_split);
-hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const void* W, float* C, int M,
-                       int N, int K, int nsplit);
+// (wdt, adt) in {(kF32,kF32), (kBF16,kBF16), (kBF16,kF16)}
+int gemm_choose_nsplit(int wdt, int M, int N, int K, int max_split);
+hipError_t launch_gemm(hipStream_t st, int wdt, int adt, const void* A, const void* W, float* C,
+                       int M, int N, int K, int nsplit);
 
 // ---- elementwise / row kernels
 hipError_t launch_embed(hipStream_t st, int dtype, const int* tokens, const int* tok_idx,
                         const void* table, float* h, int rows, int d, int vocab);
 // v = h[src] + sum partials[src];  (row_idx == NULL: src = r and h[src] = v is written back)
 // xn[r] = v * rsqrt(mean(v^2) + eps) * g
-hipError_t launch_rmsnorm(hipStream_t st, int dtype, float* h, const float* part, int nsplit,
+hipError_t launch_rmsnorm(hipStream_t st, int adt, float* h, const float* part, int nsplit,
                           size_t sstride, const int* row_idx, const float* g, void* xn, int rows,
                           int d, float eps);
-// Rotary on Q and K heads of qkv rows, cast to storage type.  q_out [rows, Hq*hd]; k_out/v_out
-// [rows, Hkv*hd] if non-NULL; if pool != NULL and kv_dst[r] >= 0, K/V of row r also go to
-// token slot kv_dst[r] (= page * page_tokens + offset) of `layer` in the paged pool.
-hipError_t launch_rope_kv(hipStream_t st, int dtype, const float* qkv, int nsplit, size_t sstride,
+// Rotary on Q and K heads of qkv rows.  q_out [rows, Hq*hd] and, if non-NULL, k_out/v_out
+// [rows, Hkv*hd] have type qdt; if pool != NULL and kv_dst[r] >= 0, K/V of row r also go (as
+// type pdt) to token slot kv_dst[r] (= page * page_tokens + offset) of `layer` in the paged pool.
+// (qdt, pdt) in {(kF32,kF32), (kBF16,kBF16), (kF32,kBF16)}.
+hipError_t launch_rope_kv(hipStream_t st, int qdt, int pdt, const float* qkv, int nsplit, size_t sstride,
                           const int* pos, const int* kv_dst, const float* rope_table,
                           void* q_out, void* k_out, void* v_out, void* pool, int layer,
                           int rows, const Dims& dm);
-hipError_t launch_swiglu(hipStream_t st, int dtype, const float* gu, int nsplit, size_t sstride,
+hipError_t launch_swiglu(hipStream_t st, int adt, const float* gu, int nsplit, size_t sstride,
                          void* act, int rows, int ffn);
 // Greedy choice per logit row (lowest id on ties), optional imposed token forced[r] >= 0;
 // writes the emitted token to tokens[tok_dst[r]] and picked[r], its log-prob to lp[lp_dst[r]].
@@ -47,8 +53,8 @@ hipError_t launch_pick(hipStream_t st, const float* logits, int nsplit, size_t s
 hipError_t launch_gather_lp(hipStream_t st, const float* logits, int nsplit, size_t sstride,
                             int rows, int vocab, const int* tokens, const int* target_idx,
                             float* out, const int* out_dst);
-// out[out_dst[r]] = <xn[r], w>
-hipError_t launch_head_dot(hipStream_t st, int dtype, const void* xn, const void* w, int rows,
+// out[out_dst[r]] = <xn[r], w>;  xn of type adt, w of type wdt
+hipError_t launch_head_dot(hipStream_t st, int adt, int wdt, const void* xn, const void* w, int rows,
                            int d, float* out, const int* out_dst);
 // page_table[upd_idx[i]] = upd_val[i]
 hipError_t launch_scatter_int(hipStream_t st, int* dst, const int* idx, const int* val, int n);
@@ -61,11 +67,11 @@ hipError_t launch_decode_attn(hipStream_t st, int dtype, const void* q, const vo
                               const int* page_table, int pt_stride, const int* row_sample,
                               const int* ctx_len, void* out, float* part_acc, float* part_ml,
                               int rows, int layer, int nsplit, const Dims& dm);
-// Prefill / scoring: packed varlen causal attention over contiguous q [T,Hq*hd], k, v
-// [T,Hkv*hd]; row r belongs to the sequence starting at row_start[r] and sits at position
+// Prefill / scoring: packed varlen causal attention over contiguous float q [T,Hq*hd], k, v
+// [T,Hkv*hd]; out has type odt; row r belongs to the sequence starting at row_start[r] and sits at position
 // row_pos[r] in it (sees keys row_start[r] .. row_start[r] + row_pos[r]).
-hipError_t launch_prefill_attn(hipStream_t st, int dtype, const void* q, const void* k,
-                               const void* v, const int* row_start, const int* row_pos,
+hipError_t launch_prefill_attn(hipStream_t st, int odt, const float* q, const float* k,
+                               const float* v, const int* row_start, const int* row_pos,
                                void* out, int rows, const Dims& dm);
 
 size_t pool_page_elems(const Dims& dm);  // elements of one page over all layers

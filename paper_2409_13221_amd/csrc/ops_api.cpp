@@ -18,11 +18,13 @@ extern "C" int rlhf_op_gemm_nsplit(int dtype, int M, int N, int K, int max_split
     return gemm_choose_nsplit(dtype == RLHF_BF16 ? kBF16 : kF32, M, N, K, max_split);
 }
 
-extern "C" int rlhf_op_gemm(int dtype, const void* A, const void* W, float* C, int M, int N, int K,
-                            int nsplit, void* stream) {
+extern "C" int rlhf_op_gemm(int dtype, int act_half, const void* A, const void* W, float* C, int M, int N,
+                            int K, int nsplit, void* stream) {
     if (!A || !W || !C || M < 0 || N < 0 || K <= 0 || nsplit < 1) return RLHF_EINVAL;
     if (dtype != RLHF_BF16 && dtype != RLHF_FP32) return RLHF_EINVAL;
-    return status_of(launch_gemm((hipStream_t)stream, dtype == RLHF_BF16 ? kBF16 : kF32, A, W, C, M, N, K, nsplit));
+    if (act_half && dtype != RLHF_BF16) return RLHF_EINVAL;
+    const int wdt = dtype == RLHF_BF16 ? kBF16 : kF32;
+    return status_of(launch_gemm((hipStream_t)stream, wdt, act_half ? kF16 : wdt, A, W, C, M, N, K, nsplit));
 }
 
 extern "C" int rlhf_op_paged_decode_attention(int dtype, const void* q, const void* pool,
@@ -41,13 +43,13 @@ extern "C" int rlhf_op_paged_decode_attention(int dtype, const void* q, const vo
                                         rows, layer, nsplit, dm));
 }
 
-extern "C" int rlhf_op_varlen_attention(int dtype, const void* q, const void* k, const void* v,
+extern "C" int rlhf_op_varlen_attention(int out_half, const float* q, const float* k, const float* v,
                                         const int32_t* row_start, const int32_t* row_pos, void* out,
                                         int rows, int n_q_heads, int n_kv_heads, int head_dim, void* stream) {
     if (!q || !k || !v || !row_start || !row_pos || !out || rows < 0 || n_kv_heads <= 0 ||
         n_q_heads % n_kv_heads)
         return RLHF_EINVAL;
     Dims dm{1, n_q_heads * head_dim, n_q_heads, n_kv_heads, head_dim, 0, 0, 16};
-    return status_of(launch_prefill_attn((hipStream_t)stream, dtype == RLHF_BF16 ? kBF16 : kF32, q, k, v,
-                                         row_start, row_pos, out, rows, dm));
+    return status_of(launch_prefill_attn((hipStream_t)stream, out_half ? kF16 : kF32, q, k, v, row_start,
+                                         row_pos, out, rows, dm));
 }

@@ -114,3 +114,37 @@ def test_errors_are_reported_not_fatal(tiny_ref):
         with pytest.raises(R.RlhfError) as e:
             g.submit(ref["forced"])                  # one sample's reservation exceeds the pool
         assert e.value.code == R.RLHF_ENOMEM
+
+
+# ------------------------------------------------------------------------------ bf16 path
+
+@pytest.fixture(scope="module")
+def gpt2s_ref():
+    """GPT-2-small shape, bf16, real depth; 6 samples with outputs capped at 24 so that the
+    float64 oracle finishes in seconds.  Weights are drawn on the GPU and copied to the host."""
+    cfg = CONFIGS["gpt2s"].with_(gain_jitter=0.05)
+    inp = H.make_inputs(cfg, n=6, max_len=24, weight_device="cuda")
+    return cfg, H.oracle_stage(cfg, inp=inp)
+
+
+def test_gpt2s_bf16_stage_matches_oracle(gpt2s_ref):
+    cfg, ref = gpt2s_ref
+    got = H.run_gpu_stage(cfg, ref, fused=True, R_t=7, chunk_tokens=600)
+    worst = H.compare_stage(cfg, ref, got)
+    print("gpt2s bf16 worst errors:", worst, "forced positions:",
+          int(sum((f >= 0).sum() for f in ref["forced"])), "of", int(ref["out_len"].sum()))
+    seq = H.run_gpu_stage(cfg, ref, fused=False, R_t=0, chunk_tokens=600)
+    H.compare_stage(cfg, ref, seq)
+    np.testing.assert_array_equal(got["tokens"], seq["tokens"])
+
+
+def test_gqa_bf16_small_model_matches_oracle():
+    """Grouped KV heads (8 query heads per KV head, head_dim 128) on a small bf16 model."""
+    from workload.configs import ModelCfg
+    base = CONFIGS["tiny"]
+    m = ModelCfg(n_layers=2, d_model=512, n_q_heads=16, n_kv_heads=2, head_dim=128, ffn=1024, vocab=2048,
+                 dtype="bf16")
+    cfg = base.with_(name="gqa_small", model=m, n_samples=5, prompt_len=(20, 45), gain_jitter=0.05)
+    ref = H.oracle_stage(cfg, max_len=20)
+    got = H.run_gpu_stage(cfg, ref, fused=True, R_t=6, chunk_tokens=64)
+    print("gqa worst errors:", H.compare_stage(cfg, ref, got))
