@@ -148,6 +148,8 @@ def main():
     ap.add_argument("--max_active", type=int, default=256)
     ap.add_argument("--role_mask", type=int, default=ROLE_MASK_DEFAULT)
     ap.add_argument("--sample_every", type=int, default=16)
+    ap.add_argument("--sequential", action="store_true",
+                    help="time the serial generate-then-score plan instead (clean per-kernel figures)")
     ap.add_argument("--no_cpu", action="store_true")
     ap.add_argument("--no_sequential", action="store_true")
     args = ap.parse_args()
@@ -166,14 +168,14 @@ def main():
     R, ctx, weights, wl, max_new = build_stage(cfg, args)
 
     for i in range(args.warmup):
-        ms, st, _ = run_stage(R, ctx, wl, max_new, True, args)
+        ms, st, _ = run_stage(R, ctx, wl, max_new, not args.sequential, args)
         log(f"[bench] warmup {i}: {ms:.1f} ms, {st.n_steps} steps, {st.n_batches} scoring batches")
     R.rlhf_profile_begin(ctx, args.sample_every)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     times, last = [], None
     for i in range(args.steps):
-        ms, st, tr = run_stage(R, ctx, wl, max_new, True, args, trace=(i == args.steps - 1))
+        ms, st, tr = run_stage(R, ctx, wl, max_new, not args.sequential, args, trace=(i == args.steps - 1))
         times.append(ms)
         last = (st, tr)
         log(f"[bench] step {i}: {ms:.1f} ms")
@@ -236,6 +238,7 @@ def main():
            "data": "synthetic",
            "config": {"workload": cfg.name, "n_samples": int(len(max_new)), "length_law": cfg.length_law,
                       "length_params": list(cfg.length_params), "length_cap": cfg.length_cap,
+                      "plan": "sequential" if args.sequential else "fused",
                       "score_chunk_tokens": args.score_chunk_tokens, "R_t": args.R_t, "role_mask": args.role_mask,
                       "page_tokens": cfg.page_tokens},
            "roofline": roof, "cpu_baseline": cpu, "fused_vs_sequential": seq, "kernels": kernels,

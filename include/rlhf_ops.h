@@ -46,6 +46,15 @@ int rlhf_op_varlen_attention(int out_half, const float* q, const float* k, const
                              const int32_t* row_start, const int32_t* row_pos, void* out, int rows,
                              int n_q_heads, int n_kv_heads, int head_dim, void* stream);
 
+/* The same attention on the matrix units, as used for bf16 models: q, k, v, out IEEE half.
+ * Queries are cut into tiles of 128 rows that do not straddle sequences: tile i covers rows
+ * tile_start[i] + tile_q0[i] .. (at most 128, up to the end) of the sequence that starts at
+ * row tile_start[i] and has tile_len[i] rows.  rows = rows of the packed buffers.
+ * head_dim must be 64 or 128. */
+int rlhf_op_flash_attention(const void* q, const void* k, const void* v, const int32_t* tile_start,
+                            const int32_t* tile_q0, const int32_t* tile_len, void* out, int n_tiles,
+                            int rows, int n_q_heads, int n_kv_heads, int head_dim, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -119,11 +119,12 @@ def lib() -> C.CDLL:
         L.rlhf_op_gemm.argtypes = [C.c_int, C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp]
         L.rlhf_op_paged_decode_attention.argtypes = [C.c_int, vp, vp, vp, C.c_int, vp, vp, vp, vp, vp] + [C.c_int] * 7 + [vp]
         L.rlhf_op_varlen_attention.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp] + [C.c_int] * 4 + [vp]
+        L.rlhf_op_flash_attention.argtypes = [vp] * 7 + [C.c_int] * 5 + [vp]
         for name in ("rlhf_create", "rlhf_load_weights", "rlhf_submit", "rlhf_generate_step", "rlhf_retire",
                      "rlhf_score", "rlhf_run_stage", "rlhf_get_results", "rlhf_debug_snapshot", "rlhf_sync",
                      "rlhf_profile_begin", "rlhf_profile_end",
                      "rlhf_op_gemm_nsplit", "rlhf_op_gemm", "rlhf_op_paged_decode_attention",
-                     "rlhf_op_varlen_attention"):
+                     "rlhf_op_varlen_attention", "rlhf_op_flash_attention"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -334,3 +335,20 @@ def rlhf_op_varlen_attention(q, k, v, row_start, row_pos, out, n_q_heads: int, n
     _op_check(lib().rlhf_op_varlen_attention(int(out.dtype == torch.float16), q.data_ptr(), k.data_ptr(), v.data_ptr(), row_start.data_ptr(),
                                              row_pos.data_ptr(), out.data_ptr(), q.shape[0], n_q_heads, n_kv_heads,
                                              head_dim, _stream_ptr()), "rlhf_op_varlen_attention")
+
+
+def rlhf_op_flash_attention(q, k, v, seq_lens, out, n_q_heads: int, n_kv_heads: int, head_dim: int):
+    """float16 q [T, Hq*hd], k, v [T, Hkv*hd], out like q; sequences of seq_lens packed back to back."""
+    import torch
+    assert q.dtype == k.dtype == v.dtype == out.dtype == torch.float16
+    ts, tq, tl, start = [], [], [], 0
+    for L in seq_lens:
+        for q0 in range(0, L, 128):
+            ts.append(start); tq.append(q0); tl.append(L)
+        start += L
+    dev = lambda a: torch.tensor(a, dtype=torch.int32, device=q.device)
+    d_ts, d_tq, d_tl = dev(ts), dev(tq), dev(tl)
+    _op_check(lib().rlhf_op_flash_attention(q.data_ptr(), k.data_ptr(), v.data_ptr(), d_ts.data_ptr(), d_tq.data_ptr(),
+                                            d_tl.data_ptr(), out.data_ptr(), len(ts), q.shape[0], n_q_heads,
+                                            n_kv_heads, head_dim, _stream_ptr()), "rlhf_op_flash_attention")
+    return d_ts, d_tq, d_tl          # keep alive until the stream has run

@@ -9,8 +9,9 @@
 // merged by shuffles at the end, waves through LDS, splits by a small merge kernel (LSE
 // merge), so that a few long samples still spread over the whole chip.
 //
-// Prefill / scoring v1 uses the same inner loop over 16-token tiles of contiguous K/V (one
-// workgroup per query row and KV head).
+// Prefill / scoring of float models uses the same inner loop over 16-token tiles of contiguous
+// K/V (one workgroup per query row and KV head); bf16 models use the MFMA kernel at the end of
+// this file.
 #include "common.cuh"
 #include "kernels.h"
 
@@ -337,16 +338,205 @@ hipError_t launch_prefill_attn(hipStream_t st, int odt, const float* q, const fl
                                                           dm.n_kv_heads);                          \
         return hipGetLastError();                                                                  \
     } while (0)
-    if (odt == kF16) {
-        if (hd == 128 && G == 1) RLHF_PRE(f16_t, 128, 1);
-        if (hd == 128 && G == 8) RLHF_PRE(f16_t, 128, 8);
-        if (hd == 64 && G == 1) RLHF_PRE(f16_t, 64, 1);
-    } else if (odt == kF32) {
+    if (odt == kF32) {
         if (hd == 128 && G == 1) RLHF_PRE(float, 128, 1);
         if (hd == 64 && G == 1) RLHF_PRE(float, 64, 1);
     }
 #undef RLHF_PRE
     return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------ prefill / scoring, half precision
+// Packed varlen causal attention on the matrix units (bf16 models).  q, k, v, out are IEEE half
+// [T, heads*HD].  A workgroup owns one tile of 128 consecutive queries of one sequence and one
+// query head; each of its four waves owns 32 queries.  Keys are walked in tiles of 64: the K
+// tile sits in LDS row-major (16-byte chunks XOR-swizzled), the V tile transposed ([d][key]) so
+// that the second product can read runs of keys.  Per key tile and wave:
+//   S^T[key][q] = K Q^T     (v_mfma_f32_16x16x32_f16, K rows as the A operand)
+//   online softmax along keys: a lane holds 16 keys of one query, lane groups are merged by
+//   two xor-shuffles; the running sum stays per lane until the end
+//   O^T[d][q] += V^T P^T    (P re-used from the lane's own registers as the B operand)
+// Masking covers causality and the sequence end; rows past the sequence end are not stored.
+constexpr int kFaBM = 128, kFaBN = 64, kFaVStride = kFaBN + 8;
+
+template <int HD>
+__global__ __launch_bounds__(256) void k_flash_attn(const f16_t* __restrict__ q,
+                                                    const f16_t* __restrict__ k,
+                                                    const f16_t* __restrict__ v,
+                                                    const int* __restrict__ tile_start,
+                                                    const int* __restrict__ tile_q0,
+                                                    const int* __restrict__ tile_len,
+                                                    f16_t* __restrict__ out, int Hq, int Hkv,
+                                                    int T_total) {
+    constexpr int KS = HD / 32;        // MFMA steps along d for Q K^T
+    constexpr int DF = HD / 16;        // 16-wide d fragments of the output
+    constexpr int CH = HD / 8;         // 16-byte chunks per K/V row
+    constexpr int LD_IT = kFaBN * CH / 256;
+    __shared__ __attribute__((aligned(16))) f16_t sK[kFaBN * HD];
+    __shared__ __attribute__((aligned(16))) f16_t sVt[HD * kFaVStride];
+
+    const int tile = blockIdx.x, h = blockIdx.y;
+    const int kh = h / (Hq / Hkv);
+    const int s0 = tile_start[tile], q0 = tile_q0[tile], L = tile_len[tile];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int fr = lane & 15, g = lane >> 4;
+    const size_t qstride = (size_t)Hq * HD, kstride = (size_t)Hkv * HD;
+    const float scale = rsqrtf((float)HD);
+
+    // Q fragments (B operand): query fr of each 16-row fragment, 8 dims at (s*32 + g*8)
+    f16x8_t qf[2][KS];
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const int row = min(q0 + wave * 32 + m * 16 + fr, L - 1);
+        const f16_t* src = q + (size_t)(s0 + row) * qstride + (size_t)h * HD + g * 8;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qf[m][s] = *reinterpret_cast<const f16x8_t*>(src + s * 32);
+    }
+    f32x4_t oacc[DF][2];
+#pragma unroll
+    for (int d = 0; d < DF; ++d)
+#pragma unroll
+        for (int m = 0; m < 2; ++m) oacc[d][m] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m_run[2] = {-1e30f, -1e30f}, l_run[2] = {0.f, 0.f};
+
+    const int q_last = min(q0 + kFaBM, L) - 1;
+    const int n_kt = q_last / kFaBN + 1;
+
+    uint4 rk[LD_IT], rv[LD_IT];
+    auto gload = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < LD_IT; ++i) {
+            const int idx = t + i * 256;
+            const int row = idx / CH, c = idx % CH;
+            const size_t grow = (size_t)min(s0 + kt * kFaBN + row, T_total - 1);
+            rk[i] = *reinterpret_cast<const uint4*>(k + grow * kstride + (size_t)kh * HD + c * 8);
+            rv[i] = *reinterpret_cast<const uint4*>(v + grow * kstride + (size_t)kh * HD + c * 8);
+        }
+    };
+    auto sstore = [&]() {
+#pragma unroll
+        for (int i = 0; i < LD_IT; ++i) {
+            const int idx = t + i * 256;
+            const int row = idx / CH, c = idx % CH;
+            const int pc = (CH == 16) ? (c ^ (row & 15)) : (c ^ ((row >> 1) & 7));
+            *reinterpret_cast<uint4*>(&sK[row * HD + pc * 8]) = rk[i];
+            const f16_t* ve = reinterpret_cast<const f16_t*>(&rv[i]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sVt[(c * 8 + e) * kFaVStride + row] = ve[e];
+        }
+    };
+
+    gload(0);
+    for (int kt = 0; kt < n_kt; ++kt) {
+        __syncthreads();                       // the previous tile has been consumed
+        sstore();
+        __syncthreads();
+        if (kt + 1 < n_kt) gload(kt + 1);
+
+        // ---- S^T = K Q^T
+        f32x4_t sacc[4][2];
+#pragma unroll
+        for (int f = 0; f < 4; ++f)
+#pragma unroll
+            for (int m = 0; m < 2; ++m) sacc[f][m] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                const int row = f * 16 + fr, c = s * 4 + g;
+                const int pc = (CH == 16) ? (c ^ (row & 15)) : (c ^ ((row >> 1) & 7));
+                const f16x8_t kf = *reinterpret_cast<const f16x8_t*>(&sK[row * HD + pc * 8]);
+#pragma unroll
+                for (int m = 0; m < 2; ++m)
+                    sacc[f][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qf[m][s], sacc[f][m], 0, 0, 0);
+            }
+        }
+        // ---- mask, online softmax (per query = per lane column)
+        f16x8_t pb[2][2];
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int qrow = q0 + wave * 32 + m * 16 + fr;
+            float mx = -INFINITY;
+#pragma unroll
+            for (int f = 0; f < 4; ++f)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int key = kt * kFaBN + f * 16 + g * 4 + r;
+                    const float sv = (key <= qrow) ? sacc[f][m][r] * scale : -INFINITY;
+                    sacc[f][m][r] = sv;
+                    mx = fmaxf(mx, sv);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            const float m_new = fmaxf(m_run[m], mx);
+            const float alpha = __expf(m_run[m] - m_new);
+            m_run[m] = m_new;
+            float ls = 0.f;
+#pragma unroll
+            for (int f = 0; f < 4; ++f)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float p = __expf(sacc[f][m][r] - m_new);
+                    ls += p;
+                    pb[m][f >> 1][(f & 1) * 4 + r] = (f16_t)p;
+                }
+            l_run[m] = l_run[m] * alpha + ls;
+#pragma unroll
+            for (int d = 0; d < DF; ++d) oacc[d][m] *= alpha;
+        }
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int d = 0; d < DF; ++d) {
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const f16_t* vr = &sVt[(d * 16 + fr) * kFaVStride + s2 * 32 + g * 4];
+                const uint2 lo = *reinterpret_cast<const uint2*>(vr);
+                const uint2 hi = *reinterpret_cast<const uint2*>(vr + 16);
+                const uint4 packed = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                const f16x8_t vf = *reinterpret_cast<const f16x8_t*>(&packed);
+#pragma unroll
+                for (int m = 0; m < 2; ++m)
+                    oacc[d][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, pb[m][s2], oacc[d][m], 0, 0, 0);
+            }
+        }
+    }
+    // ---- normalise and store: a lane holds d = 16*df + 4g + r of query fr
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        float l = l_run[m];
+        l += __shfl_xor(l, 16, kWave);
+        l += __shfl_xor(l, 32, kWave);
+        const int qrow = q0 + wave * 32 + m * 16 + fr;
+        if (qrow >= L) continue;
+        const float inv = 1.f / l;
+        f16_t* dst = out + (size_t)(s0 + qrow) * qstride + (size_t)h * HD + g * 4;
+#pragma unroll
+        for (int d = 0; d < DF; ++d) {
+            typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+            f16x4_t o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = (f16_t)(oacc[d][m][r] * inv);
+            *reinterpret_cast<f16x4_t*>(dst + d * 16) = o;
+        }
+    }
+}
+
+hipError_t launch_flash_attn(hipStream_t st, const void* q, const void* k, const void* v,
+                             const int* tile_start, const int* tile_q0, const int* tile_len, void* out,
+                             int n_tiles, int T_total, const Dims& dm) {
+    if (n_tiles <= 0) return hipSuccess;
+    dim3 grid(n_tiles, dm.n_q_heads);
+    if (dm.head_dim == 128)
+        k_flash_attn<128><<<grid, 256, 0, st>>>((const f16_t*)q, (const f16_t*)k, (const f16_t*)v, tile_start,
+                                                tile_q0, tile_len, (f16_t*)out, dm.n_q_heads, dm.n_kv_heads,
+                                                T_total);
+    else if (dm.head_dim == 64)
+        k_flash_attn<64><<<grid, 256, 0, st>>>((const f16_t*)q, (const f16_t*)k, (const f16_t*)v, tile_start,
+                                               tile_q0, tile_len, (f16_t*)out, dm.n_q_heads, dm.n_kv_heads,
+                                               T_total);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
 }
 
 }  // namespace rlhf

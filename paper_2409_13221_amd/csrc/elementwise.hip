@@ -60,9 +60,18 @@ __global__ __launch_bounds__(256) void k_rmsnorm(float* __restrict__ h, const fl
         const int i = (it * 256 + threadIdx.x) * 8;
         if (i < d) {
             load8<float>(hrow + i, v[it]);
-            for (int s = 0; s < nsplit; ++s) {
+            const float* pp = part + (size_t)src * d + i;
+            int s = 0;
+            for (; s + 2 <= nsplit; s += 2) {          // two partial planes in flight at a time
+                float p[8], p2[8];
+                load8<float>(pp + s * sstride, p);
+                load8<float>(pp + (s + 1) * sstride, p2);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[it][e] += p[e] + p2[e];
+            }
+            if (s < nsplit) {
                 float p[8];
-                load8<float>(part + s * sstride + (size_t)src * d + i, p);
+                load8<float>(pp + s * sstride, p);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[it][e] += p[e];
             }
@@ -102,65 +111,73 @@ hipError_t launch_rmsnorm(hipStream_t st, int adt, float* h, const float* part, 
 
 // ---------------------------------------------------------------- rotary + KV-cache append
 // rope_table: [max_pos][hd/2][2] = (cos, sin) of pos * base^(-2k/hd), computed in double on
-// the host.  Pair (k, k + hd/2) is rotated.
+// the host.  Pair (k, k + hd/2) is rotated.  One wave per (row, head): the Hq query heads, then
+// the Hkv key heads, then the Hkv value heads (copied).  Split-K partials are summed four at a
+// time so that their loads are in flight together.
+__device__ __forceinline__ float sum_partials(const float* p, int nsplit, size_t sstride) {
+    float a0 = p[0], a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    int s = 1;
+    for (; s + 3 <= nsplit; s += 3) {
+        a1 += p[s * sstride];
+        a2 += p[(s + 1) * sstride];
+        a3 += p[(s + 2) * sstride];
+    }
+    for (; s < nsplit; ++s) a1 += p[s * sstride];
+    return (a0 + a1) + (a2 + a3);
+}
+
 template <typename T, typename TP>
-__global__ __launch_bounds__(256) void k_rope_kv(const float* __restrict__ qkv, int nsplit,
-                                                 size_t sstride, const int* __restrict__ pos,
-                                                 const int* __restrict__ kv_dst,
-                                                 const float* __restrict__ rope_table,
-                                                 T* __restrict__ q_out, T* __restrict__ k_out,
-                                                 T* __restrict__ v_out, TP* __restrict__ pool,
-                                                 int layer, Dims dm) {
-    const int r = blockIdx.x;
+__global__ __launch_bounds__(64) void k_rope_kv(const float* __restrict__ qkv, int nsplit,
+                                                size_t sstride, const int* __restrict__ pos,
+                                                const int* __restrict__ kv_dst,
+                                                const float* __restrict__ rope_table,
+                                                T* __restrict__ q_out, T* __restrict__ k_out,
+                                                T* __restrict__ v_out, TP* __restrict__ pool,
+                                                int layer, Dims dm) {
+    const int r = blockIdx.x, hh = blockIdx.y;
     const int hd = dm.head_dim, half = hd >> 1;
     const int Hq = dm.n_q_heads, Hkv = dm.n_kv_heads;
     const int qkv_w = (Hq + 2 * Hkv) * hd;
-    const float* x = qkv + (size_t)r * qkv_w;
-    const float* tab = rope_table + (size_t)pos[r] * hd;  // hd/2 pairs of (cos, sin)
+    const float* x = qkv + (size_t)r * qkv_w + (size_t)hh * hd;
     const int slot = (pool && kv_dst) ? kv_dst[r] : -1;
-    TP* pk = nullptr;
-    TP* pv = nullptr;
+    TP* pbase = nullptr;                       // K block of this layer at this token slot
     if (slot >= 0) {
         const int pt = dm.page_tokens;
         const size_t page = slot / pt, off = slot % pt;
-        const size_t layer_base = (page * dm.n_layers + layer) * 2 * (size_t)Hkv * pt * hd;
-        pk = pool + layer_base + off * hd;                        // + kh * pt * hd + e
-        pv = pool + layer_base + (size_t)Hkv * pt * hd + off * hd;
+        pbase = pool + (page * dm.n_layers + layer) * 2 * (size_t)Hkv * pt * hd + off * hd;
     }
-    const int n_rot = (Hq + Hkv) * half;
-    for (int i = threadIdx.x; i < n_rot; i += 256) {
-        const int hh = i / half, k = i - hh * half;
-        const int col = hh * hd + k;
-        float a = x[col], b = x[col + half];
-        for (int s = 1; s < nsplit; ++s) {
-            a += x[s * sstride + col];
-            b += x[s * sstride + col + half];
-        }
-        const float c = tab[2 * k], sn = tab[2 * k + 1];
-        const float fa = a * c - b * sn, fb = a * sn + b * c;
-        if (hh < Hq) {
-            q_out[(size_t)r * Hq * hd + col] = from_f32<T>(fa);
-            q_out[(size_t)r * Hq * hd + col + half] = from_f32<T>(fb);
-        } else {
-            const int kh = hh - Hq;
-            if (k_out) {
-                k_out[(size_t)r * Hkv * hd + kh * hd + k] = from_f32<T>(fa);
-                k_out[(size_t)r * Hkv * hd + kh * hd + k + half] = from_f32<T>(fb);
+    const size_t head_stride = (size_t)dm.page_tokens * hd;      // between KV heads inside a page
+    if (hh < Hq + Hkv) {
+        const float* tab = rope_table + (size_t)pos[r] * hd;
+        for (int k = threadIdx.x; k < half; k += 64) {
+            const float a = sum_partials(x + k, nsplit, sstride);
+            const float b = sum_partials(x + k + half, nsplit, sstride);
+            const float c = tab[2 * k], sn = tab[2 * k + 1];
+            const float fa = a * c - b * sn, fb = a * sn + b * c;
+            if (hh < Hq) {
+                T* dst = q_out + ((size_t)r * Hq + hh) * hd;
+                dst[k] = from_f32<T>(fa);
+                dst[k + half] = from_f32<T>(fb);
+            } else {
+                const int kh = hh - Hq;
+                if (k_out) {
+                    T* dst = k_out + ((size_t)r * Hkv + kh) * hd;
+                    dst[k] = from_f32<T>(fa);
+                    dst[k + half] = from_f32<T>(fb);
+                }
+                if (pbase) {
+                    TP* dst = pbase + kh * head_stride;
+                    dst[k] = from_f32<TP>(fa);
+                    dst[k + half] = from_f32<TP>(fb);
+                }
             }
-            if (pk) {
-                pk[(size_t)kh * dm.page_tokens * hd + k] = from_f32<TP>(fa);
-                pk[(size_t)kh * dm.page_tokens * hd + k + half] = from_f32<TP>(fb);
-            }
         }
-    }
-    const int vbase = (Hq + Hkv) * hd;
-    for (int i = threadIdx.x; i < Hkv * hd; i += 256) {
-        float a = x[vbase + i];
-        for (int s = 1; s < nsplit; ++s) a += x[s * sstride + vbase + i];
-        if (v_out) v_out[(size_t)r * Hkv * hd + i] = from_f32<T>(a);
-        if (pv) {
-            const int kh = i / hd, e = i - kh * hd;
-            pv[(size_t)kh * dm.page_tokens * hd + e] = from_f32<TP>(a);
+    } else {
+        const int kh = hh - Hq - Hkv;
+        for (int e = threadIdx.x; e < hd; e += 64) {
+            const float a = sum_partials(x + e, nsplit, sstride);
+            if (v_out) v_out[((size_t)r * Hkv + kh) * hd + e] = from_f32<T>(a);
+            if (pbase) pbase[(size_t)Hkv * head_stride + kh * head_stride + e] = from_f32<TP>(a);
         }
     }
 }
@@ -170,18 +187,19 @@ hipError_t launch_rope_kv(hipStream_t st, int qdt, int pdt, const float* qkv, in
                           void* q_out, void* k_out, void* v_out, void* pool, int layer, int rows,
                           const Dims& dm) {
     if (rows <= 0) return hipSuccess;
+    dim3 grid(rows, dm.n_q_heads + 2 * dm.n_kv_heads);
     if (qdt == kBF16 && pdt == kBF16)
-        k_rope_kv<bf16_t, bf16_t><<<rows, 256, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
-                                                        (bf16_t*)q_out, (bf16_t*)k_out, (bf16_t*)v_out,
-                                                        (bf16_t*)pool, layer, dm);
-    else if (qdt == kF32 && pdt == kBF16)
-        k_rope_kv<float, bf16_t><<<rows, 256, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
-                                                       (float*)q_out, (float*)k_out, (float*)v_out,
+        k_rope_kv<bf16_t, bf16_t><<<grid, 64, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
+                                                       (bf16_t*)q_out, (bf16_t*)k_out, (bf16_t*)v_out,
                                                        (bf16_t*)pool, layer, dm);
+    else if (qdt == kF16 && pdt == kBF16)
+        k_rope_kv<f16_t, bf16_t><<<grid, 64, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
+                                                      (f16_t*)q_out, (f16_t*)k_out, (f16_t*)v_out,
+                                                      (bf16_t*)pool, layer, dm);
     else if (qdt == kF32 && pdt == kF32)
-        k_rope_kv<float, float><<<rows, 256, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
-                                                      (float*)q_out, (float*)k_out, (float*)v_out,
-                                                      (float*)pool, layer, dm);
+        k_rope_kv<float, float><<<grid, 64, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
+                                                     (float*)q_out, (float*)k_out, (float*)v_out,
+                                                     (float*)pool, layer, dm);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

@@ -192,6 +192,8 @@ struct rlhf_ctx {
 
 namespace {
 
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
 // Run `launch` (a callable returning hipError_t), timing it if this launch is sampled.
 template <typename F>
 hipError_t profiled(rlhf_ctx* c, hipStream_t st, int cls, double bytes, double flops, F&& launch) {
@@ -259,7 +261,7 @@ int alloc_workspace(rlhf_ctx* c, Workspace& ws, int rows, bool decode) {
     HIPCK(c, dev_alloc(&ws, &ws.h, rows * d * 4));
     HIPCK(c, dev_alloc(&ws, (char**)&ws.xn, rows * d * es));
     HIPCK(c, dev_alloc(&ws, &ws.part, ws.part_cap * 4));
-    HIPCK(c, dev_alloc(&ws, (char**)&ws.q, rows * qd * (decode ? es : 4)));   // batch passes: float q/k/v
+    HIPCK(c, dev_alloc(&ws, (char**)&ws.q, rows * qd * es));
     HIPCK(c, dev_alloc(&ws, (char**)&ws.attn, rows * qd * es));
     HIPCK(c, dev_alloc(&ws, (char**)&ws.act, rows * f * es));
     HIPCK(c, dev_alloc(&ws, (char**)&ws.xsel, rows * d * es));
@@ -267,8 +269,8 @@ int alloc_workspace(rlhf_ctx* c, Workspace& ws, int rows, bool decode) {
         HIPCK(c, dev_alloc(&ws, &ws.attn_acc, ws.attn_slots * m.head_dim * 4));
         HIPCK(c, dev_alloc(&ws, &ws.attn_ml, ws.attn_slots * 2 * 4));
     } else {
-        HIPCK(c, dev_alloc(&ws, (char**)&ws.k, rows * kvd * 4));
-        HIPCK(c, dev_alloc(&ws, (char**)&ws.v, rows * kvd * 4));
+        HIPCK(c, dev_alloc(&ws, (char**)&ws.k, rows * kvd * es));
+        HIPCK(c, dev_alloc(&ws, (char**)&ws.v, rows * kvd * es));
         HIPCK(c, dev_alloc(&ws, &ws.logits, (size_t)ws.logit_rows * V * 4));
     }
     return RLHF_OK;
@@ -298,7 +300,11 @@ struct PassMeta {         // device pointers into a MetaRing arena
     const int* kv_dst = nullptr;       // NULL: no pool writes
     const int* row_sample = nullptr;   // decode
     const int* ctx_len = nullptr;      // decode
-    const int* row_start = nullptr;    // batch
+    const int* row_start = nullptr;    // batch (float models)
+    const int* tile_start = nullptr;   // batch (bf16 models): query tiles of the MFMA attention
+    const int* tile_q0 = nullptr;
+    const int* tile_len = nullptr;
+    int n_tiles = 0;
     double attn_bytes = 0, attn_flops = 0;   // algorithmic, per layer (for the profiler)
 };
 
@@ -313,7 +319,7 @@ int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
     const int qkv_w = qd + 2 * kvd, f = m.ffn, es = c->esz, dt = c->dtype;
     const int gcls = mode == kModeDecode ? kGemmDecode : kGemmBatch;
     const int adt = act_type(c, mode == kModeBatch);
-    const int qdt = mode == kModeBatch ? kF32 : dt;
+    const int qdt = adt;               // q/k/v of a pass share the activation type
     HIPCK(c, launch_embed(st, dt, c->d_tokens, pm.tok_idx, w.embed, ws.h, rows, d, m.vocab));
     int pns = 0;
     size_t pstride = 0;
@@ -334,6 +340,9 @@ int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
             }));
         } else {
             HIPCK(c, profiled(c, st, kAttnBatch, pm.attn_bytes, pm.attn_flops, [&] {
+                if (adt == kF16)
+                    return launch_flash_attn(st, ws.q, ws.k, ws.v, pm.tile_start, pm.tile_q0, pm.tile_len, ws.attn,
+                                             pm.n_tiles, rows, c->dm);
                 return launch_prefill_attn(st, adt, (const float*)ws.q, (const float*)ws.k, (const float*)ws.v,
                                            pm.row_start, pm.pos, ws.attn, rows, c->dm);
             }));
@@ -354,8 +363,6 @@ int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
     *pend_stride = pstride;
     return RLHF_OK;
 }
-
-int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 }  // namespace
 
@@ -462,9 +469,9 @@ static int create_impl(rlhf_ctx* c) {
     if ((rc = alloc_workspace(c, c->ws_score, e.max_batch_tokens, false))) return rc;
     HIPCK(c, c->meta_dec.init((size_t)e.max_active * 10 + (size_t)e.max_active * 2 + 64));
     // prefill metadata also carries the page-table updates of the admitted prompts
-    HIPCK(c, c->meta_pre.init((size_t)e.max_batch_tokens * 8 + (size_t)e.max_samples * 8 +
+    HIPCK(c, c->meta_pre.init((size_t)e.max_batch_tokens * 9 + (size_t)e.max_samples * 12 +
                               2 * ((size_t)e.max_batch_tokens / e.page_tokens + e.max_samples) + 64));
-    HIPCK(c, c->meta_score.init((size_t)e.max_batch_tokens * 8 + (size_t)e.max_samples * 4 + 64));
+    HIPCK(c, c->meta_score.init((size_t)e.max_batch_tokens * 9 + (size_t)e.max_samples * 8 + 64));
     return RLHF_OK;
 }
 
@@ -628,6 +635,26 @@ int lm_head_chunks(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
     return RLHF_OK;
 }
 
+// Query tiles of the MFMA attention for sequences of the given lengths packed back to back:
+// writes tile_start / tile_q0 / tile_len (n each) at dst, dst + n, dst + 2n; returns n.
+int count_tiles(const std::vector<int>& lens) {
+    int n = 0;
+    for (int L : lens) n += ceil_div(L, kFlashTile);
+    return n;
+}
+void fill_tiles(const std::vector<int>& lens, int* dst) {
+    const int n = count_tiles(lens);
+    int t = 0, start = 0;
+    for (int L : lens) {
+        for (int q0 = 0; q0 < L; q0 += kFlashTile, ++t) {
+            dst[t] = start;
+            dst[n + t] = q0;
+            dst[2 * n + t] = L;
+        }
+        start += L;
+    }
+}
+
 // Algorithmic cost of one layer's packed causal attention over the current lengths of `ids`.
 void batch_attn_cost(const rlhf_ctx* c, const std::vector<int>& ids, int T, PassMeta* pm) {
     const double qd = (double)c->mc.n_q_heads * c->mc.head_dim, kvd = (double)c->mc.n_kv_heads * c->mc.head_dim;
@@ -684,8 +711,13 @@ int prefill_group(rlhf_ctx* c, const std::vector<int>& group, int T) {
     const int U = (int)upd_idx.size();
     std::copy(upd_idx.begin(), upd_idx.end(), upd);
     std::copy(upd_val.begin(), upd_val.end(), upd + U);
-    const size_t n_ints = (size_t)4 * T + 4 * n + 2 * U;
+    std::vector<int> lens;
+    for (int i : group) lens.push_back(c->smp[i].P);
+    const int n_tiles = count_tiles(lens);
+    const size_t tiles_off = (size_t)4 * T + 4 * n + 2 * U;
+    const size_t n_ints = tiles_off + 3 * (size_t)n_tiles;
     if (n_ints > c->meta_pre.cap) return c->fail(RLHF_EINVAL, "internal: prefill metadata overflow");
+    fill_tiles(lens, hm + tiles_off);
     HIPCK(c, c->meta_pre.commit(c->sd, n_ints));
     const int* dm_ = c->meta_pre.dev;
     HIPCK(c, launch_scatter_int(c->sd, c->d_page_table, dm_ + 4 * T + 4 * n, dm_ + 4 * T + 4 * n + U, U));
@@ -695,6 +727,10 @@ int prefill_group(rlhf_ctx* c, const std::vector<int>& group, int T) {
     pm.pos = dm_ + T;
     pm.row_start = dm_ + 2 * T;
     pm.kv_dst = dm_ + 3 * T;
+    pm.tile_start = dm_ + tiles_off;
+    pm.tile_q0 = dm_ + tiles_off + n_tiles;
+    pm.tile_len = dm_ + tiles_off + 2 * n_tiles;
+    pm.n_tiles = n_tiles;
     batch_attn_cost(c, group, T, &pm);
     const rlhf_weights& w = c->roles[RLHF_ACTOR].w;
     Workspace& ws = c->ws_pre;
@@ -914,7 +950,12 @@ int score_pass(rlhf_ctx* c, hipStream_t st, MetaRing& meta, Workspace& ws, const
     int* sel = hm + 3 * T;
     int* target = sel + n_sel;
     int* out_dst = target + n_sel;
-    if ((size_t)3 * T + 3 * n_sel > meta.cap) return c->fail(RLHF_EINVAL, "internal: scoring metadata overflow");
+    std::vector<int> lens;
+    for (int k = 0; k < n; ++k) lens.push_back(c->smp[ids[k]].P + c->smp[ids[k]].gen_len);
+    const int n_tiles = count_tiles(lens);
+    const size_t tiles_off = (size_t)3 * T + 3 * n_sel;
+    if (tiles_off + 3 * (size_t)n_tiles > meta.cap) return c->fail(RLHF_EINVAL, "internal: scoring metadata overflow");
+    fill_tiles(lens, hm + tiles_off);
     int row = 0, si = 0;
     for (int k = 0; k < n; ++k) {
         const int i = ids[k];
@@ -938,12 +979,16 @@ int score_pass(rlhf_ctx* c, hipStream_t st, MetaRing& meta, Workspace& ws, const
             }
         }
     }
-    HIPCK(c, meta.commit(st, (size_t)3 * T + 3 * n_sel));
+    HIPCK(c, meta.commit(st, tiles_off + 3 * (size_t)n_tiles));
     const int* dmeta = meta.dev;
     PassMeta pm;
     pm.tok_idx = dmeta;
     pm.pos = dmeta + T;
     pm.row_start = dmeta + 2 * T;
+    pm.tile_start = dmeta + tiles_off;
+    pm.tile_q0 = dmeta + tiles_off + n_tiles;
+    pm.tile_len = dmeta + tiles_off + 2 * n_tiles;
+    pm.n_tiles = n_tiles;
     batch_attn_cost(c, std::vector<int>(ids, ids + n), T, &pm);
     const rlhf_weights& w = c->roles[role].w;
     int pns;

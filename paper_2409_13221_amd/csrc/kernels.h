@@ -37,7 +37,7 @@ hipError_t launch_rmsnorm(hipStream_t st, int adt, float* h, const float* part, 
 // Rotary on Q and K heads of qkv rows.  q_out [rows, Hq*hd] and, if non-NULL, k_out/v_out
 // [rows, Hkv*hd] have type qdt; if pool != NULL and kv_dst[r] >= 0, K/V of row r also go (as
 // type pdt) to token slot kv_dst[r] (= page * page_tokens + offset) of `layer` in the paged pool.
-// (qdt, pdt) in {(kF32,kF32), (kBF16,kBF16), (kF32,kBF16)}.
+// (qdt, pdt) in {(kF32,kF32), (kBF16,kBF16), (kF16,kBF16)}.
 hipError_t launch_rope_kv(hipStream_t st, int qdt, int pdt, const float* qkv, int nsplit, size_t sstride,
                           const int* pos, const int* kv_dst, const float* rope_table,
                           void* q_out, void* k_out, void* v_out, void* pool, int layer,
@@ -73,6 +73,15 @@ hipError_t launch_decode_attn(hipStream_t st, int dtype, const void* q, const vo
 hipError_t launch_prefill_attn(hipStream_t st, int odt, const float* q, const float* k,
                                const float* v, const int* row_start, const int* row_pos,
                                void* out, int rows, const Dims& dm);
+
+// The same on the matrix units for bf16 models: q, k, v, out IEEE half.  The queries are cut
+// into tiles of kFlashTile rows that never straddle a sequence: tile i covers rows
+// tile_start[i] + tile_q0[i] .. of the sequence that starts at row tile_start[i] and has
+// tile_len[i] rows.  T_total = rows of the packed buffers (loads are clamped to it).
+constexpr int kFlashTile = 128;
+hipError_t launch_flash_attn(hipStream_t st, const void* q, const void* k, const void* v,
+                             const int* tile_start, const int* tile_q0, const int* tile_len, void* out,
+                             int n_tiles, int T_total, const Dims& dm);
 
 size_t pool_page_elems(const Dims& dm);  // elements of one page over all layers
 

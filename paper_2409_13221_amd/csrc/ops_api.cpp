@@ -53,3 +53,14 @@ extern "C" int rlhf_op_varlen_attention(int out_half, const float* q, const floa
     return status_of(launch_prefill_attn((hipStream_t)stream, out_half ? kF16 : kF32, q, k, v, row_start,
                                          row_pos, out, rows, dm));
 }
+
+extern "C" int rlhf_op_flash_attention(const void* q, const void* k, const void* v, const int32_t* tile_start,
+                                       const int32_t* tile_q0, const int32_t* tile_len, void* out, int n_tiles,
+                                       int rows, int n_q_heads, int n_kv_heads, int head_dim, void* stream) {
+    if (!q || !k || !v || !tile_start || !tile_q0 || !tile_len || !out || n_tiles < 0 || rows <= 0 ||
+        n_kv_heads <= 0 || n_q_heads % n_kv_heads)
+        return RLHF_EINVAL;
+    Dims dm{1, n_q_heads * head_dim, n_q_heads, n_kv_heads, head_dim, 0, 0, 16};
+    return status_of(launch_flash_attn((hipStream_t)stream, q, k, v, tile_start, tile_q0, tile_len, out, n_tiles,
+                                       rows, dm));
+}

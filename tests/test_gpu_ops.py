@@ -97,8 +97,29 @@ def test_paged_decode_attention(dtype, Hq, Hkv, hd, nsplit):
     np.testing.assert_allclose(got, want, rtol=0, atol=tol)
 
 
-@pytest.mark.parametrize("dtype,Hq,Hkv,hd", [("half", 4, 4, 128), ("half", 8, 1, 128), ("half", 2, 2, 64),
-                                             ("fp32", 4, 4, 64), ("fp32", 2, 2, 128)])
+@pytest.mark.parametrize("Hq,Hkv,hd", [(4, 4, 128), (8, 1, 128), (3, 3, 64)])
+def test_flash_attention(Hq, Hkv, hd):
+    """MFMA attention of bf16 models: several query tiles, ragged tails, tiny sequences."""
+    R = _R()
+    lens = [1, 130, 64, 300, 17, 128, 257]
+    T = sum(lens)
+    torch.manual_seed(5)
+    q, k, v = (torch.randn(T, Hq, hd) * 1.5).half(), torch.randn(T, Hkv, hd).half(), torch.randn(T, Hkv, hd).half()
+    want, o = np.zeros((T, Hq, hd)), 0
+    for n in lens:
+        want[o:o + n] = OT.attention(q[o:o + n].double().numpy(), k[o:o + n].double().numpy(),
+                                     v[o:o + n].double().numpy(), np.arange(n))
+        o += n
+    out = torch.zeros(T, Hq * hd, dtype=torch.float16, device="cuda")
+    keep = R.rlhf_op_flash_attention(q.cuda().reshape(T, -1).contiguous(), k.cuda().reshape(T, -1).contiguous(),
+                                     v.cuda().reshape(T, -1).contiguous(), lens, out, Hq, Hkv, hd)
+    torch.cuda.synchronize()
+    del keep
+    # probabilities and the output are rounded to half: 2^-11 relative on values of size ~1-3
+    np.testing.assert_allclose(out.double().cpu().numpy().reshape(T, Hq, hd), want, rtol=0, atol=4e-3)
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,hd", [("fp32", 4, 4, 64), ("fp32", 2, 2, 128)])
 def test_varlen_attention(dtype, Hq, Hkv, hd):
     R = _R()
     lens = [1, 7, 16, 17, 40, 3]
