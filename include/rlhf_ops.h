@@ -21,11 +21,13 @@ extern "C" {
  * C[s][m][n] = sum over the s-th K range of A[m][k] * W[n][k].  W [N,K] row-major in dtype;
  * A [M,K] in dtype, or (act_half != 0, bf16 weights only) in IEEE half, the activation type
  * of prefill / scoring passes; C float32 [nsplit][M][N]; the caller sums the nsplit partial
- * planes.  K must be a multiple of 8 (bf16) or 4 (fp32).  rlhf_op_gemm_nsplit returns the
- * split the stage itself would choose for this shape, at most max_split. */
+ * planes.  K must be a multiple of 8 (bf16) or 4 (fp32).  variant 0 takes the tiling the
+ * stage uses for M rows; a positive value forces one of the library's tilings (benchmarks;
+ * RLHF_EINVAL if it does not exist or cannot split K).  rlhf_op_gemm_nsplit returns the split
+ * the stage itself would choose for this shape, at most max_split. */
 int rlhf_op_gemm_nsplit(int dtype, int M, int N, int K, int max_split);
 int rlhf_op_gemm(int dtype, int act_half, const void* A, const void* W, float* C, int M, int N, int K,
-                 int nsplit, void* stream);
+                 int nsplit, int variant, void* stream);
 
 /* Decode attention of one step (Section 2.1, decoding phase): row r holds one query
  * [n_q_heads * head_dim] and attends to the ctx_len[r] cached tokens of the sample whose

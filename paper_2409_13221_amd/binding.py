@@ -116,7 +116,7 @@ def lib() -> C.CDLL:
         L.rlhf_profile_begin.argtypes = [vp, i32]
         L.rlhf_profile_end.argtypes = [vp, C.POINTER(rlhf_kernel_profile)]
         L.rlhf_op_gemm_nsplit.argtypes = [C.c_int] * 5
-        L.rlhf_op_gemm.argtypes = [C.c_int, C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp]
+        L.rlhf_op_gemm.argtypes = [C.c_int, C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp]
         L.rlhf_op_paged_decode_attention.argtypes = [C.c_int, vp, vp, vp, C.c_int, vp, vp, vp, vp, vp] + [C.c_int] * 7 + [vp]
         L.rlhf_op_varlen_attention.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp] + [C.c_int] * 4 + [vp]
         L.rlhf_op_flash_attention.argtypes = [vp] * 7 + [C.c_int] * 5 + [vp]
@@ -305,7 +305,7 @@ def rlhf_op_gemm_nsplit(dtype: int, M: int, N: int, K: int, max_split: int) -> i
     return lib().rlhf_op_gemm_nsplit(dtype, M, N, K, max_split)
 
 
-def rlhf_op_gemm(A, W, C_out, nsplit: int) -> None:
+def rlhf_op_gemm(A, W, C_out, nsplit: int, variant: int = 0) -> None:
     """W [N,K] (bf16 or fp32), A [M,K] of W's dtype or float16 (with bf16 W), C_out float32
     [nsplit, M, N]; on torch's current stream."""
     import torch
@@ -315,7 +315,7 @@ def rlhf_op_gemm(A, W, C_out, nsplit: int) -> None:
     half = A.dtype == torch.float16
     assert half or A.dtype == W.dtype
     _op_check(lib().rlhf_op_gemm(_dt(W), int(half), A.data_ptr(), W.data_ptr(), C_out.data_ptr(), M, N, K, nsplit,
-                                 _stream_ptr()), "rlhf_op_gemm")
+                                 variant, _stream_ptr()), "rlhf_op_gemm")
 
 
 def rlhf_op_paged_decode_attention(q, pool, page_table, row_sample, ctx_len, out, part_acc, part_ml, layer: int,

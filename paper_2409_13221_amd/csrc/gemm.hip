@@ -17,12 +17,14 @@
 
 namespace rlhf {
 
-constexpr int kTK = 64;  // K extent of one LDS tile (bf16 elements): 8 chunks of 16 bytes per row
+// 16-byte chunk swizzle inside an LDS tile row: the fragment read of a quarter wave takes one
+// chunk column of 16 consecutive rows; XOR-ing the chunk index with row bits spreads those 16
+// reads over all banks (rows of 128 bytes: two rows per 256-byte bank sweep; rows of 64 bytes:
+// four).
+template <int TK> __device__ __forceinline__ int swz(int row, int chunk) {
+    return TK == 64 ? (chunk ^ ((row >> 1) & 7)) : (chunk ^ ((row >> 2) & 3));
+}
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
-
-// TM x TN output tile per workgroup of 4 waves arranged WM x WN; each wave owns
-// (TM/WM) x (TN/WN), built from 16x16 MFMA fragments.
 template <bool AF16> struct Mfma;
 template <> struct Mfma<false> {
     typedef bf16x8_t frag;
@@ -37,37 +39,68 @@ template <> struct Mfma<true> {
     }
 };
 
-// A: 16-bit activations (bf16 if !AF16, half if AF16); W: bf16.
-template <int TM, int TN, int WM, int WN, bool AF16>
-__global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
-                                                   const bf16_t* __restrict__ W,
-                                                   float* __restrict__ C, int M, int N, int K,
-                                                   int kchunk, int tiles_n) {
-    static_assert(WM * WN == 4, "four waves");
-    constexpr int FM = TM / WM / 16, FN = TN / WN / 16;
-    constexpr int A_CH = TM * 8, B_CH = TN * 8;          // 16-byte chunks per tile
-    constexpr int A_IT = (A_CH + 255) / 256, B_IT = (B_CH + 255) / 256;
-    __shared__ __attribute__((aligned(16))) bf16_t sA[2][TM * kTK];
-    __shared__ __attribute__((aligned(16))) bf16_t sB[2][TN * kTK];
+// Tile index of a workgroup.  Few-row launches (XCD == false) walk the N tiles in order.
+// Compute-bound launches (XCD == true): tiles are numbered in panels of kGroupM tile rows,
+// column by column inside a panel, and each of the 8 XCDs (workgroup id modulo 8, the order in
+// which the dispatcher deals workgroups to XCDs) walks its own contiguous eighth of that
+// numbering.  The workgroups resident on one XCD at a time then cover a compact block of the
+// output, so its L2 re-serves the A rows and W rows they share, and every XCD gets the same
+// number of tiles whatever the shape.
+constexpr int kGroupM = 8;
+template <bool XCD>
+__device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
+    if (!XCD) {
+        tm = bid / tiles_n;
+        tn = bid - tm * tiles_n;
+        return true;
+    }
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + 7) >> 3;
+    const int pid = (bid & 7) * per_xcd + (bid >> 3);
+    if ((bid >> 3) >= per_xcd || pid >= total) return false;
+    const int in_panel = kGroupM * tiles_n;
+    const int panel = pid / in_panel, r = pid - panel * in_panel;
+    const int first = panel * kGroupM;
+    const int rows = min(tiles_m - first, kGroupM);
+    tm = first + r % rows;
+    tn = r / rows;
+    return true;
+}
 
-    const int tile = blockIdx.x;
-    const int tm = tile / tiles_n, tn = tile - tm * tiles_n;
+// A: 16-bit activations (bf16 if !AF16, half if AF16); W: bf16.
+// TM x TN output tile per workgroup of WM x WN waves; each wave owns (TM/WM) x (TN/WN), built
+// from 16x16 MFMA fragments; K advances in LDS tiles of TK (32 or 64) elements, double-buffered.
+template <int TM, int TN, int TK, int WM, int WN, bool AF16, bool XCD>
+__global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __restrict__ A,
+                                                           const bf16_t* __restrict__ W,
+                                                           float* __restrict__ C, int M, int N, int K,
+                                                           int kchunk, int tiles_m, int tiles_n) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int FM = TM / WM / 16, FN = TN / WN / 16;
+    constexpr int CH = TK / 8;                            // 16-byte chunks per tile row
+    constexpr int A_CH = TM * CH, B_CH = TN * CH;
+    constexpr int A_IT = (A_CH + NT - 1) / NT, B_IT = (B_CH + NT - 1) / NT;
+    __shared__ __attribute__((aligned(16))) bf16_t sA[2][TM * TK];
+    __shared__ __attribute__((aligned(16))) bf16_t sB[2][TN * TK];
+
+    int tm, tn;
+    if (!tile_of<XCD>(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     const int m0 = tm * TM, n0 = tn * TN;
     const int split = blockIdx.y;
     const int kbeg = split * kchunk;
     const int kend = min(K, kbeg + kchunk);
-    const int nk = (kend - kbeg + kTK - 1) / kTK;
+    const int nk = (kend - kbeg + TK - 1) / TK;
 
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     const int wm = w / WN, wn = w - wm * WN;
 
     uint4 ra[A_IT], rb[B_IT];
     auto gload = [&](int kt) {
-        const int k0 = kbeg + kt * kTK;
+        const int k0 = kbeg + kt * TK;
 #pragma unroll
         for (int i = 0; i < A_IT; ++i) {
-            const int idx = t + i * 256;
-            const int row = idx >> 3, c = idx & 7;
+            const int idx = t + i * NT;
+            const int row = idx / CH, c = idx % CH;
             const int gm = m0 + row, gk = k0 + c * 8;
             ra[i] = make_uint4(0, 0, 0, 0);
             if (idx < A_CH && gm < M && gk < kend)
@@ -75,32 +108,32 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
         }
 #pragma unroll
         for (int i = 0; i < B_IT; ++i) {
-            const int idx = t + i * 256;
-            const int row = idx >> 3, c = idx & 7;
+            const int idx = t + i * NT;
+            const int row = idx / CH, c = idx % CH;
             const int gn = n0 + row, gk = k0 + c * 8;
             rb[i] = make_uint4(0, 0, 0, 0);
             if (idx < B_CH && gn < N && gk < kend)
                 rb[i] = *reinterpret_cast<const uint4*>(W + (size_t)gn * K + gk);
-            if (AF16) {
-                rb[i].x = bf16x2_to_f16x2(rb[i].x); rb[i].y = bf16x2_to_f16x2(rb[i].y);
-                rb[i].z = bf16x2_to_f16x2(rb[i].z); rb[i].w = bf16x2_to_f16x2(rb[i].w);
-            }
         }
     };
     auto sstore = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < A_IT; ++i) {
-            const int idx = t + i * 256;
-            const int row = idx >> 3, c = idx & 7;
+            const int idx = t + i * NT;
+            const int row = idx / CH, c = idx % CH;
             if (idx < A_CH)
-                *reinterpret_cast<uint4*>(&sA[buf][row * kTK + swz(row, c) * 8]) = ra[i];
+                *reinterpret_cast<uint4*>(&sA[buf][row * TK + swz<TK>(row, c) * 8]) = ra[i];
         }
 #pragma unroll
         for (int i = 0; i < B_IT; ++i) {
-            const int idx = t + i * 256;
-            const int row = idx >> 3, c = idx & 7;
+            const int idx = t + i * NT;
+            const int row = idx / CH, c = idx % CH;
+            if (AF16) {   // bf16 -> half, exact, once per element per workgroup
+                rb[i].x = bf16x2_to_f16x2(rb[i].x); rb[i].y = bf16x2_to_f16x2(rb[i].y);
+                rb[i].z = bf16x2_to_f16x2(rb[i].z); rb[i].w = bf16x2_to_f16x2(rb[i].w);
+            }
             if (idx < B_CH)
-                *reinterpret_cast<uint4*>(&sB[buf][row * kTK + swz(row, c) * 8]) = rb[i];
+                *reinterpret_cast<uint4*>(&sB[buf][row * TK + swz<TK>(row, c) * 8]) = rb[i];
         }
     };
 
@@ -120,18 +153,18 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
         const int buf = kt & 1;
         if (kt + 1 < nk) gload(kt + 1);
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
+        for (int s = 0; s < TK / 32; ++s) {
             typename Mfma<AF16>::frag fa[FM], fb[FN];
             const int c = s * 4 + fq;
 #pragma unroll
             for (int i = 0; i < FM; ++i) {
                 const int row = wm * (TM / WM) + i * 16 + fr;
-                fa[i] = *reinterpret_cast<const typename Mfma<AF16>::frag*>(&sA[buf][row * kTK + swz(row, c) * 8]);
+                fa[i] = *reinterpret_cast<const typename Mfma<AF16>::frag*>(&sA[buf][row * TK + swz<TK>(row, c) * 8]);
             }
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
                 const int row = wn * (TN / WN) + j * 16 + fr;
-                fb[j] = *reinterpret_cast<const typename Mfma<AF16>::frag*>(&sB[buf][row * kTK + swz(row, c) * 8]);
+                fb[j] = *reinterpret_cast<const typename Mfma<AF16>::frag*>(&sB[buf][row * TK + swz<TK>(row, c) * 8]);
             }
             // weights are the MFMA "A" operand: D[i = n][j = m], so a lane ends up holding four
             // consecutive n of one row m and stores them as one float4.
@@ -219,21 +252,34 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A,
 
 // ----------------------------------------------------------------------------- dispatch
 namespace {
-struct TileCfg { int tm, tn; };
+// Tilings.  Variants 1-4 stream the weights for few rows (split along K); 5.. are the
+// compute-bound tilings of prefill / scoring passes.
+struct TileCfg { int variant, tm, tn, tk; bool xcd; };
+constexpr TileCfg kCfgs[] = {
+    {0, 0, 0, 0, false},
+    {1, 16, 128, 64, false}, {2, 32, 128, 64, false}, {3, 64, 128, 64, false}, {4, 128, 128, 64, false},
+    {5, 128, 128, 64, true}, {6, 256, 128, 32, true}, {7, 256, 128, 64, true}, {8, 256, 256, 32, true},
+    {9, 128, 256, 32, true},
+};
+constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
-TileCfg pick_tile(int M) {
-    if (M <= 16) return {16, 128};
-    if (M <= 32) return {32, 128};
-    if (M <= 64) return {64, 128};
-    return {128, 128};
+int pick_variant(int M) {
+    if (M <= 16) return 1;
+    if (M <= 32) return 2;
+    if (M <= 64) return 3;
+    if (M <= 256) return 4;
+    return M >= 1024 ? 6 : 5;
 }
 constexpr int kTargetBlocks = 1024;  // about four workgroups per compute unit
 }  // namespace
 
 int gemm_choose_nsplit(int wdt, int M, int N, int K, int max_split) {
     int tm, tn, kgran;
-    if (wdt == kBF16) { TileCfg c = pick_tile(M); tm = c.tm; tn = c.tn; kgran = kTK; }
-    else { tm = 64; tn = 64; kgran = 16; }
+    if (wdt == kBF16) {
+        const TileCfg& c = kCfgs[pick_variant(M)];
+        if (c.xcd) return 1;
+        tm = c.tm; tn = c.tn; kgran = c.tk;
+    } else { tm = 64; tn = 64; kgran = 16; }
     const long tiles = (long)((M + tm - 1) / tm) * ((N + tn - 1) / tn);
     int ns = (int)((kTargetBlocks + tiles - 1) / tiles);
     const int kmax = K / (4 * kgran) > 0 ? K / (4 * kgran) : 1;   // keep >= 4 K tiles per split
@@ -250,36 +296,55 @@ int gemm_choose_nsplit(int wdt, int M, int N, int K, int max_split) {
 }
 
 template <bool AF16>
-static void launch_bf16(hipStream_t st, int tm, dim3 grid, const bf16_t* a, const bf16_t* w, float* C, int M,
-                        int N, int K, int kchunk, int tiles_n) {
-    if (tm == 16) k_gemm_bf16<16, 128, 1, 4, AF16><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
-    else if (tm == 32) k_gemm_bf16<32, 128, 1, 4, AF16><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
-    else if (tm == 64) k_gemm_bf16<64, 128, 2, 2, AF16><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
-    else k_gemm_bf16<128, 128, 2, 2, AF16><<<grid, 256, 0, st>>>(a, w, C, M, N, K, kchunk, tiles_n);
+static hipError_t launch_bf16(hipStream_t st, int variant, const bf16_t* a, const bf16_t* w, float* C, int M,
+                              int N, int K, int nsplit) {
+    const TileCfg& c = kCfgs[variant];
+    const int tiles_m = (M + c.tm - 1) / c.tm, tiles_n = (N + c.tn - 1) / c.tn;
+    const int kchunk = ((K + nsplit - 1) / nsplit + c.tk - 1) / c.tk * c.tk;
+    int blocks = tiles_m * tiles_n;
+    if (c.xcd) blocks = (blocks + 7) / 8 * 8;
+    dim3 grid(blocks, nsplit);
+#define RLHF_GEMM(TM, TN, TK, WM, WN, XCD)                                                            \
+    k_gemm_bf16<TM, TN, TK, WM, WN, AF16, XCD><<<grid, WM * WN * 64, 0, st>>>(a, w, C, M, N, K, kchunk, \
+                                                                              tiles_m, tiles_n)
+    switch (variant) {
+        case 1: RLHF_GEMM(16, 128, 64, 1, 4, false); break;
+        case 2: RLHF_GEMM(32, 128, 64, 1, 4, false); break;
+        case 3: RLHF_GEMM(64, 128, 64, 2, 2, false); break;
+        case 4: RLHF_GEMM(128, 128, 64, 2, 2, false); break;
+        case 5: RLHF_GEMM(128, 128, 64, 2, 2, true); break;
+        case 6: RLHF_GEMM(256, 128, 32, 2, 2, true); break;
+        case 7: RLHF_GEMM(256, 128, 64, 2, 2, true); break;
+        case 8: RLHF_GEMM(256, 256, 32, 2, 2, true); break;
+        case 9: RLHF_GEMM(128, 256, 32, 2, 2, true); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef RLHF_GEMM
+    return hipGetLastError();
 }
 
 hipError_t launch_gemm(hipStream_t st, int wdt, int adt, const void* A, const void* W, float* C,
-                       int M, int N, int K, int nsplit) {
+                       int M, int N, int K, int nsplit, int variant) {
     if (M <= 0 || N <= 0) return hipSuccess;
     if (nsplit < 1 || K <= 0) return hipErrorInvalidValue;
     if (wdt == kBF16) {
         if (adt != kBF16 && adt != kF16) return hipErrorInvalidValue;
-        if (K % 8) return hipErrorInvalidValue;
-        const TileCfg c = pick_tile(M);
-        const int tiles_m = (M + c.tm - 1) / c.tm, tiles_n = (N + c.tn - 1) / c.tn;
-        const int kchunk = ((K + nsplit - 1) / nsplit + kTK - 1) / kTK * kTK;
-        dim3 grid(tiles_m * tiles_n, nsplit);
+        if (K % 8 || variant < 0 || variant >= kNumCfgs) return hipErrorInvalidValue;
+        if (variant == 0) {
+            variant = pick_variant(M);
+            if (kCfgs[variant].xcd && nsplit != 1) variant = 4;   // a caller-imposed split of a tall GEMM
+        }
+        if (kCfgs[variant].xcd && nsplit != 1) return hipErrorInvalidValue;
         const bf16_t* a = (const bf16_t*)A;
         const bf16_t* w = (const bf16_t*)W;
-        if (adt == kF16) launch_bf16<true>(st, c.tm, grid, a, w, C, M, N, K, kchunk, tiles_n);
-        else launch_bf16<false>(st, c.tm, grid, a, w, C, M, N, K, kchunk, tiles_n);
-    } else {
-        if (K % 4 || adt != kF32) return hipErrorInvalidValue;
-        const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
-        const int kchunk = ((K + nsplit - 1) / nsplit + 15) / 16 * 16;
-        dim3 grid(tiles_m * tiles_n, nsplit);
-        k_gemm_f32<<<grid, 256, 0, st>>>((const float*)A, (const float*)W, C, M, N, K, kchunk, tiles_n);
+        return adt == kF16 ? launch_bf16<true>(st, variant, a, w, C, M, N, K, nsplit)
+                           : launch_bf16<false>(st, variant, a, w, C, M, N, K, nsplit);
     }
+    if (K % 4 || adt != kF32) return hipErrorInvalidValue;
+    const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
+    const int kchunk = ((K + nsplit - 1) / nsplit + 15) / 16 * 16;
+    dim3 grid(tiles_m * tiles_n, nsplit);
+    k_gemm_f32<<<grid, 256, 0, st>>>((const float*)A, (const float*)W, C, M, N, K, kchunk, tiles_n);
     return hipGetLastError();
 }
 

@@ -23,8 +23,9 @@ struct Dims {
 // ---- GEMM: C[s][m][n] = sum over k in split s of A[m][k] * W[n][k];  C float, split stride M*N
 // (wdt, adt) in {(kF32,kF32), (kBF16,kBF16), (kBF16,kF16)}
 int gemm_choose_nsplit(int wdt, int M, int N, int K, int max_split);
+// variant 0 = the tiling chosen from M; > 0 forces one (tuning / benchmarks).
 hipError_t launch_gemm(hipStream_t st, int wdt, int adt, const void* A, const void* W, float* C,
-                       int M, int N, int K, int nsplit);
+                       int M, int N, int K, int nsplit, int variant = 0);
 
 // ---- elementwise / row kernels
 hipError_t launch_embed(hipStream_t st, int dtype, const int* tokens, const int* tok_idx,

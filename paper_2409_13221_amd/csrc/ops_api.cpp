@@ -19,12 +19,12 @@ extern "C" int rlhf_op_gemm_nsplit(int dtype, int M, int N, int K, int max_split
 }
 
 extern "C" int rlhf_op_gemm(int dtype, int act_half, const void* A, const void* W, float* C, int M, int N,
-                            int K, int nsplit, void* stream) {
+                            int K, int nsplit, int variant, void* stream) {
     if (!A || !W || !C || M < 0 || N < 0 || K <= 0 || nsplit < 1) return RLHF_EINVAL;
     if (dtype != RLHF_BF16 && dtype != RLHF_FP32) return RLHF_EINVAL;
     if (act_half && dtype != RLHF_BF16) return RLHF_EINVAL;
     const int wdt = dtype == RLHF_BF16 ? kBF16 : kF32;
-    return status_of(launch_gemm((hipStream_t)stream, wdt, act_half ? kF16 : wdt, A, W, C, M, N, K, nsplit));
+    return status_of(launch_gemm((hipStream_t)stream, wdt, act_half ? kF16 : wdt, A, W, C, M, N, K, nsplit, variant));
 }
 
 extern "C" int rlhf_op_paged_decode_attention(int dtype, const void* q, const void* pool,

@@ -143,3 +143,21 @@ def test_varlen_attention(dtype, Hq, Hkv, hd):
     torch.cuda.synchronize()
     tol = 3e-3 if dtype == "half" else 2e-5      # half: output rounding of values of size ~1-3
     np.testing.assert_allclose(out.double().cpu().numpy().reshape(T, Hq, hd), want, rtol=0, atol=tol)
+
+
+@pytest.mark.parametrize("variant", [5, 6, 7, 8, 9])
+@pytest.mark.parametrize("half_act", [False, True])
+def test_gemm_compute_bound_tilings(variant, half_act):
+    """Every large-M tiling (XCD-aware tile order, ragged M/N/K edges, more tiles than one
+    super-tile in N) against float64."""
+    R = _R()
+    M, N, K = 700, 4200, 328
+    r = np.random.default_rng(variant)
+    a, w = r.normal(size=(M, K)), r.normal(size=(N, K)) * 0.02
+    A = torch.from_numpy(a.astype(np.float32)).half().cuda() if half_act else _bf16_round(a).cuda()
+    W = _bf16_round(w).cuda()
+    want = A.double().cpu().numpy() @ W.double().cpu().numpy().T
+    out = torch.full((1, M, N), float("nan"), device="cuda")
+    R.rlhf_op_gemm(A, W, out, 1, variant)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out[0].double().cpu().numpy(), want, rtol=0, atol=2e-5)
