@@ -72,6 +72,13 @@ typedef struct rlhf_engine_cfg {
     int32_t eos_id;                /* termination token                                       */
     int32_t stop_on_eos;           /* 1: a sample also ends when it emits eos_id (costs one
                                       device->host copy per step); 0: length-driven only     */
+    int32_t decode_cus;            /* > 0: the decode stream the library creates may use only
+                                      this many compute units (CU-mask bits from the low end) */
+    int32_t score_cus;             /* > 0: likewise for the score stream, bits from the high
+                                      end; decode_cus + score_cus <= total keeps the two sets
+                                      disjoint, so that bandwidth-bound decoding and
+                                      matrix-bound scoring do not queue behind one another.
+                                      0 = the whole chip.  Ignored for caller-given streams   */
     void* decode_stream;           /* hipStream_t to use, or NULL: the library creates one    */
     void* score_stream;            /* hipStream_t to use, or NULL                             */
 } rlhf_engine_cfg;

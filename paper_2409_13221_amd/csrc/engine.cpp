@@ -427,10 +427,27 @@ static int create_impl(rlhf_ctx* c) {
                        (long long)e.kv_pool_bytes, (long long)pages, page_bytes);
     c->pool_pages = (int)pages;
 
+    int n_cus = 0;
+    {
+        int dev = 0;
+        HIPCK(c, hipGetDevice(&dev));
+        HIPCK(c, hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
+    }
+    if (e.decode_cus < 0 || e.score_cus < 0 || e.decode_cus > n_cus || e.score_cus > n_cus)
+        return c->fail(RLHF_EINVAL, "decode_cus / score_cus must be in [0, %d]", n_cus);
+    auto make_stream = [&](hipStream_t* st, int cus, bool from_top) -> hipError_t {
+        if (cus <= 0 || cus >= n_cus) return hipStreamCreateWithFlags(st, hipStreamNonBlocking);
+        std::vector<uint32_t> mask((n_cus + 31) / 32, 0u);
+        for (int k = 0; k < cus; ++k) {
+            const int bit = from_top ? n_cus - 1 - k : k;
+            mask[bit >> 5] |= 1u << (bit & 31);
+        }
+        return hipExtStreamCreateWithCUMask(st, (uint32_t)mask.size(), mask.data());
+    };
     if (e.decode_stream) c->sd = (hipStream_t)e.decode_stream;
-    else { HIPCK(c, hipStreamCreateWithFlags(&c->sd, hipStreamNonBlocking)); c->own_sd = true; }
+    else { HIPCK(c, make_stream(&c->sd, e.decode_cus, false)); c->own_sd = true; }
     if (e.score_stream) c->ss = (hipStream_t)e.score_stream;
-    else { HIPCK(c, hipStreamCreateWithFlags(&c->ss, hipStreamNonBlocking)); c->own_ss = true; }
+    else { HIPCK(c, make_stream(&c->ss, e.score_cus, true)); c->own_ss = true; }
     HIPCK(c, hipEventCreateWithFlags(&c->ev_dep, hipEventDisableTiming));
     HIPCK(c, hipEventCreate(&c->ev_d0));
     HIPCK(c, hipEventCreate(&c->ev_d1));

@@ -12,6 +12,8 @@
 // keeps the result deterministic (no float atomics).
 //
 // fp32: a plain LDS-tiled kernel for the float configuration (small model; not tuned).
+#include <cstdlib>
+
 #include "common.cuh"
 #include "kernels.h"
 
@@ -259,7 +261,7 @@ constexpr TileCfg kCfgs[] = {
     {0, 0, 0, 0, false},
     {1, 16, 128, 64, false}, {2, 32, 128, 64, false}, {3, 64, 128, 64, false}, {4, 128, 128, 64, false},
     {5, 128, 128, 64, true}, {6, 256, 128, 32, true}, {7, 256, 128, 64, true}, {8, 256, 256, 32, true},
-    {9, 128, 256, 32, true},
+    {9, 128, 256, 32, true}, {10, 256, 256, 32, true}, {11, 256, 256, 64, true}, {12, 128, 128, 32, true},
 };
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
@@ -268,7 +270,9 @@ int pick_variant(int M) {
     if (M <= 32) return 2;
     if (M <= 64) return 3;
     if (M <= 256) return 4;
-    return M >= 1024 ? 6 : 5;
+    static const int forced = [] { const char* e = getenv("RLHF_GEMM_BIG"); return e ? atoi(e) : 0; }();
+    if (forced >= 5 && forced < kNumCfgs) return forced;
+    return M >= 512 ? 11 : 5;
 }
 constexpr int kTargetBlocks = 1024;  // about four workgroups per compute unit
 }  // namespace
@@ -317,6 +321,9 @@ static hipError_t launch_bf16(hipStream_t st, int variant, const bf16_t* a, cons
         case 7: RLHF_GEMM(256, 128, 64, 2, 2, true); break;
         case 8: RLHF_GEMM(256, 256, 32, 2, 2, true); break;
         case 9: RLHF_GEMM(128, 256, 32, 2, 2, true); break;
+        case 10: RLHF_GEMM(256, 256, 32, 4, 2, true); break;
+        case 11: RLHF_GEMM(256, 256, 64, 4, 2, true); break;
+        case 12: RLHF_GEMM(128, 128, 32, 2, 2, true); break;
         default: return hipErrorInvalidValue;
     }
 #undef RLHF_GEMM

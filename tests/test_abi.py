@@ -32,7 +32,7 @@ def test_binding_structs_match_header_sizes():
     would corrupt arguments silently)."""
     import paper_2409_13221_amd.binding as B
     assert ctypes.sizeof(B.rlhf_model_cfg) == 8 * 4 + 2 * 4
-    assert ctypes.sizeof(B.rlhf_engine_cfg) == 4 + 4 + 8 + 6 * 4 + 2 * 8      # padding after page_tokens
+    assert ctypes.sizeof(B.rlhf_engine_cfg) == 4 + 4 + 8 + 8 * 4 + 2 * 8      # padding after page_tokens
     assert ctypes.sizeof(B.rlhf_weights) == 9 * 8
     assert ctypes.sizeof(B.rlhf_step_info) == 5 * 4
     assert ctypes.sizeof(B.rlhf_stage_opts) == 4 * 4 + 5 * 8 + 8
@@ -47,7 +47,7 @@ def test_create_rejects_bad_arguments_without_a_gpu():
     import paper_2409_13221_amd as R
     from workload import CONFIGS
     mc = R.model_cfg_of(CONFIGS["tiny"].model)
-    ec = R.rlhf_engine_cfg(16, 1 << 20, 4, 64, 4, 32, 2, 0, None, None)    # max_batch_tokens < max_ctx
+    ec = R.rlhf_engine_cfg(16, 1 << 20, 4, 64, 4, 32, 2, 0, 0, 0, None, None)    # max_batch_tokens < max_ctx
     try:
         R.rlhf_create(mc, ec)
         raise AssertionError("expected RLHF_EINVAL")

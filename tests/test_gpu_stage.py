@@ -95,7 +95,7 @@ def test_errors_are_reported_not_fatal(tiny_ref):
     cfg, ref = tiny_ref
     import paper_2409_13221_amd as R
     mc = R.model_cfg_of(cfg.model)
-    bad = R.rlhf_engine_cfg(8, 1 << 20, 4, 64, 4, 64, 2, 0, None, None)
+    bad = R.rlhf_engine_cfg(8, 1 << 20, 4, 64, 4, 64, 2, 0, 0, 0, None, None)
     with pytest.raises(R.RlhfError) as e:
         R.rlhf_create(mc, bad)
     assert e.value.code == R.RLHF_EINVAL and "page_tokens" in str(e.value)
