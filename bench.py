@@ -136,6 +136,59 @@ def roofline_of(prof, dtype, traffic):
             "avg_launch_us": round(v["sampled_ms"] / v["sampled"] * 1e3, 2), "launches": v["launches"]}, est
 
 
+def micro(args):
+    """Kernel-level cases at the 7B layer shapes through the ops ABI, for rocprofv3 counter runs:
+    a 1 GiB device copy (calibration of FETCH_SIZE / WRITE_SIZE), the four projections of a
+    scoring pass (M = 8192, half activations), the same four in the decode regime (M = 8), and
+    paged decode attention (32 samples x 1024 cached tokens, 32 heads x 128)."""
+    import torch
+
+    import paper_2409_13221_amd as R
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    out = []
+
+    def timed(name, fn, bytes_, flops, reps=args.micro_reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        out.append({"case": name, "us": round(us, 1), "GBps": round(bytes_ / us / 1e3, 1),
+                    "TFLOPs": round(flops / us / 1e6, 1), "alg_bytes": bytes_})
+        log(f"[micro] {name}: {us:.1f} us, {bytes_ / us / 1e3:.0f} GB/s, {flops / us / 1e6:.0f} TFLOP/s")
+
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    timed("copy_1GiB", lambda: dst.copy_(src), 2.0 * src.numel() * 4, 0)
+    del src, dst
+    shapes = [("qkv", 12288, 4096), ("o", 4096, 4096), ("gate_up", 22016, 4096), ("down", 4096, 11008)]
+    for M, half in ((8192, True), (8, False)):
+        for name, N, K in shapes:
+            A = torch.randn(M, K, device=dev).to(torch.float16 if half else torch.bfloat16)
+            W = (torch.randn(N, K, device=dev) * 0.02).to(torch.bfloat16)
+            ns = R.rlhf_op_gemm_nsplit(R.RLHF_BF16, M, N, K, 16)
+            C = torch.empty(ns, M, N, device=dev)
+            timed(f"gemm_{name}_M{M}", lambda: R.rlhf_op_gemm(A, W, C, ns),
+                  (N * K + M * K) * 2.0 + M * N * 4.0, 2.0 * M * N * K)
+    rows, ctx, Hq, hd, Ly = 32, 1024, 32, 128, 1
+    n_pages = rows * ctx // 16
+    pool = torch.randn(n_pages, Ly, 2, Hq, 16, hd, device=dev).to(torch.bfloat16)
+    q = torch.randn(rows, Hq * hd, device=dev).to(torch.bfloat16)
+    pt = torch.randperm(n_pages, device=dev).to(torch.int32).reshape(rows, ctx // 16).contiguous()
+    rs = torch.arange(rows, dtype=torch.int32, device=dev)
+    cl = torch.full((rows,), ctx, dtype=torch.int32, device=dev)
+    o = torch.empty_like(q)
+    timed("decode_attn_B32_ctx1024", lambda: R.rlhf_op_paged_decode_attention(q, pool, pt, rs, cl, o, None, None, 0, 1, Ly,
+                                                                            Hq, Hq, hd),
+          rows * ctx * 2.0 * Hq * hd * 2, 4.0 * rows * ctx * Hq * hd)
+    print(json.dumps({"micro": out}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -153,6 +206,8 @@ def main():
                     help="time every n-th launch of a kernel class (co-prime with the 4 GEMMs per layer)")
     ap.add_argument("--sequential", action="store_true",
                     help="time the serial generate-then-score plan instead (clean per-kernel figures)")
+    ap.add_argument("--micro", action="store_true", help="run the kernel-level cases instead of the stage")
+    ap.add_argument("--micro_reps", type=int, default=5)
     ap.add_argument("--no_cpu", action="store_true")
     ap.add_argument("--no_sequential", action="store_true")
     args = ap.parse_args()
@@ -166,6 +221,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.micro:
+        micro(args)
+        return
     torch.cuda.set_device(0)
     cfg = CONFIGS[args.config]
     R, ctx, weights, wl, max_new = build_stage(cfg, args)

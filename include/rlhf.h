@@ -47,11 +47,11 @@ enum rlhf_dtype { RLHF_FP32 = 0, RLHF_BF16 = 1 };
 
 /* Decoder shape shared by the four roles: pre-norm blocks, RMSNorm, rotary embedding on
  * pairs (k, k + head_dim/2), grouped KV heads, SwiGLU MLP, no biases.  dtype is the
- * storage type of the matrices and of the KV cache.  The residual stream, norms, softmax
- * and all accumulation are float32 in either case.  With BF16, activations fed to the
- * matrix units are bf16 in the decode step and IEEE half in prefill / scoring passes (the
- * bf16 weights convert to half exactly inside the kernel; the 8 times finer rounding of
- * half is what keeps values and rewards within 1e-2 of a float64 evaluation).
+ * storage type of the matrices.  The residual stream, norms, softmax and all accumulation
+ * are float32 in either case.  With BF16 matrices, the activations fed to the matrix units
+ * and the KV cache are IEEE half (2 bytes as well): the bf16 weights convert to half exactly
+ * inside the kernels, and the 8 times finer rounding of half is what keeps log-probs within
+ * 2e-2 and values / rewards within 1e-2 of a float64 evaluation at 32 layers.
  * Requirements: head_dim in {64, 128}; d_model, ffn multiples of 8; n_q_heads a multiple
  * of n_kv_heads. */
 typedef struct rlhf_model_cfg {

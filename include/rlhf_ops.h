@@ -5,7 +5,7 @@
  * All pointers are DEVICE pointers owned by the caller; `stream` is a hipStream_t (NULL =
  * the default stream).  Calls enqueue work and return without waiting.  Return values are
  * rlhf_status codes (0 = OK, RLHF_EINVAL for unsupported shapes, RLHF_EDEVICE for a failed
- * launch).  dtype is an rlhf_dtype: the storage type of weights and of the KV pool.
+ * launch).  dtype is an rlhf_dtype: the storage type of the weights.
  */
 #ifndef RLHF_OPS_H
 #define RLHF_OPS_H
@@ -32,6 +32,8 @@ int rlhf_op_gemm(int dtype, int act_half, const void* A, const void* W, float* C
 /* Decode attention of one step (Section 2.1, decoding phase): row r holds one query
  * [n_q_heads * head_dim] and attends to the ctx_len[r] cached tokens of the sample whose
  * page-table row is row_sample[r].  pool layout: [page][layer][K|V][kv_head][16][head_dim].
+ * Here dtype is the element type of q, pool and out: RLHF_FP32, RLHF_BF16, or 2 = IEEE half
+ * (what the stage uses for bf16 models).
  * part_acc / part_ml are float32 scratch of rows*n_q_heads*nsplit*head_dim and
  * rows*n_q_heads*nsplit*2 entries (unused when nsplit == 1). */
 int rlhf_op_paged_decode_attention(int dtype, const void* q, const void* pool, const int32_t* page_table,

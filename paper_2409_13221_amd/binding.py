@@ -321,9 +321,10 @@ def rlhf_op_gemm(A, W, C_out, nsplit: int, variant: int = 0) -> None:
 
 def rlhf_op_paged_decode_attention(q, pool, page_table, row_sample, ctx_len, out, part_acc, part_ml, layer: int,
                                    nsplit: int, n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int):
+    import torch
     rows = q.shape[0]
     _op_check(lib().rlhf_op_paged_decode_attention(
-        _dt(q), q.data_ptr(), pool.data_ptr(), page_table.data_ptr(), page_table.shape[1], row_sample.data_ptr(),
+        2 if q.dtype == torch.float16 else _dt(q), q.data_ptr(), pool.data_ptr(), page_table.data_ptr(), page_table.shape[1], row_sample.data_ptr(),
         ctx_len.data_ptr(), out.data_ptr(), part_acc.data_ptr() if part_acc is not None else None,
         part_ml.data_ptr() if part_ml is not None else None, rows, layer, nsplit, n_layers, n_q_heads,
         n_kv_heads, head_dim, _stream_ptr()), "rlhf_op_paged_decode_attention")

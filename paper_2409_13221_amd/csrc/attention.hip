@@ -21,11 +21,15 @@ constexpr int kPT = 16;  // tokens per page / tile
 
 template <typename T> struct Chunk;           // 8 elements of T held raw
 template <> struct Chunk<bf16_t> { uint4 r; };
+template <> struct Chunk<f16_t> { uint4 r; };
 template <> struct Chunk<float> { float4 a, b; };
 
 template <typename T> __device__ __forceinline__ Chunk<T> ld_chunk(const T* p);
 template <> __device__ __forceinline__ Chunk<bf16_t> ld_chunk<bf16_t>(const bf16_t* p) {
     Chunk<bf16_t> c; c.r = *reinterpret_cast<const uint4*>(p); return c;
+}
+template <> __device__ __forceinline__ Chunk<f16_t> ld_chunk<f16_t>(const f16_t* p) {
+    Chunk<f16_t> c; c.r = *reinterpret_cast<const uint4*>(p); return c;
 }
 template <> __device__ __forceinline__ Chunk<float> ld_chunk<float>(const float* p) {
     Chunk<float> c;
@@ -39,6 +43,11 @@ template <> __device__ __forceinline__ void unpack<bf16_t>(const Chunk<bf16_t>& 
     o[2] = __uint_as_float(c.r.y << 16); o[3] = __uint_as_float(c.r.y & 0xFFFF0000u);
     o[4] = __uint_as_float(c.r.z << 16); o[5] = __uint_as_float(c.r.z & 0xFFFF0000u);
     o[6] = __uint_as_float(c.r.w << 16); o[7] = __uint_as_float(c.r.w & 0xFFFF0000u);
+}
+template <> __device__ __forceinline__ void unpack<f16_t>(const Chunk<f16_t>& c, float (&o)[8]) {
+    const f16x8_t h = *reinterpret_cast<const f16x8_t*>(&c.r);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (float)h[e];
 }
 template <> __device__ __forceinline__ void unpack<float>(const Chunk<float>& c, float (&o)[8]) {
     o[0] = c.a.x; o[1] = c.a.y; o[2] = c.a.z; o[3] = c.a.w;
@@ -262,6 +271,10 @@ hipError_t launch_decode_attn(hipStream_t st, int dtype, const void* q, const vo
         if (hd == 128 && G == 1) RLHF_DEC(bf16_t, 128, 1);
         if (hd == 128 && G == 8) RLHF_DEC(bf16_t, 128, 8);
         if (hd == 64 && G == 1) RLHF_DEC(bf16_t, 64, 1);
+    } else if (dtype == kF16) {
+        if (hd == 128 && G == 1) RLHF_DEC(f16_t, 128, 1);
+        if (hd == 128 && G == 8) RLHF_DEC(f16_t, 128, 8);
+        if (hd == 64 && G == 1) RLHF_DEC(f16_t, 64, 1);
     } else {
         if (hd == 128 && G == 1) RLHF_DEC(float, 128, 1);
         if (hd == 64 && G == 1) RLHF_DEC(float, 64, 1);

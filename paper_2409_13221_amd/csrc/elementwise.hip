@@ -40,57 +40,69 @@ hipError_t launch_embed(hipStream_t st, int dtype, const int* tokens, const int*
 }
 
 // --------------------------------------------------------------------------------- RMSNorm
-// One block per output row.  d <= 256 * 8 * kRmsMaxIter.
-constexpr int kRmsMaxIter = 4;
+// One block per output row, one float4 of the row per thread and iteration (up to
+// kRmsMaxIter iterations).  The residual add of the split-K partial planes is fused in: all
+// planes of a float4 are requested before any is used, so a row costs one memory round trip.
+constexpr int kRmsMaxIter = 2;
+constexpr int kMaxPlanes = 16;
+
+template <typename T> __device__ __forceinline__ void store4(T* p, float4 v);
+template <> __device__ __forceinline__ void store4<float>(float* p, float4 v) {
+    *reinterpret_cast<float4*>(p) = v;
+}
+template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, float4 v) {
+    uint2 r;
+    r.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+    r.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+    *reinterpret_cast<uint2*>(p) = r;
+}
+template <> __device__ __forceinline__ void store4<f16_t>(f16_t* p, float4 v) {
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    h4 r = {(f16_t)v.x, (f16_t)v.y, (f16_t)v.z, (f16_t)v.w};
+    *reinterpret_cast<h4*>(p) = r;
+}
 
 template <typename T>
-__global__ __launch_bounds__(256) void k_rmsnorm(float* __restrict__ h, const float* __restrict__ part,
-                                                 int nsplit, size_t sstride,
-                                                 const int* __restrict__ row_idx,
-                                                 const float* __restrict__ g, T* __restrict__ xn,
-                                                 int d, float eps) {
+__global__ __launch_bounds__(1024) void k_rmsnorm(float* __restrict__ h, const float* __restrict__ part,
+                                                  int nsplit, size_t sstride,
+                                                  const int* __restrict__ row_idx,
+                                                  const float* __restrict__ g, T* __restrict__ xn,
+                                                  int d, float eps) {
     __shared__ float red[16];
     const int r = blockIdx.x;
     const int src = row_idx ? row_idx[r] : r;
     float* hrow = h + (size_t)src * d;
-    float v[kRmsMaxIter][8];
+    float4 v[kRmsMaxIter];
     float ss = 0.f;
 #pragma unroll
     for (int it = 0; it < kRmsMaxIter; ++it) {
-        const int i = (it * 256 + threadIdx.x) * 8;
+        const int i = (it * blockDim.x + threadIdx.x) * 4;
+        v[it] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (i < d) {
-            load8<float>(hrow + i, v[it]);
+            float4 p[kMaxPlanes];
             const float* pp = part + (size_t)src * d + i;
-            int s = 0;
-            for (; s + 2 <= nsplit; s += 2) {          // two partial planes in flight at a time
-                float p[8], p2[8];
-                load8<float>(pp + s * sstride, p);
-                load8<float>(pp + (s + 1) * sstride, p2);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[it][e] += p[e] + p2[e];
-            }
-            if (s < nsplit) {
-                float p[8];
-                load8<float>(pp + s * sstride, p);
+            for (int s = 0; s < kMaxPlanes; ++s)
+                p[s] = s < nsplit ? *reinterpret_cast<const float4*>(pp + s * sstride)
+                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 a = *reinterpret_cast<const float4*>(hrow + i);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[it][e] += p[e];
-            }
-            if (nsplit > 0 && !row_idx) store8<float>(hrow + i, v[it]);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) ss += v[it][e] * v[it][e];
+            for (int s = 0; s < kMaxPlanes; ++s) { a.x += p[s].x; a.y += p[s].y; a.z += p[s].z; a.w += p[s].w; }
+            if (nsplit > 0 && !row_idx) *reinterpret_cast<float4*>(hrow + i) = a;
+            v[it] = a;
+            ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
         }
     }
     const float tot = block_sum(ss, red);
     const float inv = rsqrtf(tot / (float)d + eps);
 #pragma unroll
     for (int it = 0; it < kRmsMaxIter; ++it) {
-        const int i = (it * 256 + threadIdx.x) * 8;
+        const int i = (it * blockDim.x + threadIdx.x) * 4;
         if (i < d) {
-            float gg[8], o[8];
-            load8<float>(g + i, gg);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = v[it][e] * inv * gg[e];
-            store8<T>(xn + (size_t)r * d + i, o);
+            const float4 gg = *reinterpret_cast<const float4*>(g + i);
+            store4<T>(xn + (size_t)r * d + i,
+                      make_float4(v[it].x * inv * gg.x, v[it].y * inv * gg.y, v[it].z * inv * gg.z,
+                                  v[it].w * inv * gg.w));
         }
     }
 }
@@ -99,13 +111,16 @@ hipError_t launch_rmsnorm(hipStream_t st, int adt, float* h, const float* part, 
                           size_t sstride, const int* row_idx, const float* g, void* xn, int rows,
                           int d, float eps) {
     if (rows <= 0) return hipSuccess;
-    if (d > 256 * 8 * kRmsMaxIter || d % 8) return hipErrorInvalidValue;
+    if (d > 1024 * 4 * kRmsMaxIter || d % 8 || nsplit > kMaxPlanes) return hipErrorInvalidValue;
+    const int quads = d / 4;
+    const int iters = (quads + 1023) / 1024;
+    const int threads = ((quads + iters - 1) / iters + 63) / 64 * 64;
     if (adt == kBF16)
-        k_rmsnorm<bf16_t><<<rows, 256, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (bf16_t*)xn, d, eps);
+        k_rmsnorm<bf16_t><<<rows, threads, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (bf16_t*)xn, d, eps);
     else if (adt == kF16)
-        k_rmsnorm<f16_t><<<rows, 256, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (f16_t*)xn, d, eps);
+        k_rmsnorm<f16_t><<<rows, threads, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (f16_t*)xn, d, eps);
     else
-        k_rmsnorm<float><<<rows, 256, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (float*)xn, d, eps);
+        k_rmsnorm<float><<<rows, threads, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (float*)xn, d, eps);
     return hipGetLastError();
 }
 
@@ -192,10 +207,10 @@ hipError_t launch_rope_kv(hipStream_t st, int qdt, int pdt, const float* qkv, in
         k_rope_kv<bf16_t, bf16_t><<<grid, 64, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
                                                        (bf16_t*)q_out, (bf16_t*)k_out, (bf16_t*)v_out,
                                                        (bf16_t*)pool, layer, dm);
-    else if (qdt == kF16 && pdt == kBF16)
-        k_rope_kv<f16_t, bf16_t><<<grid, 64, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
-                                                      (f16_t*)q_out, (f16_t*)k_out, (f16_t*)v_out,
-                                                      (bf16_t*)pool, layer, dm);
+    else if (qdt == kF16 && pdt == kF16)
+        k_rope_kv<f16_t, f16_t><<<grid, 64, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
+                                                     (f16_t*)q_out, (f16_t*)k_out, (f16_t*)v_out,
+                                                     (f16_t*)pool, layer, dm);
     else if (qdt == kF32 && pdt == kF32)
         k_rope_kv<float, float><<<grid, 64, 0, st>>>(qkv, nsplit, sstride, pos, kv_dst, rope_table,
                                                      (float*)q_out, (float*)k_out, (float*)v_out,
@@ -288,37 +303,76 @@ __device__ __forceinline__ void row_softmax_stats(const float* row, int nsplit, 
     out_arg = arg;
 }
 
-__global__ __launch_bounds__(256) void k_pick(const float* __restrict__ logits, int nsplit,
-                                              size_t sstride, int vocab,
-                                              const int* __restrict__ forced,
-                                              int* __restrict__ tokens,
-                                              const int* __restrict__ tok_dst,
-                                              float* __restrict__ lp, const int* __restrict__ lp_dst,
-                                              int* __restrict__ picked) {
-    const int r = blockIdx.x;
-    const float* row = logits + (size_t)r * vocab;
-    float mx, se;
-    int arg;
-    row_softmax_stats(row, nsplit, sstride, vocab, mx, arg, se);
+// Greedy pick in two stages so that a handful of rows still spreads over the chip: stage 1,
+// one block per (row, column chunk), leaves (max, argmax, sum exp(z - max)) of its chunk;
+// stage 2, one wave per row, merges the chunks in ascending order (so the lowest id wins a
+// tie), applies an imposed token and writes token and log-prob.
+constexpr int kPickChunks = 32;
+
+__global__ __launch_bounds__(256) void k_pick_stage1(const float* __restrict__ logits, int nsplit,
+                                                     size_t sstride, int vocab,
+                                                     float* __restrict__ scratch) {
+    const int r = blockIdx.x, c = blockIdx.y;
+    const int per = (vocab + kPickChunks - 1) / kPickChunks;
+    const int lo = c * per, n = max(0, min(vocab, lo + per) - lo);
+    float mx = -INFINITY, se = 0.f;
+    int arg = 0x7FFFFFFF;
+    if (n > 0) row_softmax_stats(logits + (size_t)r * vocab + lo, nsplit, sstride, n, mx, arg, se);
     if (threadIdx.x == 0) {
-        int y = arg;
+        float* o = scratch + ((size_t)r * kPickChunks + c) * 3;
+        o[0] = mx;
+        o[1] = __int_as_float(n > 0 ? arg + lo : 0x7FFFFFFF);
+        o[2] = se;
+    }
+}
+
+__global__ __launch_bounds__(64) void k_pick_stage2(const float* __restrict__ logits, int nsplit,
+                                                    size_t sstride, int vocab,
+                                                    const float* __restrict__ scratch,
+                                                    const int* __restrict__ forced,
+                                                    int* __restrict__ tokens,
+                                                    const int* __restrict__ tok_dst,
+                                                    float* __restrict__ lp,
+                                                    const int* __restrict__ lp_dst,
+                                                    int* __restrict__ picked) {
+    const int r = blockIdx.x, lane = threadIdx.x;
+    const float* sc = scratch + (size_t)r * kPickChunks * 3;
+    float mx = -INFINITY, se = 0.f;
+    int arg = 0x7FFFFFFF;
+    if (lane < kPickChunks) { mx = sc[lane * 3]; arg = __float_as_int(sc[lane * 3 + 1]); se = sc[lane * 3 + 2]; }
+    float best = mx;
+    int barg = arg;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(best, o, kWave);
+        const int oi = __shfl_xor(barg, o, kWave);
+        if (ov > best || (ov == best && oi < barg)) { best = ov; barg = oi; }
+    }
+    const float tot = wave_sum(mx > -INFINITY ? se * expf(mx - best) : 0.f);
+    if (lane == 0) {
+        int y = barg;
         const int f = forced ? forced[r] : -1;
         if (f >= 0 && f < vocab) y = f;
-        const float z = logit_at(row, nsplit, sstride, y);
+        const float z = logit_at(logits + (size_t)r * vocab, nsplit, sstride, y);
         tokens[tok_dst[r]] = y;
-        lp[lp_dst[r]] = z - mx - logf(se);
+        lp[lp_dst[r]] = z - best - logf(tot);
         if (picked) picked[r] = y;
     }
 }
 
 hipError_t launch_pick(hipStream_t st, const float* logits, int nsplit, size_t sstride, int rows,
                        int vocab, const int* forced, int* tokens, const int* tok_dst, float* lp,
-                       const int* lp_dst, int* picked) {
+                       const int* lp_dst, int* picked, float* scratch) {
     if (rows <= 0) return hipSuccess;
-    k_pick<<<rows, 256, 0, st>>>(logits, nsplit, sstride, vocab, forced, tokens, tok_dst, lp, lp_dst,
-                                 picked);
+    k_pick_stage1<<<dim3(rows, kPickChunks), 256, 0, st>>>(logits, nsplit, sstride, vocab, scratch);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    k_pick_stage2<<<rows, 64, 0, st>>>(logits, nsplit, sstride, vocab, scratch, forced, tokens, tok_dst, lp,
+                                       lp_dst, picked);
     return hipGetLastError();
 }
+
+size_t pick_scratch_floats(int rows) { return (size_t)rows * kPickChunks * 3; }
 
 __global__ __launch_bounds__(256) void k_gather_lp(const float* __restrict__ logits, int nsplit,
                                                    size_t sstride, int vocab,

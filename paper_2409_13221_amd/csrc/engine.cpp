@@ -93,6 +93,7 @@ struct Workspace {
     void* xsel = nullptr;     // [rows, d] final-norm rows selected for the head
     float* logits = nullptr;  // [logit_rows, vocab] (batch passes; decode uses `part`)
     int logit_rows = 0;
+    float* pick_scratch = nullptr;  // per-chunk partial results of the greedy pick
     float* attn_acc = nullptr;  // decode split-KV partials
     float* attn_ml = nullptr;
     size_t attn_slots = 0;
@@ -222,9 +223,8 @@ hipError_t profiled(rlhf_ctx* c, hipStream_t st, int cls, double bytes, double f
     return hipEventRecord(r.b, st);
 }
 
-// Activation type of a pass: the decode step keeps the model's storage type; prefill / scoring
-// passes of a bf16 model feed the matrix units half-precision activations.
-int act_type(const rlhf_ctx* c, bool batch) { return (batch && c->dtype == kBF16) ? kF16 : c->dtype; }
+// Activation and KV-pool type: float for a float model, IEEE half for a bf16 model.
+int act_type(const rlhf_ctx* c, bool /*batch*/) { return c->dtype == kBF16 ? kF16 : kF32; }
 
 hipError_t gemm_profiled(rlhf_ctx* c, hipStream_t st, int cls, int adt, const void* A, const void* W, float* C,
                          int M, int N, int K, int nsplit) {
@@ -265,6 +265,7 @@ int alloc_workspace(rlhf_ctx* c, Workspace& ws, int rows, bool decode) {
     HIPCK(c, dev_alloc(&ws, (char**)&ws.attn, rows * qd * es));
     HIPCK(c, dev_alloc(&ws, (char**)&ws.act, rows * f * es));
     HIPCK(c, dev_alloc(&ws, (char**)&ws.xsel, rows * d * es));
+    HIPCK(c, dev_alloc(&ws, &ws.pick_scratch, pick_scratch_floats(rows) * 4));
     if (decode) {
         HIPCK(c, dev_alloc(&ws, &ws.attn_acc, ws.attn_slots * m.head_dim * 4));
         HIPCK(c, dev_alloc(&ws, &ws.attn_ml, ws.attn_slots * 2 * 4));
@@ -328,13 +329,13 @@ int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
                                 ws.xn, rows, d, m.rms_eps));
         int ns = nsplit_for(c, ws, rows, qkv_w, d);
         HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.xn, layer_ptr(w.wqkv, l, qkv_w, d, es), ws.part, rows, qkv_w, d, ns));
-        HIPCK(c, launch_rope_kv(st, qdt, dt, ws.part, ns, (size_t)rows * qkv_w, pm.pos, pm.kv_dst, c->d_rope,
+        HIPCK(c, launch_rope_kv(st, qdt, adt, ws.part, ns, (size_t)rows * qkv_w, pm.pos, pm.kv_dst, c->d_rope,
                                 ws.q, mode == kModeBatch ? ws.k : nullptr,
                                 mode == kModeBatch ? ws.v : nullptr, pm.kv_dst ? c->pool : nullptr, l,
                                 rows, c->dm));
         if (mode == kModeDecode) {
             HIPCK(c, profiled(c, st, kAttnDecode, pm.attn_bytes, pm.attn_flops, [&] {
-                return launch_decode_attn(st, dt, ws.q, c->pool, c->d_page_table, c->max_pages, pm.row_sample,
+                return launch_decode_attn(st, adt, ws.q, c->pool, c->d_page_table, c->max_pages, pm.row_sample,
                                           pm.ctx_len, ws.attn, ws.attn_acc, ws.attn_ml, rows, l, attn_nsplit,
                                           c->dm);
             }));
@@ -644,7 +645,7 @@ int lm_head_chunks(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
         HIPCK(c, gemm_profiled(c, st, kGemmBatch, act_type(c, true), x, w.head, ws.logits, nr, V, d, 1));
         if (pick)
             HIPCK(c, launch_pick(st, ws.logits, 1, 0, nr, V, hp.forced + r0, c->d_tokens, hp.tok_dst + r0,
-                                 c->d_lp_actor, hp.lp_dst + r0, nullptr));
+                                 c->d_lp_actor, hp.lp_dst + r0, nullptr, ws.pick_scratch));
         else
             HIPCK(c, launch_gather_lp(st, ws.logits, 1, 0, nr, V, c->d_tokens, hp.target_idx + r0, hp.out,
                                       hp.out_dst + r0));
@@ -835,12 +836,12 @@ int decode_rows(rlhf_ctx* c, const std::vector<int>& rows_ids) {
     int rc = forward_layers(c, c->sd, ws, w, R, pm, kModeDecode, asplit, &pns, &pstride);
     if (rc) return rc;
     const int d = c->mc.d_model, V = c->mc.vocab;
-    HIPCK(c, launch_rmsnorm(c->sd, c->dtype, ws.h, ws.part, pns, pstride, nullptr, w.g_final, ws.xsel, R, d,
+    HIPCK(c, launch_rmsnorm(c->sd, act_type(c, false), ws.h, ws.part, pns, pstride, nullptr, w.g_final, ws.xsel, R, d,
                             c->mc.rms_eps));
     const int ns = nsplit_for(c, ws, R, V, d);
-    HIPCK(c, gemm_profiled(c, c->sd, kGemmDecode, c->dtype, ws.xsel, w.head, ws.part, R, V, d, ns));
+    HIPCK(c, gemm_profiled(c, c->sd, kGemmDecode, act_type(c, false), ws.xsel, w.head, ws.part, R, V, d, ns));
     HIPCK(c, launch_pick(c->sd, ws.part, ns, (size_t)R * V, R, V, dmeta + 7 * R, c->d_tokens, dmeta + 5 * R,
-                         c->d_lp_actor, dmeta + 6 * R, c->d_picked));
+                         c->d_lp_actor, dmeta + 6 * R, c->d_picked, ws.pick_scratch));
     // algorithmic bytes of this step
     const rlhf_model_cfg& m = c->mc;
     const int64_t qd = (int64_t)m.n_q_heads * m.head_dim, kvd = (int64_t)m.n_kv_heads * m.head_dim;

@@ -9,10 +9,10 @@
 
 namespace rlhf {
 
-// Storage types.  Weights and the KV pool are kF32 or kBF16.  Activations fed to the matrix
-// units are kF32 (float model), kBF16 (decode step of a bf16 model) or kF16 (prefill / scoring
-// passes of a bf16 model: half-precision activations keep 11 significant bits, and the bf16
-// weights convert to half exactly on their way into LDS).
+// Storage types.  Weights are kF32 or kBF16.  With bf16 weights every activation fed to the
+// matrix units and the KV pool are kF16: IEEE half keeps 11 significant bits against bf16's 8,
+// and the bf16 weights convert to half exactly on their way into LDS.  (The kernels also accept
+// bf16 activations and a bf16 pool; the engine does not use them.)
 enum DType { kF32 = 0, kBF16 = 1, kF16 = 2 };
 
 struct Dims {
@@ -38,7 +38,7 @@ hipError_t launch_rmsnorm(hipStream_t st, int adt, float* h, const float* part, 
 // Rotary on Q and K heads of qkv rows.  q_out [rows, Hq*hd] and, if non-NULL, k_out/v_out
 // [rows, Hkv*hd] have type qdt; if pool != NULL and kv_dst[r] >= 0, K/V of row r also go (as
 // type pdt) to token slot kv_dst[r] (= page * page_tokens + offset) of `layer` in the paged pool.
-// (qdt, pdt) in {(kF32,kF32), (kBF16,kBF16), (kF16,kBF16)}.
+// (qdt, pdt) in {(kF32,kF32), (kBF16,kBF16), (kF16,kF16)}.
 hipError_t launch_rope_kv(hipStream_t st, int qdt, int pdt, const float* qkv, int nsplit, size_t sstride,
                           const int* pos, const int* kv_dst, const float* rope_table,
                           void* q_out, void* k_out, void* v_out, void* pool, int layer,
@@ -47,9 +47,11 @@ hipError_t launch_swiglu(hipStream_t st, int adt, const float* gu, int nsplit, s
                          void* act, int rows, int ffn);
 // Greedy choice per logit row (lowest id on ties), optional imposed token forced[r] >= 0;
 // writes the emitted token to tokens[tok_dst[r]] and picked[r], its log-prob to lp[lp_dst[r]].
+// scratch: pick_scratch_floats(rows) floats.
 hipError_t launch_pick(hipStream_t st, const float* logits, int nsplit, size_t sstride, int rows,
                        int vocab, const int* forced, int* tokens, const int* tok_dst, float* lp,
-                       const int* lp_dst, int* picked);
+                       const int* lp_dst, int* picked, float* scratch);
+size_t pick_scratch_floats(int rows);
 // lp[out_dst[r]] = log_softmax(logits[r])[tokens[target_idx[r]]]
 hipError_t launch_gather_lp(hipStream_t st, const float* logits, int nsplit, size_t sstride,
                             int rows, int vocab, const int* tokens, const int* target_idx,

@@ -38,7 +38,8 @@ extern "C" int rlhf_op_paged_decode_attention(int dtype, const void* q, const vo
         return RLHF_EINVAL;
     if (nsplit > 1 && (!part_acc || !part_ml)) return RLHF_EINVAL;
     Dims dm{n_layers, n_q_heads * head_dim, n_q_heads, n_kv_heads, head_dim, 0, 0, 16};
-    return status_of(launch_decode_attn((hipStream_t)stream, dtype == RLHF_BF16 ? kBF16 : kF32, q, pool,
+    const int dt = dtype == 2 ? kF16 : dtype == RLHF_BF16 ? kBF16 : kF32;
+    return status_of(launch_decode_attn((hipStream_t)stream, dt, q, pool,
                                         page_table, pt_stride, row_sample, ctx_len, out, part_acc, part_ml,
                                         rows, layer, nsplit, dm));
 }

@@ -60,7 +60,7 @@ def _paged_case(seed, rows, Hq, Hkv, hd, n_layers, layer, ctx_lens, dtype):
     pt_stride = max(n_pages_each) + 1
     page_table = np.full((rows + 2, pt_stride), 0, np.int32)
     row_sample = r.permutation(rows + 2)[:rows].astype(np.int32)
-    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    tdt = {"bf16": torch.bfloat16, "half": torch.float16, "fp32": torch.float32}[dtype]
     pool = (torch.randn(pool_pages, n_layers, 2, Hkv, 16, hd) * 1.0).to(tdt)
     q = (torch.randn(rows, Hq, hd) * 2.0).to(tdt)
     nxt = 0
@@ -77,6 +77,7 @@ def _paged_case(seed, rows, Hq, Hkv, hd, n_layers, layer, ctx_lens, dtype):
 
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,hd", [("bf16", 4, 4, 128), ("bf16", 16, 2, 128), ("bf16", 3, 3, 64),
+                                             ("half", 4, 4, 128), ("half", 16, 2, 128), ("half", 3, 3, 64),
                                              ("fp32", 4, 4, 64), ("fp32", 2, 2, 128)])
 @pytest.mark.parametrize("nsplit", [1, 3, 8])
 def test_paged_decode_attention(dtype, Hq, Hkv, hd, nsplit):
@@ -93,7 +94,7 @@ def test_paged_decode_attention(dtype, Hq, Hkv, hd, nsplit):
                                      nsplit, n_layers, Hq, Hkv, hd)
     torch.cuda.synchronize()
     got = out.double().cpu().numpy().reshape(rows, Hq, hd)
-    tol = 2e-2 if dtype == "bf16" else 2e-5       # bf16: output rounding of values of size ~1-3
+    tol = {"bf16": 2e-2, "half": 3e-3, "fp32": 2e-5}[dtype]   # 16-bit: output rounding of values of size ~1-3
     np.testing.assert_allclose(got, want, rtol=0, atol=tol)
 
 
