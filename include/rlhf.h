@@ -17,7 +17,8 @@
  *     copied before it returns.  Result and snapshot buffers are caller-allocated host
  *     arrays filled before the call returns.
  *   - The library owns the paged KV pool, page tables, workspaces and (unless given) its
- *     two HIP streams.  It allocates device memory only in rlhf_create()/rlhf_submit().
+ *     two HIP streams.  It allocates device memory only in rlhf_create() (and temporaries
+ *     inside rlhf_compute_gae()).
  *   - One context may be used from one host thread at a time.
  */
 #ifndef RLHF_H
@@ -227,6 +228,18 @@ int rlhf_run_stage(rlhf_ctx* ctx, const rlhf_stage_opts* opts, rlhf_stage_stats*
 
 /* Drain both streams, then copy the stage outputs to the caller's host arrays. */
 int rlhf_get_results(rlhf_ctx* ctx, rlhf_results* out);
+
+/* Generalized Advantage Estimation over the finished stage's results, computed the way
+ * Section 6 ("System optimizations", inference stage) describes: the recursion
+ * A_t = delta_t + gamma*lam*A_{t+1} is unrolled along the output length, so that all samples'
+ * advantages are ONE matrix multiply A = D U^T, with D the zero-padded [n, L] matrix of
+ * delta_t = r_t + gamma*V_{t+1} - V_t (V after the last token = 0) and U[t][s] = (gamma*lam)^(s-t)
+ * for s >= t.  The per-token reward is r_t = -kl_coef*(lp_actor_t - lp_ref_t), plus the Reward
+ * model's score at the last token.  Needs REF, CRITIC and REWARD to have been scored for every
+ * sample.  advantages / returns (= A + V) are host arrays packed like rlhf_results (either may
+ * be NULL).  Float32 throughout; allocates and frees its temporaries; waits for both streams. */
+int rlhf_compute_gae(rlhf_ctx* ctx, float gamma, float lam, float kl_coef, float* advantages,
+                     float* returns, int64_t packed_capacity);
 
 /* Copy the integer bookkeeping state (host-side, no device work). */
 int rlhf_debug_snapshot(rlhf_ctx* ctx, rlhf_snapshot* out);

@@ -209,10 +209,12 @@ def _pick(z: np.ndarray, override: int):
     return y, lp, float(top2[1] - top2[0]), y_star
 
 
-def _override(j: int, out_len: int, eos_id: int, forced: Optional[Sequence[int]]) -> int:
+def _override(j: int, out_len: int, eos_id: int, forced: Optional[Sequence[int]],
+              impose_eos: bool = True) -> int:
     """Token imposed at output index j (1-based), or -1.  The termination token is imposed
-    at j = out_len; `forced` (teacher forcing, -1 = free) may impose earlier ones."""
-    if j == out_len:
+    at j = out_len (unless impose_eos is off: then out_len is only a cap); `forced` (teacher
+    forcing, -1 = free) may impose earlier ones."""
+    if j == out_len and impose_eos:
         return eos_id
     if forced is not None and forced[j - 1] >= 0:
         return int(forced[j - 1])
@@ -220,23 +222,29 @@ def _override(j: int, out_len: int, eos_id: int, forced: Optional[Sequence[int]]
 
 
 def greedy_generate(actor: Model, prompt: Sequence[int], out_len: int, eos_id: int,
-                    forced: Optional[Sequence[int]] = None) -> Generated:
+                    forced: Optional[Sequence[int]] = None, stop_at_eos: bool = False) -> Generated:
     """Generation of one sample by full recompute: every step runs the whole sequence
-    through the Actor and reads the last position (Section 2.1, Generation stage)."""
+    through the Actor and reads the last position (Section 2.1, Generation stage).
+    Default: the sample has exactly out_len tokens, the last one imposed to be eos_id (the
+    synthetic workloads' termination rule).  stop_at_eos: generation runs "until reaching a
+    termination token" -- it ends when eos_id is emitted, out_len is only a cap and nothing is
+    imposed there."""
     x = list(int(t) for t in prompt)
     toks, lps, margins, greedy = [], [], [], []
     for j in range(1, out_len + 1):
         _, Z = actor.forward_full(x)
-        y, lp, mg, ys = _pick(Z[-1], _override(j, out_len, eos_id, forced))
+        y, lp, mg, ys = _pick(Z[-1], _override(j, out_len, eos_id, forced, not stop_at_eos))
         toks.append(y); lps.append(lp); margins.append(mg); greedy.append(ys)
         x.append(y)
+        if stop_at_eos and y == eos_id:
+            break
     return Generated(np.array(toks, np.int32), np.array(lps, actor.dtype),
                      np.array(margins, actor.dtype), np.array(greedy, np.int32))
 
 
 def greedy_generate_cached(actor: Model, prompts: List[Sequence[int]], out_lens: Sequence[int],
-                           eos_id: int, forced: Optional[List[Optional[Sequence[int]]]] = None
-                           ) -> List[Generated]:
+                           eos_id: int, forced: Optional[List[Optional[Sequence[int]]]] = None,
+                           stop_at_eos: bool = False) -> List[Generated]:
     """The same results by prefill + KV-cached decoding steps, all samples advanced in
     lock step (sample i drops out after out_lens[i] tokens).  Equal to `greedy_generate`
     per sample; this is the variant that is affordable beyond toy sizes."""
@@ -252,11 +260,11 @@ def greedy_generate_cached(actor: Model, prompts: List[Sequence[int]], out_lens:
         ends = np.cumsum([len(feed[i]) for i in live]) - 1
         nxt = []
         for row, i in zip(ends, live):
-            y, lp, mg, ys = _pick(Z[row], _override(j, out_lens[i], eos_id, forced[i]))
+            y, lp, mg, ys = _pick(Z[row], _override(j, out_lens[i], eos_id, forced[i], not stop_at_eos))
             for lst, val in zip(rec[i], (y, lp, mg, ys)):
                 lst.append(val)
             feed[i] = [y]
-            if j < out_lens[i]:
+            if j < out_lens[i] and not (stop_at_eos and y == eos_id):
                 nxt.append(i)
         live = nxt
         j += 1

@@ -114,6 +114,7 @@ def lib() -> C.CDLL:
         L.rlhf_get_results.argtypes = [vp, C.POINTER(rlhf_results)]
         L.rlhf_debug_snapshot.argtypes = [vp, C.POINTER(rlhf_snapshot)]
         L.rlhf_sync.argtypes = [vp]
+        L.rlhf_compute_gae.argtypes = [vp, C.c_float, C.c_float, C.c_float, vp, vp, i64]
         L.rlhf_profile_begin.argtypes = [vp, i32]
         L.rlhf_profile_end.argtypes = [vp, C.POINTER(rlhf_kernel_profile)]
         L.rlhf_op_gemm_nsplit.argtypes = [C.c_int] * 5
@@ -123,7 +124,7 @@ def lib() -> C.CDLL:
         L.rlhf_op_flash_attention.argtypes = [vp] * 7 + [C.c_int] * 5 + [vp]
         for name in ("rlhf_create", "rlhf_load_weights", "rlhf_submit", "rlhf_generate_step", "rlhf_retire",
                      "rlhf_score", "rlhf_run_stage", "rlhf_get_results", "rlhf_debug_snapshot", "rlhf_sync",
-                     "rlhf_profile_begin", "rlhf_profile_end",
+                     "rlhf_profile_begin", "rlhf_profile_end", "rlhf_compute_gae",
                      "rlhf_op_gemm_nsplit", "rlhf_op_gemm", "rlhf_op_paged_decode_attention",
                      "rlhf_op_varlen_attention", "rlhf_op_flash_attention"):
             getattr(L, name).restype = C.c_int
@@ -272,6 +273,15 @@ def rlhf_debug_snapshot(ctx, cap_samples: int, cap_max_pages: int, cap_pool_page
 
 def rlhf_sync(ctx) -> None:
     _check(ctx, lib().rlhf_sync(ctx))
+
+
+def rlhf_compute_gae(ctx, gamma: float, lam: float, kl_coef: float, packed_capacity: int):
+    """Returns (advantages, returns), float32 arrays of packed_capacity entries (the caller
+    trims them with resp_offsets)."""
+    adv = np.full(packed_capacity, np.nan, np.float32)
+    ret = np.full(packed_capacity, np.nan, np.float32)
+    _check(ctx, lib().rlhf_compute_gae(ctx, gamma, lam, kl_coef, _p(adv), _p(ret), packed_capacity))
+    return adv, ret
 
 
 def rlhf_profile_begin(ctx, sample_every: int = 1) -> None:

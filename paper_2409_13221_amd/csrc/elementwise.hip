@@ -450,4 +450,59 @@ hipError_t launch_scatter_int(hipStream_t st, int* dst, const int* idx, const in
     return hipGetLastError();
 }
 
+// ------------------------------------------------- Generalized Advantage Estimation
+// The recursion A_t = delta_t + gamma*lam*A_{t+1} unrolled along the output length: with
+// delta as a zero-padded matrix D [n, Lp] and U[t][s] = (gamma*lam)^(s-t) for s >= t (else 0),
+// A = D U^T is one matrix multiply.  These kernels build D and U and finish the returns.
+//   delta_t = r_t + gamma*V_{t+1} - V_t,  V_{L+1} = 0,
+//   r_t = -kl_coef*(lp_actor_t - lp_ref_t) + [t == L] * reward
+// Inputs are the stage's result buffers, row stride `stride`, entry j-1 of row i for token j.
+__global__ void k_gae_delta(const float* __restrict__ lp_actor, const float* __restrict__ lp_ref,
+                            const float* __restrict__ values, const float* __restrict__ reward,
+                            const int* __restrict__ gen_len, int stride, float gamma, float kl_coef,
+                            float* __restrict__ D, int Lp) {
+    const int i = blockIdx.x, L = gen_len[i];
+    for (int t = threadIdx.x; t < Lp; t += blockDim.x) {
+        float d = 0.f;
+        if (t < L) {
+            const size_t o = (size_t)i * stride + t;
+            float r = -kl_coef * (lp_actor[o] - lp_ref[o]);
+            if (t == L - 1) r += reward[i];
+            const float vnext = t + 1 < L ? values[o + 1] : 0.f;
+            d = r + gamma * vnext - values[o];
+        }
+        D[(size_t)i * Lp + t] = d;
+    }
+}
+
+__global__ void k_gae_matrix(float* __restrict__ U, int Lp, double gl) {
+    const int s = blockIdx.x * blockDim.x + threadIdx.x, t = blockIdx.y;
+    if (s < Lp) U[(size_t)t * Lp + s] = s >= t ? (float)pow(gl, (double)(s - t)) : 0.f;
+}
+
+__global__ void k_gae_returns(const float* __restrict__ A, const float* __restrict__ values,
+                              const int* __restrict__ gen_len, int stride, float* __restrict__ R, int Lp) {
+    const int i = blockIdx.x, L = gen_len[i];
+    for (int t = threadIdx.x; t < Lp; t += blockDim.x)
+        R[(size_t)i * Lp + t] = t < L ? A[(size_t)i * Lp + t] + values[(size_t)i * stride + t] : 0.f;
+}
+
+hipError_t launch_gae_delta(hipStream_t st, const float* lp_actor, const float* lp_ref, const float* values,
+                            const float* reward, const int* gen_len, int stride, float gamma, float kl_coef,
+                            float* D, int n, int Lp) {
+    if (n <= 0) return hipSuccess;
+    k_gae_delta<<<n, 256, 0, st>>>(lp_actor, lp_ref, values, reward, gen_len, stride, gamma, kl_coef, D, Lp);
+    return hipGetLastError();
+}
+hipError_t launch_gae_matrix(hipStream_t st, float* U, int Lp, double gamma_lam) {
+    k_gae_matrix<<<dim3((Lp + 255) / 256, Lp), 256, 0, st>>>(U, Lp, gamma_lam);
+    return hipGetLastError();
+}
+hipError_t launch_gae_returns(hipStream_t st, const float* A, const float* values, const int* gen_len,
+                              int stride, float* R, int n, int Lp) {
+    if (n <= 0) return hipSuccess;
+    k_gae_returns<<<n, 256, 0, st>>>(A, values, gen_len, stride, R, Lp);
+    return hipGetLastError();
+}
+
 }  // namespace rlhf

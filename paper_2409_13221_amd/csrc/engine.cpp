@@ -1284,6 +1284,63 @@ extern "C" int rlhf_debug_snapshot(rlhf_ctx* c, rlhf_snapshot* o) {
     return RLHF_OK;
 }
 
+// ====================================================================================== GAE
+
+extern "C" int rlhf_compute_gae(rlhf_ctx* c, float gamma, float lam, float kl_coef, float* advantages,
+                                float* returns, int64_t packed_capacity) {
+    if (!c) return RLHF_EINVAL;
+    if (!(gamma >= 0.f && gamma <= 1.f) || !(lam >= 0.f && lam <= 1.f))
+        return c->fail(RLHF_EINVAL, "rlhf_compute_gae: gamma and lam must be in [0, 1]");
+    int rc = rlhf_sync(c);
+    if (rc) return rc;
+    const int n = c->N, mc = c->ec.max_ctx;
+    int64_t total = 0;
+    int Lmax = 0;
+    std::vector<int> gl(n);
+    for (int i = 0; i < n; ++i) {
+        const Sample& s = c->smp[i];
+        if (!sample_done(s) || s.gen_len < 1) return c->fail(RLHF_ESTATE, "rlhf_compute_gae: sample %d is not finished", i);
+        gl[i] = s.gen_len;
+        total += s.gen_len;
+        Lmax = std::max(Lmax, s.gen_len);
+    }
+    if ((advantages || returns) && packed_capacity < total)
+        return c->fail(RLHF_EINVAL, "rlhf_compute_gae: packed_capacity %lld < %lld", (long long)packed_capacity, (long long)total);
+    if (n == 0) return RLHF_OK;
+    const int Lp = (Lmax + 15) / 16 * 16;
+    float *D = nullptr, *U = nullptr, *A = nullptr, *R = nullptr;
+    int* d_gl = nullptr;
+    auto cleanup = [&] { for (void* p : {(void*)D, (void*)U, (void*)A, (void*)R, (void*)d_gl}) if (p) (void)hipFree(p); };
+#define GAECK(call)                                                                              \
+    do {                                                                                         \
+        hipError_t e_ = (call);                                                                  \
+        if (e_ != hipSuccess) { cleanup(); return c->fail(RLHF_EDEVICE, "%s failed: %s", #call, hipGetErrorString(e_)); } \
+    } while (0)
+    GAECK(hipMalloc((void**)&D, (size_t)n * Lp * 4));
+    GAECK(hipMalloc((void**)&A, (size_t)n * Lp * 4));
+    GAECK(hipMalloc((void**)&R, (size_t)n * Lp * 4));
+    GAECK(hipMalloc((void**)&U, (size_t)Lp * Lp * 4));
+    GAECK(hipMalloc((void**)&d_gl, (size_t)n * sizeof(int)));
+    GAECK(hipMemcpyAsync(d_gl, gl.data(), (size_t)n * sizeof(int), hipMemcpyHostToDevice, c->sd));
+    GAECK(launch_gae_delta(c->sd, c->d_lp_actor, c->d_lp_ref, c->d_values, c->d_reward, d_gl, mc, gamma, kl_coef, D, n, Lp));
+    GAECK(launch_gae_matrix(c->sd, U, Lp, (double)gamma * (double)lam));
+    GAECK(launch_gemm(c->sd, kF32, kF32, D, U, A, n, Lp, Lp, 1));          // A = D U^T, one matrix multiply
+    GAECK(launch_gae_returns(c->sd, A, c->d_values, d_gl, mc, R, n, Lp));
+    std::vector<float> ha((size_t)n * Lp), hr((size_t)n * Lp);
+    GAECK(hipMemcpyAsync(ha.data(), A, ha.size() * 4, hipMemcpyDeviceToHost, c->sd));
+    GAECK(hipMemcpyAsync(hr.data(), R, hr.size() * 4, hipMemcpyDeviceToHost, c->sd));
+    GAECK(hipStreamSynchronize(c->sd));
+#undef GAECK
+    cleanup();
+    int64_t o = 0;
+    for (int i = 0; i < n; ++i) {
+        if (advantages) std::copy(ha.begin() + (size_t)i * Lp, ha.begin() + (size_t)i * Lp + gl[i], advantages + o);
+        if (returns) std::copy(hr.begin() + (size_t)i * Lp, hr.begin() + (size_t)i * Lp + gl[i], returns + o);
+        o += gl[i];
+    }
+    return RLHF_OK;
+}
+
 // ================================================================================ profiling
 
 extern "C" int rlhf_profile_begin(rlhf_ctx* c, int32_t sample_every) {

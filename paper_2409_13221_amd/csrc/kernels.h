@@ -62,6 +62,14 @@ hipError_t launch_head_dot(hipStream_t st, int adt, int wdt, const void* xn, con
 // page_table[upd_idx[i]] = upd_val[i]
 hipError_t launch_scatter_int(hipStream_t st, int* dst, const int* idx, const int* val, int n);
 
+// ---- GAE as one matrix multiply: D = delta (zero-padded [n, Lp]), U[t][s] = (gamma lam)^(s-t)
+hipError_t launch_gae_delta(hipStream_t st, const float* lp_actor, const float* lp_ref, const float* values,
+                            const float* reward, const int* gen_len, int stride, float gamma, float kl_coef,
+                            float* D, int n, int Lp);
+hipError_t launch_gae_matrix(hipStream_t st, float* U, int Lp, double gamma_lam);
+hipError_t launch_gae_returns(hipStream_t st, const float* A, const float* values, const int* gen_len,
+                              int stride, float* R, int n, int Lp);
+
 // ---- attention
 // Decode: one query row per active sample against its paged K/V.  q [rows, Hq*hd]; out the same.
 // row_sample[r] selects the page-table row; ctx_len[r] keys are visible.  part_* hold split

@@ -148,3 +148,66 @@ def test_gqa_bf16_small_model_matches_oracle():
     ref = H.oracle_stage(cfg, max_len=20)
     got = H.run_gpu_stage(cfg, ref, fused=True, R_t=6, chunk_tokens=64)
     print("gqa worst errors:", H.compare_stage(cfg, ref, got))
+
+
+# --------------------------------------------------------------- termination on EOS, GAE
+
+def test_tiny_stop_on_eos_matches_oracle():
+    """Generation "until reaching a termination token": the Actor's LM-head row of eos_id is
+    scaled up so that EOS becomes the greedy choice at scattered positions; samples end there,
+    earlier than their cap, and the bookkeeping follows."""
+    import torch
+    from oracle import transformer as OT
+    cfg = CONFIGS["tiny"].with_(gain_jitter=0.05)
+    inp = H.make_inputs(cfg, n=8)
+    inp["weights"][0]["head"][cfg.eos_id] *= 4.5
+    cap = 40
+    actor = H.oracle_models(cfg, inp)[0]
+    po = inp["prompt_offsets"]
+    prompts = [inp["prompt_tokens"][po[i]:po[i + 1]].tolist() for i in range(8)]
+    gen = OT.greedy_generate_cached(actor, prompts, [cap] * 8, cfg.eos_id, stop_at_eos=True)
+    lens = np.array([len(g.tokens) for g in gen], np.int32)
+    assert lens.min() < cap and len(set(lens.tolist())) > 2, lens          # EOS really ends samples early
+    inp["out_len"] = lens
+    forced = [np.where(g.margin < H.MARGIN, g.tokens, -1).astype(np.int32) for g in gen]
+    with H.GpuStage(cfg, inp, stop_on_eos=True, max_new_cap=cap) as g:
+        g.submit(forced, use_forced_len=False)
+        model = H.scheduler_model_for(g)
+        while not model.generation_done():
+            info, want = g.R.rlhf_generate_step(g.ctx), model.generate_step()
+            assert (info.n_admitted, info.n_decoded, info.n_active) == (want.n_admitted, want.n_decoded, want.n_active)
+            assert g.R.rlhf_retire(g.ctx, g.n).tolist() == model.retire()
+            snap = g.snapshot()
+            assert snap["active"] == model.active and snap["free"] == model.free
+        got = g.results()
+    assert got["gen_len"].tolist() == lens.tolist()
+    for i, gi in enumerate(gen):
+        np.testing.assert_array_equal(H.unpack(got, "tokens")[i], gi.tokens)
+        assert np.abs(H.unpack(got, "lp_actor")[i] - gi.logprob).max() <= 1e-4
+        assert gi.tokens[-1] == cfg.eos_id or len(gi.tokens) == cap
+
+
+@pytest.mark.parametrize("which", ["tiny", "gpt2s"])
+def test_gae_single_matmul_matches_recursion(which, tiny_ref, gpt2s_ref):
+    """Section 6: GAE unrolled into one matrix multiply, against the backward recursion fed with
+    the oracle's own log-probs, values and rewards."""
+    from oracle.gae import gae, token_rewards
+    cfg, ref = tiny_ref if which == "tiny" else gpt2s_ref
+    gamma, lam, kl = 0.99, 0.95, 0.1
+    with H.GpuStage(cfg, ref) as g:
+        g.submit(ref["forced"])
+        g.R.rlhf_run_stage(g.ctx, True, g.n + 1, 256, 0b1110)
+        res = g.results()
+        adv, ret = g.R.rlhf_compute_gae(g.ctx, gamma, lam, kl, int(g.max_new.sum()))
+    o = res["resp_offsets"]
+    want_a, want_r = [], []
+    for i in range(g.n):
+        a, r = gae(token_rewards(ref["lp_actor"][i], ref["lp_ref"][i], ref["reward"][i], kl), ref["values"][i], gamma, lam)
+        want_a.append(a); want_r.append(r)
+    want_a, want_r = np.concatenate(want_a), np.concatenate(want_r)
+    got_a, got_r = adv[:o[-1]], ret[:o[-1]]
+    if which == "tiny":          # float model: inputs agree to 1e-6, the product adds float32 rounding
+        np.testing.assert_allclose(got_a, want_a, rtol=0, atol=2e-5)
+        np.testing.assert_allclose(got_r, want_r, rtol=0, atol=2e-5)
+    else:                        # bf16 model: the inputs carry the activation rounding of the stage
+        assert H.rel_err(got_a, want_a) <= 1e-2 and H.rel_err(got_r, want_r) <= 1e-2

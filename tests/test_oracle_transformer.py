@@ -306,6 +306,24 @@ def test_generation_semantics():
     assert T._pick(np.array([0.0, 3.0, 3.0, 1.0]), -1)[0] == 1
 
 
+def test_stop_at_eos_semantics():
+    """"Until reaching a termination token": with stop_at_eos the response ends at the first
+    emitted eos_id; both generation variants agree, and the prefix equals free greedy decoding."""
+    model, w, s = rand_model(21)
+    prompt = [4, 9, 3]
+    free = T.greedy_generate(model, prompt, 12, eos_id=2, stop_at_eos=True)
+    # make the free run's 4th token the termination token and generate again
+    eos = int(free.tokens[3])
+    a = T.greedy_generate(model, prompt, 12, eos_id=eos, stop_at_eos=True)
+    first = int(np.argmax(free.tokens == eos))
+    assert len(a.tokens) == first + 1 <= 4 and a.tokens[-1] == eos
+    np.testing.assert_array_equal(a.tokens, free.tokens[:first + 1])
+    b = T.greedy_generate_cached(model, [prompt, prompt], [12, 2], eos, stop_at_eos=True)
+    np.testing.assert_array_equal(a.tokens, b[0].tokens)
+    assert len(b[1].tokens) == min(2, first + 1)                # the cap still applies, nothing imposed
+    np.testing.assert_array_equal(b[1].tokens, free.tokens[:len(b[1].tokens)])
+
+
 def test_scoring_alignment_and_heads():
     actor, _, s = rand_model(13)
     critic, wc, _ = rand_model(14, head_rows=1)
