@@ -189,6 +189,59 @@ def micro(args):
     print(json.dumps({"micro": out}), flush=True)
 
 
+def rt_sweep(cfg, args):
+    """Fused stage time against the trigger R_t (Section 4.2, Figure 9's single-GPU analogue):
+    R_t = 0 is the serial plan, R_t > N scores from the first retirement on."""
+    R, ctx, weights, wl, max_new = build_stage(cfg, args)
+    n = len(max_new)
+    out = []
+    run_stage(R, ctx, wl, max_new, True, args)                      # warm-up
+    for frac in (0.0, 0.05, 0.1, 0.2, 0.35, 0.5, 0.75, 1.01):
+        args.R_t = int(round(frac * n)) if frac <= 1.0 else n + 1
+        ms, st, _ = run_stage(R, ctx, wl, max_new, args.R_t > 0, args)
+        out.append({"R_t_over_N": frac, "R_t": args.R_t, "stage_ms": round(ms, 1), "batches": int(st.n_batches),
+                    "decode_stream_ms": round(st.decode_stream_ms, 1), "score_stream_ms": round(st.score_stream_ms, 1)})
+        log(f"[rt_sweep] R_t/N = {frac}: {ms:.0f} ms")
+    R.rlhf_destroy(ctx)
+    print(json.dumps({"rt_sweep": out, "workload": cfg.name, "score_chunk_tokens": args.score_chunk_tokens}), flush=True)
+
+
+def bs_curve(cfg, args):
+    """Decode step latency against the batch size B at a fixed context (the BS_max of
+    Section 4.2: latency stays flat while decoding is bandwidth-bound)."""
+    import torch
+
+    import paper_2409_13221_amd as R
+    from workload import make_weights
+    m = cfg.model
+    actor = make_weights(cfg, 0, device="cuda")
+    P, steps = args.bs_ctx, 24
+    page_b = m.n_layers * 2 * m.n_kv_heads * cfg.page_tokens * m.head_dim * m.elem_bytes()
+    out = []
+    for B in (1, 2, 4, 8, 16, 32, 64, 128, 256):
+        pages = B * -(-(P + steps + 2) // cfg.page_tokens)
+        ec = R.rlhf_engine_cfg(cfg.page_tokens, pages * page_b, B, P + steps + 2, B, max(8192, P + steps + 2),
+                               cfg.eos_id, 0, 0, 0, None, None)
+        ctx = R.rlhf_create(R.model_cfg_of(m), ec)
+        R.rlhf_load_weights(ctx, 0, actor)
+        rng = np.random.default_rng(B)
+        toks = rng.integers(3, m.vocab, B * P).astype(np.int32)
+        offs = (np.arange(B + 1) * P).astype(np.int64)
+        lens = np.full(B, steps + 1, np.int32)
+        med = []
+        for rep in range(2):
+            R.rlhf_submit(ctx, toks, offs, lens, lens)
+            st, tr = R.rlhf_run_stage(ctx, False, 0, 1 << 30, 0, trace_cap=64, trace_time=True)
+            med.append(float(np.median(tr["step_ms"][2:])))          # step 0 holds the prefill
+        kv = B * (P + steps // 2) * m.kv_bytes_per_token()
+        ms = min(med)
+        out.append({"B": B, "ctx": P, "step_ms": round(ms, 3), "tokens_per_s": round(B / ms * 1e3, 1),
+                    "hbm_GBps": round((m.decode_weight_bytes() + kv) / ms / 1e6, 1)})
+        log(f"[bs_curve] B = {B}: {ms:.3f} ms/step")
+        R.rlhf_destroy(ctx)
+    print(json.dumps({"bs_curve": out, "workload": cfg.name}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -206,6 +259,9 @@ def main():
                     help="time every n-th launch of a kernel class (co-prime with the 4 GEMMs per layer)")
     ap.add_argument("--sequential", action="store_true",
                     help="time the serial generate-then-score plan instead (clean per-kernel figures)")
+    ap.add_argument("--rt_sweep", action="store_true", help="fused stage time vs the trigger R_t")
+    ap.add_argument("--bs_curve", action="store_true", help="decode step latency vs batch size (BS_max)")
+    ap.add_argument("--bs_ctx", type=int, default=512)
     ap.add_argument("--micro", action="store_true", help="run the kernel-level cases instead of the stage")
     ap.add_argument("--micro_reps", type=int, default=5)
     ap.add_argument("--no_cpu", action="store_true")
@@ -226,6 +282,12 @@ def main():
         return
     torch.cuda.set_device(0)
     cfg = CONFIGS[args.config]
+    if args.rt_sweep:
+        rt_sweep(cfg, args)
+        return
+    if args.bs_curve:
+        bs_curve(cfg, args)
+        return
     R, ctx, weights, wl, max_new = build_stage(cfg, args)
 
     for i in range(args.warmup):

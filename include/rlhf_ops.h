@@ -29,6 +29,13 @@ int rlhf_op_gemm_nsplit(int dtype, int M, int N, int K, int max_split);
 int rlhf_op_gemm(int dtype, int act_half, const void* A, const void* W, float* C, int M, int N, int K,
                  int nsplit, int variant, void* stream);
 
+/* Gate||up projection of the SwiGLU MLP with the activation fused into the epilogue, as the
+ * stage runs it in prefill / scoring passes: act[m][c] = silu(<A[m], W[c]>) * <A[m], W[ffn + c]>.
+ * W_gate_up bf16 [2*ffn, K] (gate rows, then up rows); A and act IEEE half (act_half != 0) or
+ * bf16, [M, K] and [M, ffn].  Needs M >= 512, ffn and K multiples of 8 (else RLHF_EINVAL). */
+int rlhf_op_gemm_swiglu(int act_half, const void* A, const void* W_gate_up, void* act, int M, int ffn, int K,
+                        void* stream);
+
 /* Decode attention of one step (Section 2.1, decoding phase): row r holds one query
  * [n_q_heads * head_dim] and attends to the ctx_len[r] cached tokens of the sample whose
  * page-table row is row_sample[r].  pool layout: [page][layer][K|V][kv_head][16][head_dim].

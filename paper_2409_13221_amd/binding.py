@@ -122,11 +122,12 @@ def lib() -> C.CDLL:
         L.rlhf_op_paged_decode_attention.argtypes = [C.c_int, vp, vp, vp, C.c_int, vp, vp, vp, vp, vp] + [C.c_int] * 7 + [vp]
         L.rlhf_op_varlen_attention.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp] + [C.c_int] * 4 + [vp]
         L.rlhf_op_flash_attention.argtypes = [vp] * 7 + [C.c_int] * 5 + [vp]
+        L.rlhf_op_gemm_swiglu.argtypes = [C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp]
         for name in ("rlhf_create", "rlhf_load_weights", "rlhf_submit", "rlhf_generate_step", "rlhf_retire",
                      "rlhf_score", "rlhf_run_stage", "rlhf_get_results", "rlhf_debug_snapshot", "rlhf_sync",
                      "rlhf_profile_begin", "rlhf_profile_end", "rlhf_compute_gae",
                      "rlhf_op_gemm_nsplit", "rlhf_op_gemm", "rlhf_op_paged_decode_attention",
-                     "rlhf_op_varlen_attention", "rlhf_op_flash_attention"):
+                     "rlhf_op_varlen_attention", "rlhf_op_flash_attention", "rlhf_op_gemm_swiglu"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -364,3 +365,13 @@ def rlhf_op_flash_attention(q, k, v, seq_lens, out, n_q_heads: int, n_kv_heads: 
                                             d_tl.data_ptr(), out.data_ptr(), len(ts), q.shape[0], n_q_heads,
                                             n_kv_heads, head_dim, _stream_ptr()), "rlhf_op_flash_attention")
     return d_ts, d_tq, d_tl          # keep alive until the stream has run
+
+
+def rlhf_op_gemm_swiglu(A, W_gate_up, act) -> None:
+    """A [M,K] float16 or bfloat16, W_gate_up bfloat16 [2f, K], act [M, f] of A's dtype."""
+    import torch
+    M, K = A.shape
+    f = W_gate_up.shape[0] // 2
+    assert W_gate_up.dtype == torch.bfloat16 and act.dtype == A.dtype and tuple(act.shape) == (M, f)
+    _op_check(lib().rlhf_op_gemm_swiglu(int(A.dtype == torch.float16), A.data_ptr(), W_gate_up.data_ptr(),
+                                        act.data_ptr(), M, f, K, _stream_ptr()), "rlhf_op_gemm_swiglu")

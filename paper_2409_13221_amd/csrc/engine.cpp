@@ -352,10 +352,17 @@ int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
         HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.attn, layer_ptr(w.wo, l, d, qd, es), ws.part, rows, d, qd, ns));
         HIPCK(c, launch_rmsnorm(st, adt, ws.h, ws.part, ns, (size_t)rows * d, nullptr,
                                 w.g_mlp + (size_t)l * d, ws.xn, rows, d, m.rms_eps));
-        ns = nsplit_for(c, ws, rows, 2 * f, d);
-        HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.xn, layer_ptr(w.w_gate_up, l, 2 * (size_t)f, d, es), ws.part, rows,
-                               2 * f, d, ns));
-        HIPCK(c, launch_swiglu(st, adt, ws.part, ns, (size_t)rows * 2 * f, ws.act, rows, f));
+        if (gemm_swiglu_supported(dt, adt, rows, f, d)) {
+            const void* wgu = layer_ptr(w.w_gate_up, l, 2 * (size_t)f, d, es);
+            const double bytes = (2.0 * f * d + (double)rows * d) * es + (double)rows * f * es;
+            HIPCK(c, profiled(c, st, gcls, bytes, 4.0 * rows * f * d,
+                              [&] { return launch_gemm_swiglu(st, dt, adt, ws.xn, wgu, ws.act, rows, f, d); }));
+        } else {
+            ns = nsplit_for(c, ws, rows, 2 * f, d);
+            HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.xn, layer_ptr(w.w_gate_up, l, 2 * (size_t)f, d, es), ws.part,
+                                   rows, 2 * f, d, ns));
+            HIPCK(c, launch_swiglu(st, adt, ws.part, ns, (size_t)rows * 2 * f, ws.act, rows, f));
+        }
         pns = nsplit_for(c, ws, rows, d, f);
         pstride = (size_t)rows * d;
         HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.act, layer_ptr(w.w_down, l, d, f, es), ws.part, rows, d, f, pns));

@@ -72,7 +72,13 @@ __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int& 
 // A: 16-bit activations (bf16 if !AF16, half if AF16); W: bf16.
 // TM x TN output tile per workgroup of WM x WN waves; each wave owns (TM/WM) x (TN/WN), built
 // from 16x16 MFMA fragments; K advances in LDS tiles of TK (32 or 64) elements, double-buffered.
-template <int TM, int TN, int TK, int WM, int WN, bool AF16, bool XCD>
+//
+// SWIGLU: W is a gate||up matrix [2f, K] (gate rows, then up rows) and N = 2f.  The tile's
+// columns alternate, in blocks of 16, between gate rows and the matching up rows, so that a
+// lane ends up with gate and up of the same output column in neighbouring fragments; the
+// epilogue writes act = silu(gate) * up as 16-bit [M, f] (of the activation type) to C and the
+// float [M, 2f] intermediate never exists.
+template <int TM, int TN, int TK, int WM, int WN, bool AF16, bool XCD, bool SWIGLU>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __restrict__ A,
                                                            const bf16_t* __restrict__ W,
                                                            float* __restrict__ C, int M, int N, int K,
@@ -112,9 +118,16 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
         for (int i = 0; i < B_IT; ++i) {
             const int idx = t + i * NT;
             const int row = idx / CH, c = idx % CH;
-            const int gn = n0 + row, gk = k0 + c * 8;
+            int gn = n0 + row;
+            bool ok = gn < N;
+            if (SWIGLU) {      // tile column -> gate row (even 16-blocks) or up row (odd) of out col
+                const int oc = (n0 >> 1) + (row >> 5) * 16 + (row & 15);
+                ok = oc < (N >> 1);
+                gn = ((row >> 4) & 1) * (N >> 1) + oc;
+            }
+            const int gk = k0 + c * 8;
             rb[i] = make_uint4(0, 0, 0, 0);
-            if (idx < B_CH && gn < N && gk < kend)
+            if (idx < B_CH && ok && gk < kend)
                 rb[i] = *reinterpret_cast<const uint4*>(W + (size_t)gn * K + gk);
         }
     };
@@ -180,6 +193,38 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
         __syncthreads();
     }
 
+    if (SWIGLU) {
+        static_assert(!SWIGLU || (FN % 2 == 0), "gate and up fragments come in pairs");
+        const int f = N >> 1;
+        uint16_t* act = reinterpret_cast<uint16_t*>(C);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int m = m0 + wm * (TM / WM) + i * 16 + fr;
+            if (m >= M) continue;
+#pragma unroll
+            for (int j = 0; j < FN; j += 2) {
+                const int oc = (n0 >> 1) + ((wn * (TN / WN) + j * 16) >> 1) + fq * 4;
+                if (oc >= f) continue;       // f is a multiple of 8: a group of 4 is in or out
+                float o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float g = acc[i][j][e];
+                    o[e] = g / (1.f + __expf(-g)) * acc[i][j + 1][e];
+                }
+                uint2 pk;
+                if (AF16) {
+                    fp16x2_t a = {(__fp16)o[0], (__fp16)o[1]}, b = {(__fp16)o[2], (__fp16)o[3]};
+                    pk.x = *reinterpret_cast<uint32_t*>(&a);
+                    pk.y = *reinterpret_cast<uint32_t*>(&b);
+                } else {
+                    pk.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
+                    pk.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
+                }
+                *reinterpret_cast<uint2*>(act + (size_t)m * f + oc) = pk;
+            }
+        }
+        return;
+    }
     float* Cs = C + (size_t)split * M * N;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
@@ -309,8 +354,8 @@ static hipError_t launch_bf16(hipStream_t st, int variant, const bf16_t* a, cons
     if (c.xcd) blocks = (blocks + 7) / 8 * 8;
     dim3 grid(blocks, nsplit);
 #define RLHF_GEMM(TM, TN, TK, WM, WN, XCD)                                                            \
-    k_gemm_bf16<TM, TN, TK, WM, WN, AF16, XCD><<<grid, WM * WN * 64, 0, st>>>(a, w, C, M, N, K, kchunk, \
-                                                                              tiles_m, tiles_n)
+    k_gemm_bf16<TM, TN, TK, WM, WN, AF16, XCD, false><<<grid, WM * WN * 64, 0, st>>>(a, w, C, M, N, K, kchunk, \
+                                                                                     tiles_m, tiles_n)
     switch (variant) {
         case 1: RLHF_GEMM(16, 128, 64, 1, 4, false); break;
         case 2: RLHF_GEMM(32, 128, 64, 1, 4, false); break;
@@ -327,6 +372,27 @@ static hipError_t launch_bf16(hipStream_t st, int variant, const bf16_t* a, cons
         default: return hipErrorInvalidValue;
     }
 #undef RLHF_GEMM
+    return hipGetLastError();
+}
+
+bool gemm_swiglu_supported(int wdt, int adt, int M, int ffn, int K) {
+    return wdt == kBF16 && (adt == kF16 || adt == kBF16) && M >= 512 && ffn % 8 == 0 && K % 8 == 0;
+}
+
+hipError_t launch_gemm_swiglu(hipStream_t st, int wdt, int adt, const void* A, const void* W_gate_up,
+                              void* act, int M, int ffn, int K) {
+    if (!gemm_swiglu_supported(wdt, adt, M, ffn, K)) return hipErrorInvalidValue;
+    constexpr int TM = 256, TN = 256;
+    const int N = 2 * ffn;
+    const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
+    dim3 grid((tiles_m * tiles_n + 7) / 8 * 8, 1);
+    const int kchunk = (K + 63) / 64 * 64;
+    if (adt == kF16)
+        k_gemm_bf16<TM, TN, 64, 4, 2, true, true, true><<<grid, 512, 0, st>>>(
+            (const bf16_t*)A, (const bf16_t*)W_gate_up, (float*)act, M, N, K, kchunk, tiles_m, tiles_n);
+    else
+        k_gemm_bf16<TM, TN, 64, 4, 2, false, true, true><<<grid, 512, 0, st>>>(
+            (const bf16_t*)A, (const bf16_t*)W_gate_up, (float*)act, M, N, K, kchunk, tiles_m, tiles_n);
     return hipGetLastError();
 }
 

@@ -27,6 +27,12 @@ int gemm_choose_nsplit(int wdt, int M, int N, int K, int max_split);
 hipError_t launch_gemm(hipStream_t st, int wdt, int adt, const void* A, const void* W, float* C,
                        int M, int N, int K, int nsplit, int variant = 0);
 
+// Gate||up projection with SwiGLU fused into the epilogue (tall passes of bf16 models):
+// act[m][c] = silu(<A[m], W[c]>) * <A[m], W[ffn + c]>, written as adt [M, ffn].
+bool gemm_swiglu_supported(int wdt, int adt, int M, int ffn, int K);
+hipError_t launch_gemm_swiglu(hipStream_t st, int wdt, int adt, const void* A, const void* W_gate_up,
+                              void* act, int M, int ffn, int K);
+
 // ---- elementwise / row kernels
 hipError_t launch_embed(hipStream_t st, int dtype, const int* tokens, const int* tok_idx,
                         const void* table, float* h, int rows, int d, int vocab);

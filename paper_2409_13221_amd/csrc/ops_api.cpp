@@ -65,3 +65,11 @@ extern "C" int rlhf_op_flash_attention(const void* q, const void* k, const void*
     return status_of(launch_flash_attn((hipStream_t)stream, q, k, v, tile_start, tile_q0, tile_len, out, n_tiles,
                                        rows, dm));
 }
+
+extern "C" int rlhf_op_gemm_swiglu(int act_half, const void* A, const void* W_gate_up, void* act, int M, int ffn,
+                                   int K, void* stream) {
+    if (!A || !W_gate_up || !act) return RLHF_EINVAL;
+    const int adt = act_half ? kF16 : kBF16;
+    if (!gemm_swiglu_supported(kBF16, adt, M, ffn, K)) return RLHF_EINVAL;
+    return status_of(launch_gemm_swiglu((hipStream_t)stream, kBF16, adt, A, W_gate_up, act, M, ffn, K));
+}

@@ -162,3 +162,23 @@ def test_gemm_compute_bound_tilings(variant, half_act):
     R.rlhf_op_gemm(A, W, out, 1, variant)
     torch.cuda.synchronize()
     np.testing.assert_allclose(out[0].double().cpu().numpy(), want, rtol=0, atol=2e-5)
+
+
+@pytest.mark.parametrize("half_act", [True, False])
+@pytest.mark.parametrize("M,f,K", [(512, 688, 256), (700, 1000, 328), (1024, 11008, 512)])
+def test_gemm_swiglu_fused(half_act, M, f, K):
+    """Gate||up projection with the SwiGLU epilogue against float64 (ragged M, f, K edges)."""
+    R = _R()
+    r = np.random.default_rng(f)
+    a, w = r.normal(size=(M, K)), r.normal(size=(2 * f, K)) * 0.06
+    A = torch.from_numpy(a.astype(np.float32)).half().cuda() if half_act else _bf16_round(a).cuda()
+    W = _bf16_round(w).cuda()
+    z = A.double().cpu().numpy() @ W.double().cpu().numpy().T
+    want = OT.silu(z[:, :f]) * z[:, f:]
+    act = torch.full((M, f), float("nan"), dtype=A.dtype, device="cuda")
+    R.rlhf_op_gemm_swiglu(A, W, act)
+    torch.cuda.synchronize()
+    got = act.double().cpu().numpy()
+    assert np.isfinite(got).all() and np.abs(want).max() > 0.3
+    tol = (2 ** -11 if half_act else 2 ** -8) * np.maximum(np.abs(want), 1e-2) + 1e-4   # output rounding
+    assert np.all(np.abs(got - want) <= tol), np.abs(got - want).max()
