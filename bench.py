@@ -62,7 +62,7 @@ def build_stage(cfg, args):
     pool_pages = int(min(need_pages, max(1, (free_b - ws_est) // page_b)))
     mc = R.model_cfg_of(m)
     ec = R.rlhf_engine_cfg(cfg.page_tokens, pool_pages * page_b, n, max_ctx, min(n, args.max_active),
-                           max_batch_tokens, cfg.eos_id, 0, args.decode_cus, args.score_cus, None, None)
+                           max_batch_tokens, cfg.eos_id, 0, args.corun_decode_cus, 0, None, None)
     ctx = R.rlhf_create(mc, ec)
     for role, w in enumerate(weights):
         R.rlhf_load_weights(ctx, role, w)
@@ -253,8 +253,8 @@ def main():
     ap.add_argument("--max_batch_tokens", type=int, default=8192)
     ap.add_argument("--max_active", type=int, default=256)
     ap.add_argument("--role_mask", type=int, default=ROLE_MASK_DEFAULT)
-    ap.add_argument("--decode_cus", type=int, default=0, help="CU-mask size of the decode stream (0 = all)")
-    ap.add_argument("--score_cus", type=int, default=0, help="CU-mask size of the score stream (0 = all)")
+    ap.add_argument("--corun_decode_cus", type=int, default=0,
+                    help="compute units given to decoding while scoring is in flight (0 = no partition)")
     ap.add_argument("--sample_every", type=int, default=7,
                     help="time every n-th launch of a kernel class (co-prime with the 4 GEMMs per layer)")
     ap.add_argument("--sequential", action="store_true",
@@ -362,7 +362,7 @@ def main():
            "config": {"workload": cfg.name, "n_samples": int(len(max_new)), "length_law": cfg.length_law,
                       "length_params": list(cfg.length_params), "length_cap": cfg.length_cap,
                       "plan": "sequential" if args.sequential else "fused",
-                      "decode_cus": args.decode_cus, "score_cus": args.score_cus,
+                      "corun_decode_cus": args.corun_decode_cus,
                       "score_chunk_tokens": args.score_chunk_tokens, "R_t": args.R_t, "role_mask": args.role_mask,
                       "page_tokens": cfg.page_tokens},
            "roofline": roof, "cpu_baseline": cpu, "fused_vs_sequential": seq, "kernels": kernels,

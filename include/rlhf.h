@@ -73,13 +73,14 @@ typedef struct rlhf_engine_cfg {
     int32_t eos_id;                /* termination token                                       */
     int32_t stop_on_eos;           /* 1: a sample also ends when it emits eos_id (costs one
                                       device->host copy per step); 0: length-driven only     */
-    int32_t decode_cus;            /* > 0: the decode stream the library creates may use only
-                                      this many compute units (CU-mask bits from the low end) */
-    int32_t score_cus;             /* > 0: likewise for the score stream, bits from the high
-                                      end; decode_cus + score_cus <= total keeps the two sets
-                                      disjoint, so that bandwidth-bound decoding and
-                                      matrix-bound scoring do not queue behind one another.
-                                      0 = the whole chip.  Ignored for caller-given streams   */
+    int32_t corun_decode_cus;      /* > 0: while scoring work is in flight inside rlhf_run_stage,
+                                      decode steps are issued on a stream whose CU mask holds
+                                      this many compute units (bits from the low end) and
+                                      scoring on a stream with the remaining ones, so that the
+                                      bandwidth-bound and the matrix-bound work do not queue
+                                      behind one another; whichever side is alone uses the whole
+                                      chip.  0 = no partition.  Needs a multiple of 32          */
+    int32_t reserved;              /* must be 0                                                */
     void* decode_stream;           /* hipStream_t to use, or NULL: the library creates one    */
     void* score_stream;            /* hipStream_t to use, or NULL                             */
 } rlhf_engine_cfg;

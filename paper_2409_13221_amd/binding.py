@@ -39,8 +39,8 @@ class rlhf_model_cfg(C.Structure):
 class rlhf_engine_cfg(C.Structure):
     _fields_ = [("page_tokens", C.c_int32), ("kv_pool_bytes", C.c_int64), ("max_samples", C.c_int32),
                 ("max_ctx", C.c_int32), ("max_active", C.c_int32), ("max_batch_tokens", C.c_int32),
-                ("eos_id", C.c_int32), ("stop_on_eos", C.c_int32), ("decode_cus", C.c_int32),
-                ("score_cus", C.c_int32), ("decode_stream", C.c_void_p),
+                ("eos_id", C.c_int32), ("stop_on_eos", C.c_int32), ("corun_decode_cus", C.c_int32),
+                ("reserved", C.c_int32), ("decode_stream", C.c_void_p),
                 ("score_stream", C.c_void_p)]
 
 

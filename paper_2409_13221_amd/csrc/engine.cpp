@@ -132,8 +132,11 @@ struct rlhf_ctx {
     int max_pages = 0, pool_pages = 0;
     char err[512] = "";
 
-    hipStream_t sd = nullptr, ss = nullptr;
+    hipStream_t sd = nullptr, ss = nullptr;            // the streams decode / scoring work goes to NOW
+    hipStream_t sd_full = nullptr, ss_full = nullptr;  // whole chip
+    hipStream_t sd_part = nullptr, ss_part = nullptr;  // disjoint CU masks for co-running (optional)
     bool own_sd = false, own_ss = false;
+    hipEvent_t ev_sw_d = nullptr, ev_sw_s = nullptr, ev_score_last = nullptr;
     hipEvent_t ev_dep = nullptr;                       // decode -> score dependency
     hipEvent_t ev_d0 = nullptr, ev_d1 = nullptr, ev_s0 = nullptr, ev_s1 = nullptr;
     std::vector<hipEvent_t> step_events;
@@ -380,8 +383,8 @@ extern "C" const char* rlhf_last_error(const rlhf_ctx* ctx) { return ctx ? ctx->
 
 extern "C" void rlhf_destroy(rlhf_ctx* c) {
     if (!c) return;
-    if (c->sd) (void)hipStreamSynchronize(c->sd);
-    if (c->ss) (void)hipStreamSynchronize(c->ss);
+    for (hipStream_t st : {c->sd_full, c->ss_full, c->sd_part, c->ss_part})
+        if (st) (void)hipStreamSynchronize(st);
     free_workspace(c->ws_dec);
     free_workspace(c->ws_pre);
     free_workspace(c->ws_score);
@@ -393,13 +396,15 @@ extern "C" void rlhf_destroy(rlhf_ctx* c) {
     for (void* p : bufs)
         if (p) (void)hipFree(p);
     if (c->h_picked) (void)hipHostFree(c->h_picked);
-    hipEvent_t evs[] = {c->ev_dep, c->ev_d0, c->ev_d1, c->ev_s0, c->ev_s1};
+    hipEvent_t evs[] = {c->ev_dep, c->ev_d0, c->ev_d1, c->ev_s0, c->ev_s1, c->ev_sw_d, c->ev_sw_s, c->ev_score_last};
     for (hipEvent_t e : evs)
         if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->step_events) (void)hipEventDestroy(e);
     for (auto& r : c->prof.recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
-    if (c->own_sd && c->sd) (void)hipStreamDestroy(c->sd);
-    if (c->own_ss && c->ss) (void)hipStreamDestroy(c->ss);
+    if (c->own_sd && c->sd_full) (void)hipStreamDestroy(c->sd_full);
+    if (c->own_ss && c->ss_full) (void)hipStreamDestroy(c->ss_full);
+    if (c->sd_part) (void)hipStreamDestroy(c->sd_part);
+    if (c->ss_part) (void)hipStreamDestroy(c->ss_part);
     delete c;
 }
 
@@ -441,21 +446,26 @@ static int create_impl(rlhf_ctx* c) {
         HIPCK(c, hipGetDevice(&dev));
         HIPCK(c, hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
     }
-    if (e.decode_cus < 0 || e.score_cus < 0 || e.decode_cus > n_cus || e.score_cus > n_cus)
-        return c->fail(RLHF_EINVAL, "decode_cus / score_cus must be in [0, %d]", n_cus);
-    auto make_stream = [&](hipStream_t* st, int cus, bool from_top) -> hipError_t {
-        if (cus <= 0 || cus >= n_cus) return hipStreamCreateWithFlags(st, hipStreamNonBlocking);
+    if (e.corun_decode_cus < 0 || e.corun_decode_cus >= n_cus || e.corun_decode_cus % 32 || e.reserved != 0)
+        return c->fail(RLHF_EINVAL, "corun_decode_cus must be a multiple of 32 in [0, %d) and reserved must be 0", n_cus);
+    auto make_masked = [&](hipStream_t* st, int lo, int hi) -> hipError_t {   // CU-mask bits [lo, hi)
         std::vector<uint32_t> mask((n_cus + 31) / 32, 0u);
-        for (int k = 0; k < cus; ++k) {
-            const int bit = from_top ? n_cus - 1 - k : k;
-            mask[bit >> 5] |= 1u << (bit & 31);
-        }
+        for (int bit = lo; bit < hi; ++bit) mask[bit >> 5] |= 1u << (bit & 31);
         return hipExtStreamCreateWithCUMask(st, (uint32_t)mask.size(), mask.data());
     };
-    if (e.decode_stream) c->sd = (hipStream_t)e.decode_stream;
-    else { HIPCK(c, make_stream(&c->sd, e.decode_cus, false)); c->own_sd = true; }
-    if (e.score_stream) c->ss = (hipStream_t)e.score_stream;
-    else { HIPCK(c, make_stream(&c->ss, e.score_cus, true)); c->own_ss = true; }
+    if (e.decode_stream) c->sd_full = (hipStream_t)e.decode_stream;
+    else { HIPCK(c, hipStreamCreateWithFlags(&c->sd_full, hipStreamNonBlocking)); c->own_sd = true; }
+    if (e.score_stream) c->ss_full = (hipStream_t)e.score_stream;
+    else { HIPCK(c, hipStreamCreateWithFlags(&c->ss_full, hipStreamNonBlocking)); c->own_ss = true; }
+    if (e.corun_decode_cus > 0) {
+        HIPCK(c, make_masked(&c->sd_part, 0, e.corun_decode_cus));
+        HIPCK(c, make_masked(&c->ss_part, e.corun_decode_cus, n_cus));
+    }
+    c->sd = c->sd_full;
+    c->ss = c->ss_full;
+    HIPCK(c, hipEventCreateWithFlags(&c->ev_sw_d, hipEventDisableTiming));
+    HIPCK(c, hipEventCreateWithFlags(&c->ev_sw_s, hipEventDisableTiming));
+    HIPCK(c, hipEventCreateWithFlags(&c->ev_score_last, hipEventDisableTiming));
     HIPCK(c, hipEventCreateWithFlags(&c->ev_dep, hipEventDisableTiming));
     HIPCK(c, hipEventCreate(&c->ev_d0));
     HIPCK(c, hipEventCreate(&c->ev_d1));
@@ -535,10 +545,22 @@ extern "C" int rlhf_load_weights(rlhf_ctx* c, int role, const rlhf_weights* w) {
 
 extern "C" int rlhf_sync(rlhf_ctx* c) {
     if (!c) return RLHF_EINVAL;
-    HIPCK(c, hipStreamSynchronize(c->sd));
-    HIPCK(c, hipStreamSynchronize(c->ss));
+    for (hipStream_t st : {c->sd_full, c->ss_full, c->sd_part, c->ss_part})
+        if (st) HIPCK(c, hipStreamSynchronize(st));
     return RLHF_OK;
 }
+
+namespace {
+// Continue a logical stream (decode or scoring) on another HIP stream: the new one first waits
+// for everything issued on the old one.
+int switch_stream(rlhf_ctx* c, hipStream_t* cur, hipStream_t next, hipEvent_t ev) {
+    if (*cur == next || !next) return RLHF_OK;
+    HIPCK(c, hipEventRecord(ev, *cur));
+    HIPCK(c, hipStreamWaitEvent(next, ev, 0));
+    *cur = next;
+    return RLHF_OK;
+}
+}  // namespace
 
 // =================================================================================== submit
 
@@ -1051,6 +1073,12 @@ int score_ids(rlhf_ctx* c, const int* ids, int n, uint32_t role_mask, bool on_sc
         if (!sample_done(c->smp[ids[k]]) || c->smp[ids[k]].gen_len < 1)
             return c->fail(RLHF_ESTATE, "rlhf_score: sample %d is still generating", ids[k]);
     }
+    if (on_score_stream && c->ss_part) {
+        // generation still running: keep to the scoring share of the chip; otherwise take it all
+        const bool generating = !c->waiting.empty() || !c->active.empty();
+        int rc = switch_stream(c, &c->ss, generating ? c->ss_part : c->ss_full, c->ev_sw_s);
+        if (rc) return rc;
+    }
     hipStream_t st = on_score_stream ? c->ss : c->sd;
     Workspace& ws = on_score_stream ? c->ws_score : c->ws_pre;
     MetaRing& meta = on_score_stream ? c->meta_score : c->meta_pre;
@@ -1078,6 +1106,7 @@ int score_ids(rlhf_ctx* c, const int* ids, int n, uint32_t role_mask, bool on_sc
             }
         lo = hi;
     }
+    if (on_score_stream) HIPCK(c, hipEventRecord(c->ev_score_last, c->ss));
     return RLHF_OK;
 }
 
@@ -1141,6 +1170,12 @@ extern "C" int rlhf_run_stage(rlhf_ctx* c, const rlhf_stage_opts* o, rlhf_stage_
         return RLHF_OK;
     };
     while (!c->waiting.empty() || !c->active.empty()) {
+        if (c->sd_part) {
+            // share the chip only while scoring work is actually in flight
+            const bool scoring = c->score_used && hipEventQuery(c->ev_score_last) == hipErrorNotReady;
+            rc = switch_stream(c, &c->sd, scoring ? c->sd_part : c->sd_full, c->ev_sw_d);
+            if (rc) return rc;
+        }
         if (timing && n_steps < o->trace_cap) {
             while ((int)c->step_events.size() < 2 * (n_steps + 1)) {
                 hipEvent_t e;
@@ -1172,10 +1207,12 @@ extern "C" int rlhf_run_stage(rlhf_ctx* c, const rlhf_stage_opts* o, rlhf_stage_
         }
     }
     HIPCK(c, hipEventRecord(c->ev_d1, c->sd));
+    if ((rc = switch_stream(c, &c->sd, c->sd_full, c->ev_sw_d))) return rc;
     rc = run_new_batches(form_batches(c, o->score_chunk_tokens));   // generation is over: flush
     if (rc) return rc;
     if (c->score_used) HIPCK(c, hipEventRecord(c->ev_s1, c->ss));
     else HIPCK(c, hipEventRecord(c->ev_d1, c->sd));                  // serial scoring ran on the decode stream
+    if ((rc = switch_stream(c, &c->ss, c->ss_full, c->ev_sw_s))) return rc;
     rc = rlhf_sync(c);
     if (rc) return rc;
     const auto t1 = std::chrono::steady_clock::now();

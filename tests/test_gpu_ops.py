@@ -146,7 +146,7 @@ def test_varlen_attention(dtype, Hq, Hkv, hd):
     np.testing.assert_allclose(out.double().cpu().numpy().reshape(T, Hq, hd), want, rtol=0, atol=tol)
 
 
-@pytest.mark.parametrize("variant", [5, 6, 7, 8, 9, 10, 11, 12])
+@pytest.mark.parametrize("variant", [5, 6, 7])
 @pytest.mark.parametrize("half_act", [False, True])
 def test_gemm_compute_bound_tilings(variant, half_act):
     """Every large-M tiling (XCD-aware tile order, ragged M/N/K edges, more tiles than one

@@ -211,3 +211,15 @@ def test_gae_single_matmul_matches_recursion(which, tiny_ref, gpt2s_ref):
         np.testing.assert_allclose(got_r, want_r, rtol=0, atol=2e-5)
     else:                        # bf16 model: the inputs carry the activation rounding of the stage
         assert H.rel_err(got_a, want_a) <= 1e-2 and H.rel_err(got_r, want_r) <= 1e-2
+
+
+def test_cu_partition_gives_identical_results(gpt2s_ref):
+    """Splitting the chip between the two streams while scoring is in flight changes where
+    kernels run, not what they compute."""
+    cfg, ref = gpt2s_ref
+    a = H.run_gpu_stage(cfg, ref, fused=True, R_t=7, chunk_tokens=300)
+    b = H.run_gpu_stage(cfg, ref, fused=True, R_t=7, chunk_tokens=300, corun_decode_cus=128)
+    H.compare_stage(cfg, ref, b)
+    for k in ("tokens", "lp_actor", "lp_ref", "values", "reward", "lp_actor_rescored"):
+        np.testing.assert_array_equal(a[k], b[k])
+    assert a["snapshot"]["batches"] == b["snapshot"]["batches"]
