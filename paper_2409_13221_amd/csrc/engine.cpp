@@ -620,6 +620,11 @@ extern "C" int rlhf_submit(rlhf_ctx* c, int32_t n, const int32_t* prompt_tokens,
         if (s.has_forced_len) c->h_forced[(size_t)i * mc + s.target - 1] = c->ec.eos_id;
     }
     if (n) HIPCK(c, hipMemcpy(c->d_tokens, tok.data(), tok.size() * sizeof(int), hipMemcpyHostToDevice));
+    // results of roles that are never scored read back as NaN (all-ones bit pattern), not as
+    // leftovers of an earlier stage
+    for (float* r : {c->d_lp_actor, c->d_lp_rescored, c->d_lp_ref, c->d_values})
+        HIPCK(c, hipMemset(r, 0xFF, (size_t)c->ec.max_samples * mc * 4));
+    HIPCK(c, hipMemset(c->d_reward, 0xFF, (size_t)c->ec.max_samples * 4));
     c->waiting.clear();
     for (int i = 0; i < n; ++i) c->waiting.push_back(i);
     c->active.clear();

@@ -39,7 +39,8 @@ template <> struct Mfma<true> {
     }
 };
 
-// Tile index of a workgroup.  Few-row launches (XCD == false) walk the N tiles in order.
+// Tile index of a workgroup.  Few-row launches (XCD == false) walk the N tiles in order, the
+// row tiles of a column tile next to each other so that its weights are fetched once.
 // Compute-bound launches (XCD == true): tiles are numbered in panels of kGroupM tile rows,
 // column by column inside a panel, and each of the 8 XCDs (workgroup id modulo 8, the order in
 // which the dispatcher deals workgroups to XCDs) walks its own contiguous eighth of that
@@ -49,9 +50,9 @@ template <> struct Mfma<true> {
 constexpr int kGroupM = 8;
 template <bool XCD>
 __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
-    if (!XCD) {
-        tm = bid / tiles_n;
-        tn = bid - tm * tiles_n;
+    if (!XCD) {           // the (at most two) row tiles of one column tile run side by side
+        tn = bid / tiles_m;
+        tm = bid - tn * tiles_m;
         return true;
     }
     const int total = tiles_m * tiles_n;

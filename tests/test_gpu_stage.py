@@ -223,3 +223,38 @@ def test_cu_partition_gives_identical_results(gpt2s_ref):
     for k in ("tokens", "lp_actor", "lp_ref", "values", "reward", "lp_actor_rescored"):
         np.testing.assert_array_equal(a[k], b[k])
     assert a["snapshot"]["batches"] == b["snapshot"]["batches"]
+
+
+def test_degenerate_workloads(tiny_ref):
+    """Empty batch, a single one-token sample (it ends at its prefill), role subsets, and a
+    context reused for a second stage."""
+    cfg, ref = tiny_ref
+    import paper_2409_13221_amd as R
+    with H.GpuStage(cfg, ref) as g:
+        # nothing submitted: a stage over zero samples is zero steps
+        R.rlhf_submit(g.ctx, np.zeros(0, np.int32), np.zeros(1, np.int64), np.zeros(0, np.int32))
+        st, _ = R.rlhf_run_stage(g.ctx, True, 1, 64, H.ALL_ROLES)
+        assert (st.n_steps, st.n_batches, st.generated_tokens) == (0, 0, 0)
+        assert R.rlhf_get_results(g.ctx, 0, 0)["tokens"].size == 0
+        # one sample of length 1: prefill emits the termination token, no decode step follows
+        p0 = ref["prompts"][0]
+        R.rlhf_submit(g.ctx, np.array(p0, np.int32), np.array([0, len(p0)], np.int64), np.array([1], np.int32),
+                      np.array([1], np.int32))
+        info = R.rlhf_generate_step(g.ctx)
+        assert (info.n_admitted, info.n_decoded) == (1, 0)
+        assert R.rlhf_retire(g.ctx, 1).tolist() == [0]
+        R.rlhf_score(g.ctx, [0], 0b0110, True)              # Reference and Critic only
+        out = R.rlhf_get_results(g.ctx, 1, 1)
+        assert out["tokens"].tolist() == [cfg.eos_id] and out["gen_len"].tolist() == [1]
+        assert np.isfinite(out["lp_actor"]).all() and np.isfinite(out["lp_ref"]).all() and np.isfinite(out["values"]).all()
+        assert np.isnan(out["reward"]).all() and np.isnan(out["lp_actor_rescored"]).all()   # never scored
+        # the same context runs the full workload afterwards, twice, with identical results
+        g.submit(ref["forced"])
+        R.rlhf_run_stage(g.ctx, True, 9, 128, H.ALL_ROLES)
+        a = g.results()
+        g.submit(ref["forced"])
+        R.rlhf_run_stage(g.ctx, True, 9, 128, H.ALL_ROLES)
+        b = g.results()
+    H.compare_stage(cfg, ref, a)
+    for k in ("tokens", "lp_actor", "lp_ref", "values", "reward"):
+        np.testing.assert_array_equal(a[k], b[k])
