@@ -218,7 +218,7 @@ def bs_curve(cfg, args):
     P, steps = args.bs_ctx, 24
     page_b = m.n_layers * 2 * m.n_kv_heads * cfg.page_tokens * m.head_dim * m.elem_bytes()
     out = []
-    for B in (1, 2, 4, 8, 16, 32, 64, 128, 256):
+    for B in [int(b) for b in args.bs_list.split(",")]:
         pages = B * -(-(P + steps + 2) // cfg.page_tokens)
         ec = R.rlhf_engine_cfg(cfg.page_tokens, pages * page_b, B, P + steps + 2, B, max(8192, P + steps + 2),
                                cfg.eos_id, 0, 0, 0, None, None)
@@ -261,6 +261,7 @@ def main():
                     help="time the serial generate-then-score plan instead (clean per-kernel figures)")
     ap.add_argument("--rt_sweep", action="store_true", help="fused stage time vs the trigger R_t")
     ap.add_argument("--bs_curve", action="store_true", help="decode step latency vs batch size (BS_max)")
+    ap.add_argument("--bs_list", default="1,2,4,8,16,32,64,128,256", help="batch sizes of --bs_curve")
     ap.add_argument("--bs_ctx", type=int, default=512)
     ap.add_argument("--micro", action="store_true", help="run the kernel-level cases instead of the stage")
     ap.add_argument("--micro_reps", type=int, default=5)
