@@ -21,6 +21,15 @@ rules below are this build's reading, stated so that every integer is determined
   of length L costs one prefill and L-1 decode inputs; its last token is never fed back.
 * retire(): scan slots in order; a sample whose generated length equals its target
   leaves; its pages go back in reverse page-table order; survivors keep their order.
+* migrate(ids): the second migration mechanism of Section 4.2 ("Migration mechanism"): an
+  unfinished sample's KV cache is discarded and only its tokens travel; the receiver reruns
+  the prefill phase over prompt + tokens generated so far and goes on decoding.  On one
+  instance sender and receiver coincide: the listed active samples give their pages back
+  (each in reverse page-table order, samples in the order listed), release their
+  reservation, leave the active array (survivors keep their order) and re-enter the waiting
+  queue, at its head in the order listed (or at its tail).  When re-admitted, a sample with
+  g tokens generated rebuilds positions 0 .. P+g-2 (everything but its newest token, which
+  was never fed), emits nothing, and feeds that newest token in the same step's decode.
 * Scoring batches: after each step's retire, if scoring is enabled (fused mode and
   remaining = waiting + active < R_t, or generation is over) the un-scored part of the
   retired FIFO is cut, from its head, into consecutive batches each reaching at least
@@ -84,10 +93,15 @@ class SchedulerModel:
             i = self.waiting.pop(0)
             self.reserved += self.reserve[i]
             newcomers.append(i)
-        for i in newcomers:                          # prefill: prompt positions, y_1
-            for _ in range(self.P[i]):
+        n_pre = 0
+        for i in newcomers:
+            # first admission: prompt positions, then y_1.  After a migration: prompt and all
+            # generated tokens but the newest are rebuilt, nothing is emitted.
+            rebuilt = self.P[i] + max(self.gen_len[i] - 1, 0)
+            for _ in range(rebuilt):
                 self._write_position(i)
-            self.gen_len[i] = 1
+            n_pre += rebuilt
+            self.gen_len[i] = max(self.gen_len[i], 1)
             self.admit_step[i] = self.step
             self.active.append(i)
         n_dec = 0
@@ -96,8 +110,7 @@ class SchedulerModel:
                 self._write_position(i)
                 self.gen_len[i] += 1
                 n_dec += 1
-        info = StepInfo(self.step, len(newcomers), sum(self.P[i] for i in newcomers), n_dec,
-                        len(self.active))
+        info = StepInfo(self.step, len(newcomers), n_pre, n_dec, len(self.active))
         self.step += 1
         return info
 
@@ -115,6 +128,22 @@ class SchedulerModel:
                 keep.append(i)
         self.active = keep
         return out
+
+    def migrate(self, ids: Sequence[int], to_back: bool = False) -> None:
+        ids = [int(i) for i in ids]
+        if len(set(ids)) != len(ids):
+            raise ValueError("duplicate id")
+        for i in ids:
+            if i not in self.active or self.gen_len[i] >= self.target[i]:
+                raise ValueError(f"sample {i} is not an unfinished active sample")
+        for i in ids:
+            for pg in reversed(self.pages[i]):
+                self.free.append(pg)
+            self.pages[i] = []
+            self.ctx[i] = 0
+            self.reserved -= self.reserve[i]
+        self.active = [i for i in self.active if i not in ids]
+        self.waiting = self.waiting + ids if to_back else ids + self.waiting
 
     def generation_done(self) -> bool:
         return not self.waiting and not self.active

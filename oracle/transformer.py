@@ -244,10 +244,16 @@ def greedy_generate(actor: Model, prompt: Sequence[int], out_len: int, eos_id: i
 
 def greedy_generate_cached(actor: Model, prompts: List[Sequence[int]], out_lens: Sequence[int],
                            eos_id: int, forced: Optional[List[Optional[Sequence[int]]]] = None,
-                           stop_at_eos: bool = False) -> List[Generated]:
+                           stop_at_eos: bool = False,
+                           migrate_after: Optional[dict] = None) -> List[Generated]:
     """The same results by prefill + KV-cached decoding steps, all samples advanced in
     lock step (sample i drops out after out_lens[i] tokens).  Equal to `greedy_generate`
-    per sample; this is the variant that is affordable beyond toy sizes."""
+    per sample; this is the variant that is affordable beyond toy sizes.
+
+    migrate_after = {j: [ids]}: after output index j, the listed unfinished samples are
+    migrated by the second mechanism of Section 4.2 ("Migration mechanism"): their KV cache
+    is discarded, only their tokens are kept, and the cache is regenerated by rerunning the
+    prefill over prompt + generated tokens before generation goes on."""
     n = len(prompts)
     forced = forced if forced is not None else [None] * n
     caches = [actor.new_cache() for _ in range(n)]
@@ -266,6 +272,10 @@ def greedy_generate_cached(actor: Model, prompts: List[Sequence[int]], out_lens:
             feed[i] = [y]
             if j < out_lens[i] and not (stop_at_eos and y == eos_id):
                 nxt.append(i)
+        for i in (migrate_after or {}).get(j, []):
+            if i in nxt:
+                caches[i] = actor.new_cache()
+                feed[i] = [int(t) for t in prompts[i]] + [int(t) for t in rec[i][0]]
         live = nxt
         j += 1
     return [Generated(np.array(t, np.int32), np.array(lp, actor.dtype),

@@ -54,13 +54,45 @@ def test_hand_worked_batches(fused, R_t, chunk, want, want_steps):
     assert [len(t[2]) for t in trace].count(0) == 4 - len(set(want_steps))
 
 
-def _check_invariants(m: SchedulerModel):
+@pytest.mark.parametrize("to_back", [False, True])
+def test_hand_worked_migration(to_back):
+    """Re-prefill migration (Section 4.2, second mechanism) worked by hand on the same three
+    samples: after step 0 sample 0 (5 prompt tokens, 2 generated, pages 0 and 1) is migrated."""
+    m = _hand_model()
+    m.generate_step()
+    assert m.retire() == [1]
+    with pytest.raises(ValueError):
+        m.migrate([1])                               # retired samples cannot move
+    with pytest.raises(ValueError):
+        m.migrate([2])                               # nor waiting ones
+    m.migrate([0], to_back=to_back)
+    # its pages return in reverse table order (1, then 0), its reservation is released
+    assert m.free == [5, 4, 3, 2, 1, 0] and m.reserved == 0 and m.active == []
+    assert m.waiting == ([2, 0] if to_back else [0, 2]) and m.ctx[0] == 0 and m.gen_len[0] == 2
+    # step 1: both fit (2 + 3 <= 6).  Sample 0 rebuilds prompt + first generated token = 6
+    # positions and emits nothing; sample 2 prefills its 6 prompt tokens.  Pages are issued
+    # in admission order.  Then both decode: sample 0 feeds its second token (position 6).
+    i1 = m.generate_step()
+    assert (i1.n_admitted, i1.n_prefill_tokens, i1.n_decoded, i1.n_active) == (2, 12, 2, 2)
+    if to_back:
+        assert m.active == [2, 0] and m.pages[2] == [0, 1] and m.pages[0] == [2, 3]
+    else:
+        assert m.active == [0, 2] and m.pages[0] == [0, 1] and m.pages[2] == [2, 3]
+    assert m.ctx == [7, 4, 7] and m.gen_len == [3, 2, 2]
+    assert m.retire() == [0] and m.reserved == 3
+    assert m.generate_step().n_decoded == 1 and m.retire() == []
+    assert m.generate_step().n_decoded == 1 and m.retire() == [2]
+    assert m.retired == [1, 0, 2] and m.generation_done() and m.step == 4
+    assert sorted(m.free) == list(range(6)) and m.admit_step == [1, 0, 1]
+
+
+def _check_invariants(m: SchedulerModel, ordered: bool = True):
     owned = [p for pl in m.pages for p in pl]
     assert len(owned) == len(set(owned))                         # a page has one owner
     assert sorted(owned + m.free) == list(range(m.pool_pages))   # free + owned = pool
     for i in range(m.N):
         assert len(m.pages[i]) == (-(-m.ctx[i] // m.page) if i in m.active else 0)
-    assert m.active == sorted(m.active)                          # admission order = id order
+    assert not ordered or m.active == sorted(m.active)           # admission order = id order
     assert m.reserved == sum(m.reserve[i] for i in m.active) <= m.pool_pages
     assert len(m.active) <= m.max_active
 
@@ -99,6 +131,40 @@ def test_invariants_random(seed):
     # waiting samples are admitted in order
     adm = [m.admit_step[i] for i in range(N)]
     assert adm == sorted(adm)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_invariants_random_with_migrations(seed):
+    """Random migrations of unfinished samples: pages and reservations stay consistent, every
+    sample still ends with its own length, and a migrated sample costs exactly one more
+    prefill over what it had cached."""
+    r = np.random.default_rng(100 + seed)
+    N = int(r.integers(2, 30))
+    P = r.integers(1, 50, N)
+    L = r.integers(1, 60, N)
+    page = int(r.choice([4, 16]))
+    need = max(-(-(int(p) + int(l)) // page) for p, l in zip(P, L))
+    m = SchedulerModel(P, L, L, int(need * r.choice([1, 3])), page, max_active=int(r.choice([2, N])))
+    decoded, prefilled, extra = 0, 0, 0
+    while not m.generation_done():
+        info = m.generate_step()
+        decoded += info.n_decoded
+        prefilled += info.n_prefill_tokens
+        _check_invariants(m, ordered=False)
+        m.retire()
+        _check_invariants(m, ordered=False)
+        movable = [i for i in m.active if m.gen_len[i] < m.target[i]]
+        if movable and r.random() < 0.4:
+            ids = [int(i) for i in r.permutation(movable)[:int(r.integers(1, len(movable) + 1))]]
+            extra += sum(int(P[i]) + m.gen_len[i] - 1 for i in ids)
+            m.migrate(ids, to_back=bool(r.integers(0, 2)))
+            _check_invariants(m, ordered=False)
+            assert all(m.ctx[i] == 0 and m.pages[i] == [] for i in ids)
+        assert m.step < 100000
+    assert sorted(m.retired) == list(range(N)) and len(m.free) == m.pool_pages and m.reserved == 0
+    assert decoded == int(np.sum(L - 1)) and prefilled == int(np.sum(P)) + extra
+    for i in range(N):
+        assert m.gen_len[i] == L[i] and m.ctx[i] == P[i] + L[i] - 1
 
 
 def test_oversized_sample_is_rejected():

@@ -261,6 +261,21 @@ def test_cached_decode_equals_full_recompute():
         np.testing.assert_allclose(a.margin, b.margin, atol=1e-12)
 
 
+def test_reprefill_migration_changes_nothing():
+    """Section 4.2, second migration mechanism: discarding a sample's KV cache and rebuilding it
+    by a prefill over prompt + generated tokens leaves tokens and log-probs as they were."""
+    model, _, s = rand_model(13, n_layers=2)
+    r = np.random.default_rng(4)
+    prompts = [r.integers(3, s.vocab, n).tolist() for n in (6, 3, 8)]
+    lens = [9, 5, 2]
+    plain = T.greedy_generate_cached(model, prompts, lens, eos_id=2)
+    moved = T.greedy_generate_cached(model, prompts, lens, eos_id=2, migrate_after={1: [0, 2], 3: [1, 0], 4: [1]})
+    for a, b in zip(plain, moved):
+        np.testing.assert_array_equal(a.tokens, b.tokens)
+        np.testing.assert_allclose(a.logprob, b.logprob, atol=1e-12)
+        np.testing.assert_allclose(a.margin, b.margin, atol=1e-12)
+
+
 def test_cached_decode_equals_full_recompute_tiny_workload_fp32():
     """The same at the Tiny workload's shape in float32 (tolerance 1e-5)."""
     cfg = CONFIGS["tiny"]
