@@ -242,6 +242,50 @@ def bs_curve(cfg, args):
     print(json.dumps({"bs_curve": out, "workload": cfg.name}), flush=True)
 
 
+def migrate_probe(cfg, args):
+    """Cost of the re-prefill migration mechanism (Section 4.2, "Migration mechanism"): a sample
+    at context ctx loses its KV cache and rebuilds it by one prefill; set beside the time to move
+    the same cache as bytes (the first mechanism), at HBM copy speed and at one xGMI link."""
+    import time
+
+    import paper_2409_13221_amd as R
+    from workload import make_weights
+    m = cfg.model
+    actor = make_weights(cfg, 0, device="cuda")
+    page_b = m.n_layers * 2 * m.n_kv_heads * cfg.page_tokens * m.head_dim * m.elem_bytes()
+    out = []
+    for ctx_len in [int(c) for c in args.migrate_ctx.split(",")]:
+        P, extra = ctx_len - 8, 24
+        pages = -(-(P + extra + 2) // cfg.page_tokens)
+        ec = R.rlhf_engine_cfg(cfg.page_tokens, pages * page_b, 1, P + extra + 2, 1, max(8192, P + extra + 2),
+                               cfg.eos_id, 0, 0, 0, None, None)
+        ctx = R.rlhf_create(R.model_cfg_of(m), ec)
+        R.rlhf_load_weights(ctx, 0, actor)
+        toks = np.random.default_rng(ctx_len).integers(3, m.vocab, P).astype(np.int32)
+        lens = np.array([extra], np.int32)
+        R.rlhf_submit(ctx, toks, np.array([0, P], np.int64), lens, lens)
+
+        def step_ms():
+            R.rlhf_sync(ctx)
+            t0 = time.perf_counter()
+            R.rlhf_generate_step(ctx)
+            R.rlhf_sync(ctx)
+            return (time.perf_counter() - t0) * 1e3
+        first = step_ms()                                   # prompt prefill + one decode
+        plain = min(step_ms() for _ in range(7))            # plain decode steps; context is now ctx_len
+        R.rlhf_migrate(ctx, [0])
+        moved = step_ms()                                   # re-prefill of ctx_len tokens + one decode
+        after = step_ms()
+        kv = ctx_len * m.kv_bytes_per_token()
+        out.append({"ctx": ctx_len, "first_step_ms": round(first, 2), "decode_step_ms": round(plain, 2),
+                    "reprefill_step_ms": round(moved, 2), "reprefill_ms": round(moved - plain, 2),
+                    "decode_step_after_ms": round(after, 2), "kv_MB": round(kv / 1e6, 1),
+                    "kv_copy_ms_at_5TBps": round(kv / 5.0e9, 3), "kv_xgmi_ms_at_153GBps": round(kv / 153e6, 2)})
+        log(f"[migrate_probe] ctx {ctx_len}: re-prefill {moved - plain:.2f} ms, KV {kv / 1e6:.0f} MB")
+        R.rlhf_destroy(ctx)
+    print(json.dumps({"migrate_probe": out, "workload": cfg.name}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -261,6 +305,8 @@ def main():
                     help="time the serial generate-then-score plan instead (clean per-kernel figures)")
     ap.add_argument("--rt_sweep", action="store_true", help="fused stage time vs the trigger R_t")
     ap.add_argument("--bs_curve", action="store_true", help="decode step latency vs batch size (BS_max)")
+    ap.add_argument("--migrate_probe", action="store_true", help="cost of migration by re-prefill vs moving the KV cache")
+    ap.add_argument("--migrate_ctx", default="512,1024,2048", help="contexts of --migrate_probe")
     ap.add_argument("--bs_list", default="1,2,4,8,16,32,64,128,256", help="batch sizes of --bs_curve")
     ap.add_argument("--bs_ctx", type=int, default=512)
     ap.add_argument("--micro", action="store_true", help="run the kernel-level cases instead of the stage")
@@ -285,6 +331,9 @@ def main():
     cfg = CONFIGS[args.config]
     if args.rt_sweep:
         rt_sweep(cfg, args)
+        return
+    if args.migrate_probe:
+        migrate_probe(cfg, args)
         return
     if args.bs_curve:
         bs_curve(cfg, args)

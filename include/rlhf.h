@@ -213,6 +213,20 @@ int rlhf_generate_step(rlhf_ctx* ctx, rlhf_step_info* out);
  * capacity >= active count, may be NULL) receives them. */
 int rlhf_retire(rlhf_ctx* ctx, int32_t* retired_ids, int32_t* n_retired);
 
+/* Migration of unfinished samples by re-prefill (Section 4.2, "Migration mechanism", the
+ * second choice: the KV cache is discarded, only the sample's tokens travel, and the receiver
+ * reruns the prefill phase to regenerate the cache).  On one GPU sender and receiver are the
+ * same instance: each listed sample gives its pages back to the pool (in reverse page-table
+ * order, samples in the order listed), releases its reservation, leaves the active set
+ * (survivors keep their order) and re-enters the waiting queue, at its head in the order
+ * listed, or at its tail when to_back != 0.  When rlhf_generate_step admits it again, one
+ * packed prefill over its prompt and all generated tokens but the newest rebuilds the cache;
+ * nothing is emitted, recorded log-probs stay, and the sample takes part in that step's decode.
+ * Also usable as preemption: the pages go to whoever is admitted next.
+ * ids: host array of n distinct ids of active samples that have not reached their end;
+ * otherwise RLHF_EINVAL and nothing changes.  Host bookkeeping only, no device work. */
+int rlhf_migrate(rlhf_ctx* ctx, const int32_t* ids, int32_t n, int32_t to_back);
+
 /* Inference stage for n retired samples as one packed batch (Section 2.1): for each role in
  * role_mask one causal forward over prompt + response; REF/ACTOR give the log-prob of every
  * response token, CRITIC a value per response token, REWARD one scalar at the last token.

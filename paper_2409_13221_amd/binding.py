@@ -109,6 +109,7 @@ def lib() -> C.CDLL:
         L.rlhf_submit.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
         L.rlhf_generate_step.argtypes = [vp, C.POINTER(rlhf_step_info)]
         L.rlhf_retire.argtypes = [vp, vp, C.POINTER(i32)]
+        L.rlhf_migrate.argtypes = [vp, vp, i32, i32]
         L.rlhf_score.argtypes = [vp, i32, vp, u32, i32]
         L.rlhf_run_stage.argtypes = [vp, C.POINTER(rlhf_stage_opts), C.POINTER(rlhf_stage_stats)]
         L.rlhf_get_results.argtypes = [vp, C.POINTER(rlhf_results)]
@@ -124,7 +125,7 @@ def lib() -> C.CDLL:
         L.rlhf_op_flash_attention.argtypes = [vp] * 7 + [C.c_int] * 5 + [vp]
         L.rlhf_op_gemm_swiglu.argtypes = [C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp]
         for name in ("rlhf_create", "rlhf_load_weights", "rlhf_submit", "rlhf_generate_step", "rlhf_retire",
-                     "rlhf_score", "rlhf_run_stage", "rlhf_get_results", "rlhf_debug_snapshot", "rlhf_sync",
+                     "rlhf_migrate", "rlhf_score", "rlhf_run_stage", "rlhf_get_results", "rlhf_debug_snapshot", "rlhf_sync",
                      "rlhf_profile_begin", "rlhf_profile_end", "rlhf_compute_gae",
                      "rlhf_op_gemm_nsplit", "rlhf_op_gemm", "rlhf_op_paged_decode_attention",
                      "rlhf_op_varlen_attention", "rlhf_op_flash_attention", "rlhf_op_gemm_swiglu"):
@@ -201,6 +202,11 @@ def rlhf_retire(ctx, capacity: int) -> np.ndarray:
     n = C.c_int32()
     _check(ctx, lib().rlhf_retire(ctx, _p(ids), C.byref(n)))
     return ids[:n.value].copy()
+
+
+def rlhf_migrate(ctx, sample_ids: Sequence[int], to_back: bool = False) -> None:
+    ids = _np(sample_ids, np.int32)
+    _check(ctx, lib().rlhf_migrate(ctx, _p(ids), len(ids), int(to_back)))
 
 
 def rlhf_score(ctx, sample_ids: Sequence[int], role_mask: int, on_score_stream: bool = True) -> None:

@@ -166,6 +166,7 @@ struct rlhf_ctx {
     std::vector<int64_t> h_prompt_off;
     std::vector<int> h_forced;            // [N * max_ctx] imposed token per output index, -1 = free
     std::deque<int> waiting;
+    int64_t n_migrated = 0;
     std::vector<int> active;
     std::vector<int> free_list;
     int reserved = 0;
@@ -636,6 +637,7 @@ extern "C" int rlhf_submit(rlhf_ctx* c, int32_t n, const int32_t* prompt_tokens,
     c->batch_offsets.assign(1, 0);
     c->batch_step.clear();
     c->step = 0;
+    c->n_migrated = 0;
     c->score_used = false;
     c->acc_weight_bytes = c->acc_kv_bytes = c->acc_prefill_tokens = 0;
     return RLHF_OK;
@@ -707,20 +709,27 @@ void fill_tiles(const std::vector<int>& lens, int* dst) {
     }
 }
 
-// Algorithmic cost of one layer's packed causal attention over the current lengths of `ids`.
-void batch_attn_cost(const rlhf_ctx* c, const std::vector<int>& ids, int T, PassMeta* pm) {
+// Algorithmic cost of one layer's packed causal attention over sequences of the given lengths.
+void batch_attn_cost(const rlhf_ctx* c, const std::vector<int>& lens, int T, PassMeta* pm) {
     const double qd = (double)c->mc.n_q_heads * c->mc.head_dim, kvd = (double)c->mc.n_kv_heads * c->mc.head_dim;
     double pairs = 0;
-    for (int i : ids) {
-        const Sample& s = c->smp[i];
-        const double t = s.gen_len > 0 && s.ctx >= s.P ? s.P + s.gen_len : s.P;   // scoring vs prefill
+    for (int L : lens) {
+        const double t = L;
         pairs += t * (t + 1) / 2;
     }
     pm->attn_flops = 4.0 * qd * pairs;
     pm->attn_bytes = (double)T * (2 * qd + 2 * kvd) * c->esz;
 }
 
-// Prefill of newly admitted samples [group], whose prompts total `T` rows <= max_batch_tokens.
+// Rows a sample needs when it is (re-)admitted: its prompt, plus, after a migration (Section
+// 4.2, "Migration mechanism", second choice: only the tokens travel and the KV cache is
+// regenerated by rerunning the prefill), every generated token but the newest, which the same
+// step's decode feeds.
+int prefill_rows(const Sample& s) { return s.P + std::max(s.gen_len - 1, 0); }
+
+// Prefill of newly admitted samples [group], whose rows total `T` <= max_batch_tokens.  A
+// first-time sample gets its first output token from the last prompt row; a migrated one emits
+// nothing.
 int prefill_group(rlhf_ctx* c, const std::vector<int>& group, int T) {
     const int mc = c->ec.max_ctx, pt = c->ec.page_tokens, n = (int)group.size();
     int* hm;
@@ -735,13 +744,14 @@ int prefill_group(rlhf_ctx* c, const std::vector<int>& group, int T) {
     int* tok_dst = forced + n;
     int* lp_dst = tok_dst + n;
     int* upd = lp_dst + n;
-    std::vector<int> upd_idx, upd_val;
-    int row = 0;
+    std::vector<int> upd_idx, upd_val, lens;
+    int row = 0, n_sel = 0;
     for (int gi = 0; gi < n; ++gi) {
         const int i = group[gi];
         Sample& s = c->smp[i];
-        const int start = row;
-        for (int p = 0; p < s.P; ++p, ++row) {
+        const int start = row, rows_i = prefill_rows(s);
+        lens.push_back(rows_i);
+        for (int p = 0; p < rows_i; ++p, ++row) {
             if (p % pt == 0) {
                 const int pg = take_page(c, s);
                 upd_idx.push_back(i * c->max_pages + p / pt);
@@ -752,19 +762,20 @@ int prefill_group(rlhf_ctx* c, const std::vector<int>& group, int T) {
             row_start[row] = start;
             kv_dst[row] = s.pages[p / pt] * pt + p % pt;
         }
-        s.ctx = s.P;
-        s.gen_len = 1;
+        s.ctx = rows_i;
         s.admit_step = c->step;
-        sel[gi] = row - 1;
-        forced[gi] = forced_at(c, i, 1);
-        tok_dst[gi] = i * mc + s.P;
-        lp_dst[gi] = i * mc + 0;
+        if (s.gen_len == 0) {
+            s.gen_len = 1;
+            sel[n_sel] = row - 1;
+            forced[n_sel] = forced_at(c, i, 1);
+            tok_dst[n_sel] = i * mc + s.P;
+            lp_dst[n_sel] = i * mc + 0;
+            ++n_sel;
+        }
     }
     const int U = (int)upd_idx.size();
     std::copy(upd_idx.begin(), upd_idx.end(), upd);
     std::copy(upd_val.begin(), upd_val.end(), upd + U);
-    std::vector<int> lens;
-    for (int i : group) lens.push_back(c->smp[i].P);
     const int n_tiles = count_tiles(lens);
     const size_t tiles_off = (size_t)4 * T + 4 * n + 2 * U;
     const size_t n_ints = tiles_off + 3 * (size_t)n_tiles;
@@ -783,22 +794,24 @@ int prefill_group(rlhf_ctx* c, const std::vector<int>& group, int T) {
     pm.tile_q0 = dm_ + tiles_off + n_tiles;
     pm.tile_len = dm_ + tiles_off + 2 * n_tiles;
     pm.n_tiles = n_tiles;
-    batch_attn_cost(c, group, T, &pm);
+    batch_attn_cost(c, lens, T, &pm);
     const rlhf_weights& w = c->roles[RLHF_ACTOR].w;
     Workspace& ws = c->ws_pre;
     int pns;
     size_t pstride;
     int rc = forward_layers(c, c->sd, ws, w, T, pm, kModeBatch, 1, &pns, &pstride);
     if (rc) return rc;
-    HIPCK(c, launch_rmsnorm(c->sd, act_type(c, true), ws.h, ws.part, pns, pstride, dm_ + 4 * T, w.g_final, ws.xsel, n,
-                            c->mc.d_model, c->mc.rms_eps));
-    HeadPlan hp;
-    hp.n_sel = n;
-    hp.forced = dm_ + 4 * T + n;
-    hp.tok_dst = dm_ + 4 * T + 2 * n;
-    hp.lp_dst = dm_ + 4 * T + 3 * n;
-    rc = lm_head_chunks(c, c->sd, ws, w, hp, true);
-    if (rc) return rc;
+    if (n_sel > 0) {
+        HIPCK(c, launch_rmsnorm(c->sd, act_type(c, true), ws.h, ws.part, pns, pstride, dm_ + 4 * T, w.g_final, ws.xsel,
+                                n_sel, c->mc.d_model, c->mc.rms_eps));
+        HeadPlan hp;
+        hp.n_sel = n_sel;
+        hp.forced = dm_ + 4 * T + n;
+        hp.tok_dst = dm_ + 4 * T + 2 * n;
+        hp.lp_dst = dm_ + 4 * T + 3 * n;
+        rc = lm_head_chunks(c, c->sd, ws, w, hp, true);
+        if (rc) return rc;
+    }
     c->acc_prefill_tokens += T;
     return RLHF_OK;
 }
@@ -919,16 +932,18 @@ extern "C" int rlhf_generate_step(rlhf_ctx* c, rlhf_step_info* out) {
         std::vector<int> group;
         int T = 0;
         size_t g1 = g0;
-        while (g1 < newcomers.size() && T + c->smp[newcomers[g1]].P <= c->ec.max_batch_tokens) {
-            T += c->smp[newcomers[g1]].P;
+        std::vector<int> fresh;
+        while (g1 < newcomers.size() && T + prefill_rows(c->smp[newcomers[g1]]) <= c->ec.max_batch_tokens) {
+            T += prefill_rows(c->smp[newcomers[g1]]);
             group.push_back(newcomers[g1]);
+            if (c->smp[newcomers[g1]].gen_len == 0) fresh.push_back(newcomers[g1]);
             ++g1;
         }
         int rc = prefill_group(c, group, T);
         if (rc) return rc;
         if (c->ec.stop_on_eos) {
             // picked tokens of a prefill are not in d_picked; read them from the token buffer
-            for (int i : group) {
+            for (int i : fresh) {
                 int y;
                 HIPCK(c, hipMemcpyAsync(&y, c->d_tokens + (size_t)i * c->ec.max_ctx + c->smp[i].P, sizeof(int),
                                         hipMemcpyDeviceToHost, c->sd));
@@ -981,6 +996,39 @@ extern "C" int rlhf_retire(rlhf_ctx* c, int32_t* retired_ids, int32_t* n_retired
     }
     c->active.swap(keep);
     if (n_retired) *n_retired = n;
+    return RLHF_OK;
+}
+
+extern "C" int rlhf_migrate(rlhf_ctx* c, const int32_t* ids, int32_t n, int32_t to_back) {
+    if (!c || n < 0 || (n > 0 && !ids)) return RLHF_EINVAL;
+    std::vector<char> listed(c->smp.size(), 0);
+    for (int k = 0; k < n; ++k) {
+        const int i = ids[k];
+        if (i < 0 || i >= (int)c->smp.size()) return c->fail(RLHF_EINVAL, "rlhf_migrate: id %d out of range", i);
+        if (listed[i]) return c->fail(RLHF_EINVAL, "rlhf_migrate: id %d listed twice", i);
+        listed[i] = 1;
+        const bool is_active = std::find(c->active.begin(), c->active.end(), i) != c->active.end();
+        if (!is_active || sample_done(c->smp[i]))
+            return c->fail(RLHF_EINVAL, "rlhf_migrate: sample %d is not an unfinished active sample", i);
+    }
+    // work already enqueued on the decode stream that reads these pages runs before whatever is
+    // enqueued later and writes them again: stream order is the only ordering needed
+    for (int k = 0; k < n; ++k) {
+        Sample& s = c->smp[ids[k]];
+        for (auto it = s.pages.rbegin(); it != s.pages.rend(); ++it) c->free_list.push_back(*it);
+        s.pages.clear();
+        s.ctx = 0;
+        c->reserved -= s.reserve;
+    }
+    std::vector<int> keep;
+    for (int i : c->active)
+        if (!listed[i]) keep.push_back(i);
+    c->active.swap(keep);
+    if (to_back)
+        for (int k = 0; k < n; ++k) c->waiting.push_back(ids[k]);
+    else
+        for (int k = n - 1; k >= 0; --k) c->waiting.push_front(ids[k]);
+    c->n_migrated += n;
     return RLHF_OK;
 }
 
@@ -1041,7 +1089,7 @@ int score_pass(rlhf_ctx* c, hipStream_t st, MetaRing& meta, Workspace& ws, const
     pm.tile_q0 = dmeta + tiles_off + n_tiles;
     pm.tile_len = dmeta + tiles_off + 2 * n_tiles;
     pm.n_tiles = n_tiles;
-    batch_attn_cost(c, std::vector<int>(ids, ids + n), T, &pm);
+    batch_attn_cost(c, lens, T, &pm);
     const rlhf_weights& w = c->roles[role].w;
     int pns;
     size_t pstride;

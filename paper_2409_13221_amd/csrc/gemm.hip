@@ -314,25 +314,33 @@ constexpr TileCfg kCfgs[] = {
 };
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
-int pick_variant(int M) {
+// Few rows: the smallest row tile that holds them, weights streamed once, K split.  Many rows:
+// the 256 x 256 tiling, unless its tiles would leave much of the chip idle (a prefill of a few
+// hundred tokens, a narrow N): then 128 x 128 tiles with K split, which trades some efficiency
+// per workgroup for having all compute units busy.
+int pick_variant(int M, int N) {
     if (M <= 16) return 1;
     if (M <= 32) return 2;
     if (M <= 64) return 3;
     if (M <= 256) return 4;
-    return M >= 512 ? 7 : 5;
+    const long tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
+    const long rounds = (tiles + 255) / 256;            // one 256 x 256 tile per compute unit at a time
+    return tiles * 10 >= rounds * 256 * 6 ? 7 : 4;      // at least 60 % of the tile slots filled
 }
-constexpr int kTargetBlocks = 1024;  // about four workgroups per compute unit
+constexpr int kTargetBlocks = 1024;      // about four workgroups per compute unit (few rows)
+constexpr int kTargetBlocksTall = 512;   // two of the 128 x 128 workgroups per compute unit
 }  // namespace
 
 int gemm_choose_nsplit(int wdt, int M, int N, int K, int max_split) {
     int tm, tn, kgran;
     if (wdt == kBF16) {
-        const TileCfg& c = kCfgs[pick_variant(M)];
+        const TileCfg& c = kCfgs[pick_variant(M, N)];
         if (c.xcd) return 1;
         tm = c.tm; tn = c.tn; kgran = c.tk;
     } else { tm = 64; tn = 64; kgran = 16; }
     const long tiles = (long)((M + tm - 1) / tm) * ((N + tn - 1) / tn);
-    int ns = (int)((kTargetBlocks + tiles - 1) / tiles);
+    const int target = M > 256 ? kTargetBlocksTall : kTargetBlocks;
+    int ns = (int)((target + tiles - 1) / tiles);
     const int kmax = K / (4 * kgran) > 0 ? K / (4 * kgran) : 1;   // keep >= 4 K tiles per split
     if (ns > kmax) ns = kmax;
     if (ns > max_split) ns = max_split;
@@ -401,7 +409,7 @@ hipError_t launch_gemm(hipStream_t st, int wdt, int adt, const void* A, const vo
         if (adt != kBF16 && adt != kF16) return hipErrorInvalidValue;
         if (K % 8 || variant < 0 || variant >= kNumCfgs) return hipErrorInvalidValue;
         if (variant == 0) {
-            variant = pick_variant(M);
+            variant = pick_variant(M, N);
             if (kCfgs[variant].xcd && nsplit != 1) variant = 4;   // a caller-imposed split of a tall GEMM
         }
         if (kCfgs[variant].xcd && nsplit != 1) return hipErrorInvalidValue;

@@ -66,6 +66,46 @@ def test_tiny_bookkeeping_is_bit_exact_step_by_step(tiny_ref, pool_factor, max_a
     H.compare_stage(cfg, ref, got)
 
 
+@pytest.mark.parametrize("to_back,pool_factor", [(False, 1.0), (True, 1.0), (False, 0.4)])
+def test_tiny_migration_by_reprefill(tiny_ref, to_back, pool_factor):
+    """Section 4.2, second migration mechanism: stragglers lose their KV cache and get it back by
+    a prefill over prompt + generated tokens.  Bookkeeping follows the scheduler model bit for bit
+    and tokens, log-probs, values and rewards are those of an undisturbed run."""
+    cfg, ref = tiny_ref
+    with H.GpuStage(cfg, ref) as probe:
+        need = probe.pool_pages
+        biggest = int(np.ceil((probe.plen + probe.max_new) / cfg.page_tokens).max())
+    pool = max(biggest, int(need * pool_factor))
+    r = np.random.default_rng(5)
+    with H.GpuStage(cfg, ref, pool_pages=pool) as g:
+        g.submit(ref["forced"])
+        model = H.scheduler_model_for(g)
+        moved = 0
+        while not model.generation_done():
+            info = g.R.rlhf_generate_step(g.ctx)
+            want = model.generate_step()
+            assert (info.step, info.n_admitted, info.n_prefill_tokens, info.n_decoded, info.n_active) == \
+                   (want.step, want.n_admitted, want.n_prefill_tokens, want.n_decoded, want.n_active)
+            assert g.R.rlhf_retire(g.ctx, g.n).tolist() == model.retire()
+            movable = [i for i in model.active if model.gen_len[i] < model.target[i]]
+            if movable and info.step % 3 == 1:
+                ids = [int(i) for i in r.permutation(movable)[:max(1, len(movable) // 2)]]
+                g.R.rlhf_migrate(g.ctx, ids, to_back)
+                model.migrate(ids, to_back)
+                moved += len(ids)
+            snap, ms = g.snapshot(), model.snapshot()
+            for k in ("step", "n_waiting", "active", "ctx", "gen_len", "pages", "free", "reserved", "retired"):
+                assert snap[k] == ms[k], k
+        assert moved >= 3
+        # what cannot move: retired, waiting or unknown samples, duplicates
+        for bad in ([model.retired[0]], [g.n], [-1]):
+            with pytest.raises(g.R.RlhfError):
+                g.R.rlhf_migrate(g.ctx, bad)
+        g.R.rlhf_score(g.ctx, model.retired, H.ALL_ROLES, True)
+        got = g.results()
+    H.compare_stage(cfg, ref, got)
+
+
 @pytest.mark.parametrize("fused,R_t,chunk", [(True, 9, 64), (True, 3, 64), (False, 0, 100), (True, 9, 1)])
 def test_tiny_run_stage_batches_match_scheduler_model(tiny_ref, fused, R_t, chunk):
     cfg, ref = tiny_ref
@@ -136,6 +176,32 @@ def test_gpt2s_bf16_stage_matches_oracle(gpt2s_ref):
     seq = H.run_gpu_stage(cfg, ref, fused=False, R_t=0, chunk_tokens=600)
     H.compare_stage(cfg, ref, seq)
     np.testing.assert_array_equal(got["tokens"], seq["tokens"])
+
+
+def test_gpt2s_bf16_migration_by_reprefill(gpt2s_ref):
+    """The same migration on the bf16 path, where the rebuilt cache comes from the MFMA prefill
+    kernels instead of the decode kernels: results stay within the stage's tolerances, and
+    tokens are those of the undisturbed run except where the oracle itself is within MARGIN of
+    a tie (those positions are teacher-forced in both runs)."""
+    cfg, ref = gpt2s_ref
+    plain = H.run_gpu_stage(cfg, ref, fused=True, R_t=7, chunk_tokens=600)
+    with H.GpuStage(cfg, ref) as g:
+        g.submit(ref["forced"])
+        model = H.scheduler_model_for(g)
+        while not model.generation_done():
+            info = g.R.rlhf_generate_step(g.ctx)
+            model.generate_step()
+            assert g.R.rlhf_retire(g.ctx, g.n).tolist() == model.retire()
+            movable = [i for i in model.active if model.gen_len[i] < model.target[i]]
+            if movable and info.step in (4, 9, 10):
+                ids = movable[::2]
+                g.R.rlhf_migrate(g.ctx, ids, info.step == 9)
+                model.migrate(ids, info.step == 9)
+        g.R.rlhf_score(g.ctx, model.retired, H.ALL_ROLES, True)
+        got = g.results()
+    print("gpt2s migrated worst errors:", H.compare_stage(cfg, ref, got))
+    np.testing.assert_array_equal(got["tokens"], plain["tokens"])
+    assert np.abs(got["lp_actor"] - plain["lp_actor"]).max() <= 2 * H.LP_TOL["bf16"]
 
 
 def test_gqa_bf16_small_model_matches_oracle():
