@@ -45,7 +45,17 @@ def build_stage(cfg, args):
 
     m = cfg.model
     t0 = time.time()
-    weights = [make_weights(cfg, r, device="cuda") for r in range(4)]
+    if args.weights == "seeded":
+        weights = [make_weights(cfg, r, device="cuda") for r in range(4)]
+    else:
+        # same distribution from torch's own generator: for runs under a counter-collecting profiler,
+        # whose tool aborts in the integer kernels of the counter-based generator
+        from workload.generate import weight_shapes
+        torch.manual_seed(cfg.seed)
+        wdt = torch.float32 if m.dtype == "fp32" else torch.bfloat16
+        weights = [{k: (torch.ones(sh, device="cuda") if k.startswith("g_") else
+                        torch.empty(sh, device="cuda", dtype=wdt).normal_(0.0, 0.02))
+                    for k, sh in weight_shapes(m, r).items()} for r in range(4)]
     torch.cuda.synchronize()
     log(f"[bench] weights for 4 roles on device in {time.time() - t0:.1f}s")
     wl = make_workload(cfg)
@@ -139,8 +149,9 @@ def roofline_of(prof, dtype, traffic):
 def micro(args):
     """Kernel-level cases at the 7B layer shapes through the ops ABI, for rocprofv3 counter runs:
     a 1 GiB device copy (calibration of FETCH_SIZE / WRITE_SIZE), the four projections of a
-    scoring pass (M = 8192, half activations), the same four in the decode regime (M = 8), and
-    paged decode attention (32 samples x 1024 cached tokens, 32 heads x 128)."""
+    scoring pass (M = --micro_rows, half activations, SwiGLU fused into gate||up as in the stage),
+    the same four in the decode regime (M = 8), and paged decode attention (32 samples x 1024
+    cached tokens, 32 heads x 128, half)."""
     import torch
 
     import paper_2409_13221_amd as R
@@ -167,18 +178,23 @@ def micro(args):
     timed("copy_1GiB", lambda: dst.copy_(src), 2.0 * src.numel() * 4, 0)
     del src, dst
     shapes = [("qkv", 12288, 4096), ("o", 4096, 4096), ("gate_up", 22016, 4096), ("down", 4096, 11008)]
-    for M, half in ((8192, True), (8, False)):
+    for M in (args.micro_rows, 8):
         for name, N, K in shapes:
-            A = torch.randn(M, K, device=dev).to(torch.float16 if half else torch.bfloat16)
+            A = torch.randn(M, K, device=dev).to(torch.float16)
             W = (torch.randn(N, K, device=dev) * 0.02).to(torch.bfloat16)
+            if name == "gate_up" and M >= 512:       # as the stage runs it: SwiGLU in the epilogue
+                act = torch.empty(M, N // 2, device=dev, dtype=torch.float16)
+                timed(f"gemm_{name}_swiglu_M{M}", lambda: R.rlhf_op_gemm_swiglu(A, W, act),
+                      (N * K + M * K) * 2.0 + M * (N // 2) * 2.0, 2.0 * M * N * K)
+                continue
             ns = R.rlhf_op_gemm_nsplit(R.RLHF_BF16, M, N, K, 16)
             C = torch.empty(ns, M, N, device=dev)
             timed(f"gemm_{name}_M{M}", lambda: R.rlhf_op_gemm(A, W, C, ns),
                   (N * K + M * K) * 2.0 + M * N * 4.0, 2.0 * M * N * K)
     rows, ctx, Hq, hd, Ly = 32, 1024, 32, 128, 1
     n_pages = rows * ctx // 16
-    pool = torch.randn(n_pages, Ly, 2, Hq, 16, hd, device=dev).to(torch.bfloat16)
-    q = torch.randn(rows, Hq * hd, device=dev).to(torch.bfloat16)
+    pool = torch.randn(n_pages, Ly, 2, Hq, 16, hd, device=dev).to(torch.float16)
+    q = torch.randn(rows, Hq * hd, device=dev).to(torch.float16)
     pt = torch.randperm(n_pages, device=dev).to(torch.int32).reshape(rows, ctx // 16).contiguous()
     rs = torch.arange(rows, dtype=torch.int32, device=dev)
     cl = torch.full((rows,), ctx, dtype=torch.int32, device=dev)
@@ -305,6 +321,9 @@ def main():
                     help="time the serial generate-then-score plan instead (clean per-kernel figures)")
     ap.add_argument("--rt_sweep", action="store_true", help="fused stage time vs the trigger R_t")
     ap.add_argument("--bs_curve", action="store_true", help="decode step latency vs batch size (BS_max)")
+    ap.add_argument("--weights", choices=["seeded", "normal"], default="seeded",
+                    help="seeded: the workload's counter-based generator; normal: torch's (profiler runs only)")
+    ap.add_argument("--micro_rows", type=int, default=6144, help="rows of the scoring-pass cases of --micro")
     ap.add_argument("--migrate_probe", action="store_true", help="cost of migration by re-prefill vs moving the KV cache")
     ap.add_argument("--migrate_ctx", default="512,1024,2048", help="contexts of --migrate_probe")
     ap.add_argument("--bs_list", default="1,2,4,8,16,32,64,128,256", help="batch sizes of --bs_curve")
@@ -360,13 +379,18 @@ def main():
     G, S = int(st.generated_tokens), int(st.scored_tokens)
     value = (G + S) / (ms_per_step * 1e-3)
 
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath))
+    # HBM-side bytes per launch of the dominant kernel class, from the committed rocprofv3 counter summary
+    # (FETCH_SIZE and WRITE_SIZE runs, each scaled by a 1 GiB copy); null where no such run exists
     roof, est = roofline_of(prof, cfg.model.dtype, None)
-    if traffic and roof["kernel"] in traffic:
-        roof["traffic"] = traffic[roof["kernel"]]
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{cfg.name}.txt")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            f = line.split()
+            if len(f) == 4 and f[0] == roof["kernel"]:
+                roof["traffic"] = float(f[1]) + float(f[2])
+                roof["traffic_detail"] = {"fetched_bytes": float(f[1]), "written_bytes": float(f[2]),
+                                          "algorithmic_bytes": float(f[3]),
+                                          "source": "profiles/gemm_7b_layer_shapes_hbm_traffic.md"}
     kernels = {}
     for k, v in prof.items():
         if not v["sampled"]:
