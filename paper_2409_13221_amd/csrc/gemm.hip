@@ -327,8 +327,7 @@ int pick_variant(int M, int N) {
     const long rounds = (tiles + 255) / 256;            // one 256 x 256 tile per compute unit at a time
     return tiles * 10 >= rounds * 256 * 6 ? 7 : 4;      // at least 60 % of the tile slots filled
 }
-constexpr int kTargetBlocks = 1024;      // about four workgroups per compute unit (few rows)
-constexpr int kTargetBlocksTall = 512;   // two of the 128 x 128 workgroups per compute unit
+constexpr int kTargetBlocks = 1024;      // about four workgroups per compute unit (tiles of up to 64 rows)
 }  // namespace
 
 int gemm_choose_nsplit(int wdt, int M, int N, int K, int max_split) {
@@ -339,9 +338,23 @@ int gemm_choose_nsplit(int wdt, int M, int N, int K, int max_split) {
         tm = c.tm; tn = c.tn; kgran = c.tk;
     } else { tm = 64; tn = 64; kgran = 16; }
     const long tiles = (long)((M + tm - 1) / tm) * ((N + tn - 1) / tn);
-    const int target = M > 256 ? kTargetBlocksTall : kTargetBlocks;
-    int ns = (int)((target + tiles - 1) / tiles);
     const int kmax = K / (4 * kgran) > 0 ? K / (4 * kgran) : 1;   // keep >= 4 K tiles per split
+    int ns;
+    if (tm >= 128) {
+        // 128-row tiles: every split writes a float plane of M x N that the consumer reads back,
+        // which at these M is no longer small beside the weights.  Take the split that minimises
+        // (weight bytes + plane bytes) / (share of the chip in use), 384 workgroups filling it.
+        const double wbytes = 2.0 * N * K, plane = 8.0 * M * N;
+        double best = 0;
+        ns = 1;
+        for (int c = 1; c <= kmax && c <= max_split; c *= 2) {
+            const double fill = (double)(tiles * c) / 384.0;
+            const double cost = (wbytes + plane * c) / (fill < 1.0 ? fill : 1.0);
+            if (c == 1 || cost < best) { best = cost; ns = c; }
+        }
+    } else {
+        ns = (int)((kTargetBlocks + tiles - 1) / tiles);
+    }
     if (ns > kmax) ns = kmax;
     if (ns > max_split) ns = max_split;
     if (ns < 1) ns = 1;
