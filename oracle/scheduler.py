@@ -30,6 +30,15 @@ rules below are this build's reading, stated so that every integer is determined
   queue, at its head in the order listed (or at its tail).  When re-admitted, a sample with
   g tokens generated rebuilds positions 0 .. P+g-2 (everything but its newest token, which
   was never fed), emits nothing, and feeds that newest token in the same step's decode.
+* optimistic = True replaces the reservation rule (the paper only asks that an instance have
+  "sufficient memory", Section 4.2) by admission on present need plus preemption, with
+  migrate() as the preemption: the head of the queue is admitted while the pages for the rows
+  it rebuilds plus one more token fit in what is free after the newcomers before it, and,
+  unless nothing is running, one further free page is left per running sample.  Before the
+  step's decode, if the pages the decode is about to take exceed the free ones, the most
+  recently admitted unfinished samples are preempted one by one until they fit; the victims
+  return to the head of the queue in their admission order.  A single sample always fits
+  (the pool holds any one sample at its cap), so every step decodes at least one token.
 * Scoring batches: after each step's retire, if scoring is enabled (fused mode and
   remaining = waiting + active < R_t, or generation is over) the un-scored part of the
   retired FIFO is cut, from its head, into consecutive batches each reaching at least
@@ -53,7 +62,7 @@ class StepInfo:
 class SchedulerModel:
     def __init__(self, prompt_lens: Sequence[int], max_new: Sequence[int],
                  target_len: Sequence[int], pool_pages: int, page_tokens: int = 16,
-                 max_active: Optional[int] = None):
+                 max_active: Optional[int] = None, optimistic: bool = False):
         self.N = len(prompt_lens)
         self.P = [int(p) for p in prompt_lens]
         self.max_new = [int(m) for m in max_new]
@@ -62,6 +71,8 @@ class SchedulerModel:
         self.page = int(page_tokens)
         self.pool_pages = int(pool_pages)
         self.max_active = self.N if max_active is None else int(max_active)
+        self.optimistic = bool(optimistic)
+        self.n_preempted = 0
         self.reserve = [-(-(p + m) // self.page) for p, m in zip(self.P, self.max_new)]
         if any(r > self.pool_pages for r in self.reserve):
             raise MemoryError("a sample's reservation exceeds the pool")
@@ -86,13 +97,51 @@ class SchedulerModel:
             self.pages[i].append(self.free.pop())
         self.ctx[i] += 1
 
-    def generate_step(self) -> StepInfo:
+    def _rebuilt_rows(self, i: int) -> int:
+        return self.P[i] + max(self.gen_len[i] - 1, 0)
+
+    def _admit(self) -> List[int]:
         newcomers = []
-        while (self.waiting and len(self.active) + len(newcomers) < self.max_active
-               and self.reserved + self.reserve[self.waiting[0]] <= self.pool_pages):
-            i = self.waiting.pop(0)
+        if not self.optimistic:
+            while (self.waiting and len(self.active) + len(newcomers) < self.max_active
+                   and self.reserved + self.reserve[self.waiting[0]] <= self.pool_pages):
+                i = self.waiting.pop(0)
+                self.reserved += self.reserve[i]
+                newcomers.append(i)
+            return newcomers
+        free = len(self.free)
+        while self.waiting and len(self.active) + len(newcomers) < self.max_active:
+            i = self.waiting[0]
+            need = -(-(self._rebuilt_rows(i) + 1) // self.page)
+            running = len(self.active) + len(newcomers)
+            if need > free or (running > 0 and free - need < running):
+                break
+            free -= need
+            self.waiting.pop(0)
             self.reserved += self.reserve[i]
             newcomers.append(i)
+        return newcomers
+
+    def _preempt_for_decode(self) -> None:
+        victims = []
+        while True:
+            dec = [i for i in self.active if self.gen_len[i] < self.target[i]]
+            need = sum(1 for i in dec if self.ctx[i] % self.page == 0)
+            if need <= len(self.free):
+                break
+            v = dec[-1]                               # most recently admitted unfinished sample
+            for pg in reversed(self.pages[v]):
+                self.free.append(pg)
+            self.pages[v] = []
+            self.ctx[v] = 0
+            self.reserved -= self.reserve[v]
+            self.active.remove(v)
+            victims.append(v)
+        self.waiting = victims[::-1] + self.waiting
+        self.n_preempted += len(victims)
+
+    def generate_step(self) -> StepInfo:
+        newcomers = self._admit()
         n_pre = 0
         for i in newcomers:
             # first admission: prompt positions, then y_1.  After a migration: prompt and all
@@ -104,6 +153,8 @@ class SchedulerModel:
             self.gen_len[i] = max(self.gen_len[i], 1)
             self.admit_step[i] = self.step
             self.active.append(i)
+        if self.optimistic:
+            self._preempt_for_decode()
         n_dec = 0
         for i in self.active:                        # decode: feed the last token
             if self.gen_len[i] < self.target[i]:
@@ -198,4 +249,5 @@ class SchedulerModel:
             "reserved": self.reserved,
             "retired": list(self.retired),
             "batches": [list(b) for b in self.batches],
+            "n_preempted": self.n_preempted,
         }

@@ -166,7 +166,6 @@ struct rlhf_ctx {
     std::vector<int64_t> h_prompt_off;
     std::vector<int> h_forced;            // [N * max_ctx] imposed token per output index, -1 = free
     std::deque<int> waiting;
-    int64_t n_migrated = 0;
     std::vector<int> active;
     std::vector<int> free_list;
     int reserved = 0;
@@ -637,7 +636,6 @@ extern "C" int rlhf_submit(rlhf_ctx* c, int32_t n, const int32_t* prompt_tokens,
     c->batch_offsets.assign(1, 0);
     c->batch_step.clear();
     c->step = 0;
-    c->n_migrated = 0;
     c->score_used = false;
     c->acc_weight_bytes = c->acc_kv_bytes = c->acc_prefill_tokens = 0;
     return RLHF_OK;
@@ -1028,7 +1026,6 @@ extern "C" int rlhf_migrate(rlhf_ctx* c, const int32_t* ids, int32_t n, int32_t 
         for (int k = 0; k < n; ++k) c->waiting.push_back(ids[k]);
     else
         for (int k = n - 1; k >= 0; --k) c->waiting.push_front(ids[k]);
-    c->n_migrated += n;
     return RLHF_OK;
 }
 

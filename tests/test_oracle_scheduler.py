@@ -93,7 +93,8 @@ def _check_invariants(m: SchedulerModel, ordered: bool = True):
     for i in range(m.N):
         assert len(m.pages[i]) == (-(-m.ctx[i] // m.page) if i in m.active else 0)
     assert not ordered or m.active == sorted(m.active)           # admission order = id order
-    assert m.reserved == sum(m.reserve[i] for i in m.active) <= m.pool_pages
+    assert m.reserved == sum(m.reserve[i] for i in m.active)
+    assert m.optimistic or m.reserved <= m.pool_pages
     assert len(m.active) <= m.max_active
 
 
@@ -165,6 +166,78 @@ def test_invariants_random_with_migrations(seed):
     assert decoded == int(np.sum(L - 1)) and prefilled == int(np.sum(P)) + extra
     for i in range(N):
         assert m.gen_len[i] == L[i] and m.ctx[i] == P[i] + L[i] - 1
+
+
+def test_hand_worked_optimistic_admission_and_preemption():
+    """Admission on present need + preemption by re-prefill, worked by hand: page = 4 tokens, pool = 3
+    pages, two samples (P, L) = (3, 9) and (3, 6) whose cap reservations (3 pages each) would run
+    them one after the other."""
+    m = SchedulerModel([3, 3], [9, 9], [9, 6], pool_pages=3, page_tokens=4, optimistic=True)
+    # step 0: each needs ceil((3 + 1) / 4) = 1 page now; after sample 0, 2 pages are free and one
+    # must stay free per running sample: 2 - 1 >= 1, so sample 1 is admitted too.
+    i0 = m.generate_step()
+    assert (i0.n_admitted, i0.n_prefill_tokens, i0.n_decoded) == (2, 6, 2)
+    assert m.pages == [[0], [1]] and m.ctx == [4, 4] and m.free == [2]
+    # step 1: both are about to write position 4 (a new page each) and one page is free: the
+    # most recently admitted sample, 1, is preempted; its page comes back and sample 0 takes it.
+    i1 = m.generate_step()
+    assert (i1.n_admitted, i1.n_decoded, i1.n_active) == (0, 1, 1) and m.n_preempted == 1
+    assert m.waiting == [1] and m.pages == [[0, 1], []] and m.ctx == [5, 0] and m.gen_len == [3, 2]
+    assert m.free == [2]
+    # steps 2-7: sample 1 would rebuild 3 + 1 rows and decode one more: 2 pages, only 1 (then 0)
+    # free, so it waits; sample 0 takes the last page at position 8 and ends at step 7.
+    for step in range(2, 8):
+        info = m.generate_step()
+        assert (info.n_admitted, info.n_decoded) == (0, 1)
+        assert m.retire() == ([0] if step == 7 else [])
+    assert m.free == [2, 1, 0] and m.ctx[0] == 11
+    # step 8: sample 1 comes back: 4 rows rebuilt (page 0), nothing emitted, then it feeds its
+    # second token at position 4 (page 1) in the same step.
+    i8 = m.generate_step()
+    assert (i8.step, i8.n_admitted, i8.n_prefill_tokens, i8.n_decoded) == (8, 1, 4, 1)
+    assert m.pages[1] == [0, 1] and m.ctx[1] == 5 and m.gen_len[1] == 3
+    while not m.generation_done():
+        m.generate_step(); m.retire()
+    assert m.step == 12 and m.retired == [0, 1] and sorted(m.free) == [0, 1, 2]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_invariants_random_optimistic(seed):
+    """Random workloads under optimistic admission, pools from barely one sample to ample: pages
+    stay consistent, every step decodes something, everybody ends with their own length, prefill
+    work is the prompts plus exactly the rows rebuilt after preemptions, and the run is never
+    longer than under cap reservations."""
+    r = np.random.default_rng(200 + seed)
+    N = int(r.integers(2, 40))
+    P = r.integers(1, 60, N)
+    L = np.minimum(np.floor(3 * r.uniform(1e-3, 1, N) ** (-1 / 1.2)), 120).astype(int)
+    cap = np.full(N, 120)
+    page = int(r.choice([4, 16]))
+    need = max(-(-(int(p) + 120) // page) for p in P)
+    pool = int(need * r.choice([1, 1, 2, 6]))
+    ma = int(r.choice([3, N]))
+    m = SchedulerModel(P, cap, L, pool, page, max_active=ma, optimistic=True)
+    decoded = prefilled = 0
+    rebuilt = 0
+    while not m.generation_done():
+        before = {i: m.gen_len[i] for i in m.waiting}
+        info = m.generate_step()
+        decoded += info.n_decoded
+        prefilled += info.n_prefill_tokens
+        assert info.n_decoded >= 1 or all(m.gen_len[i] >= m.target[i] for i in m.active)
+        _check_invariants(m, ordered=False)
+        m.retire()
+        _check_invariants(m, ordered=False)
+        assert m.step < 200000
+    assert sorted(m.retired) == list(range(N)) and len(m.free) == pool and m.reserved == 0
+    assert decoded == int(np.sum(L - 1)) and prefilled >= int(np.sum(P))
+    assert (prefilled == int(np.sum(P))) == (m.n_preempted == 0)
+    for i in range(N):
+        assert m.gen_len[i] == L[i] and m.ctx[i] == P[i] + L[i] - 1
+    c = SchedulerModel(P, cap, L, pool, page, max_active=ma)
+    while not c.generation_done():
+        c.generate_step(); c.retire()
+    assert m.step <= c.step
 
 
 def test_oversized_sample_is_rejected():
