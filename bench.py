@@ -72,7 +72,7 @@ def build_stage(cfg, args):
     pool_pages = int(min(need_pages, max(1, (free_b - ws_est) // page_b)))
     mc = R.model_cfg_of(m)
     ec = R.rlhf_engine_cfg(cfg.page_tokens, pool_pages * page_b, n, max_ctx, min(n, args.max_active),
-                           max_batch_tokens, cfg.eos_id, 0, args.corun_decode_cus, 0, None, None)
+                           max_batch_tokens, cfg.eos_id, 0, args.corun_decode_cus, int(args.admission == "optimistic"), None, None)
     ctx = R.rlhf_create(mc, ec)
     for role, w in enumerate(weights):
         R.rlhf_load_weights(ctx, role, w)
@@ -321,6 +321,9 @@ def main():
                     help="time the serial generate-then-score plan instead (clean per-kernel figures)")
     ap.add_argument("--rt_sweep", action="store_true", help="fused stage time vs the trigger R_t")
     ap.add_argument("--bs_curve", action="store_true", help="decode step latency vs batch size (BS_max)")
+    ap.add_argument("--admission", choices=["reserve", "optimistic"], default="optimistic",
+                    help="reserve: a sample is admitted when its KV reservation at the length cap fits; "
+                         "optimistic: on present need, with preemption by re-prefill")
     ap.add_argument("--weights", choices=["seeded", "normal"], default="seeded",
                     help="seeded: the workload's counter-based generator; normal: torch's (profiler runs only)")
     ap.add_argument("--micro_rows", type=int, default=6144, help="rows of the scoring-pass cases of --micro")
@@ -436,7 +439,7 @@ def main():
            "config": {"workload": cfg.name, "n_samples": int(len(max_new)), "length_law": cfg.length_law,
                       "length_params": list(cfg.length_params), "length_cap": cfg.length_cap,
                       "plan": "sequential" if args.sequential else "fused",
-                      "corun_decode_cus": args.corun_decode_cus,
+                      "corun_decode_cus": args.corun_decode_cus, "admission": args.admission,
                       "score_chunk_tokens": args.score_chunk_tokens, "R_t": args.R_t, "role_mask": args.role_mask,
                       "page_tokens": cfg.page_tokens},
            "roofline": roof, "cpu_baseline": cpu, "fused_vs_sequential": seq, "kernels": kernels,

@@ -62,7 +62,8 @@ typedef struct rlhf_model_cfg {
 } rlhf_model_cfg;
 
 /* Engine limits.  kv_pool_bytes is the budget "C" of Section 4.2's memory constraint; a
- * sample reserves ceil((prompt + max_new) / page_tokens) pages on admission ("M"). */
+ * sample reserves ceil((prompt + max_new) / page_tokens) pages on admission ("M"), unless
+ * optimistic_admission is set. */
 typedef struct rlhf_engine_cfg {
     int32_t page_tokens;           /* tokens per KV page; must be 16                          */
     int64_t kv_pool_bytes;         /* device bytes for the paged KV pool                      */
@@ -80,7 +81,15 @@ typedef struct rlhf_engine_cfg {
                                       bandwidth-bound and the matrix-bound work do not queue
                                       behind one another; whichever side is alone uses the whole
                                       chip.  0 = no partition.  Needs a multiple of 32          */
-    int32_t reserved;              /* must be 0                                                */
+    int32_t optimistic_admission;  /* 0: a sample is admitted when its reservation at the cap fits
+                                      (never preempted).  1: admission on present need: the head
+                                      of the queue is admitted while the pages for the rows it
+                                      (re)builds plus one token fit in what is free and, unless
+                                      nothing is running, one more free page is left per running
+                                      sample; when a step's decode needs more pages than are
+                                      free, the most recently admitted unfinished samples are
+                                      preempted (rlhf_migrate to the head of the queue, in
+                                      admission order) until it fits                            */
     void* decode_stream;           /* hipStream_t to use, or NULL: the library creates one    */
     void* score_stream;            /* hipStream_t to use, or NULL                             */
 } rlhf_engine_cfg;
@@ -113,6 +122,7 @@ typedef struct rlhf_step_info {
     int32_t n_prefill_tokens;
     int32_t n_decoded;             /* rows of the decode batch                                */
     int32_t n_active;              /* active-array length after the step (before retire)      */
+    int32_t n_preempted;           /* samples preempted before the decode (optimistic admission) */
 } rlhf_step_info;
 
 typedef struct rlhf_stage_opts {

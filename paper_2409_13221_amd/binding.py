@@ -40,7 +40,7 @@ class rlhf_engine_cfg(C.Structure):
     _fields_ = [("page_tokens", C.c_int32), ("kv_pool_bytes", C.c_int64), ("max_samples", C.c_int32),
                 ("max_ctx", C.c_int32), ("max_active", C.c_int32), ("max_batch_tokens", C.c_int32),
                 ("eos_id", C.c_int32), ("stop_on_eos", C.c_int32), ("corun_decode_cus", C.c_int32),
-                ("reserved", C.c_int32), ("decode_stream", C.c_void_p),
+                ("optimistic_admission", C.c_int32), ("decode_stream", C.c_void_p),
                 ("score_stream", C.c_void_p)]
 
 
@@ -50,7 +50,8 @@ class rlhf_weights(C.Structure):
 
 
 class rlhf_step_info(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("step", "n_admitted", "n_prefill_tokens", "n_decoded", "n_active")]
+    _fields_ = [(n, C.c_int32) for n in ("step", "n_admitted", "n_prefill_tokens", "n_decoded", "n_active",
+                                         "n_preempted")]
 
 
 class rlhf_stage_opts(C.Structure):

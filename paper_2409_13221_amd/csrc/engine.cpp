@@ -446,7 +446,7 @@ static int create_impl(rlhf_ctx* c) {
         HIPCK(c, hipGetDevice(&dev));
         HIPCK(c, hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
     }
-    if (e.corun_decode_cus < 0 || e.corun_decode_cus >= n_cus || e.corun_decode_cus % 32 || e.reserved != 0)
+    if (e.corun_decode_cus < 0 || e.corun_decode_cus >= n_cus || e.corun_decode_cus % 32 || (e.optimistic_admission != 0 && e.optimistic_admission != 1))
         return c->fail(RLHF_EINVAL, "corun_decode_cus must be a multiple of 32 in [0, %d) and reserved must be 0", n_cus);
     auto make_masked = [&](hipStream_t* st, int lo, int hi) -> hipError_t {   // CU-mask bits [lo, hi)
         std::vector<uint32_t> mask((n_cus + 31) / 32, 0u);
@@ -908,17 +908,44 @@ int check_eos(rlhf_ctx* c, const std::vector<int>& ids, const int* d_src) {
 
 bool sample_done(const Sample& s) { return s.finished || s.gen_len >= s.target; }
 
+// The listed active samples give their pages back (each in reverse page-table order), release
+// their reservation and leave the active array; the caller puts them back into the queue.
+void release_samples(rlhf_ctx* c, const int* ids, int n) {
+    std::vector<char> listed(c->smp.size(), 0);
+    for (int k = 0; k < n; ++k) {
+        Sample& s = c->smp[ids[k]];
+        listed[ids[k]] = 1;
+        for (auto it = s.pages.rbegin(); it != s.pages.rend(); ++it) c->free_list.push_back(*it);
+        s.pages.clear();
+        s.ctx = 0;
+        c->reserved -= s.reserve;
+    }
+    std::vector<int> keep;
+    for (int i : c->active)
+        if (!listed[i]) keep.push_back(i);
+    c->active.swap(keep);
+}
+
 }  // namespace
 
 extern "C" int rlhf_generate_step(rlhf_ctx* c, rlhf_step_info* out) {
     if (!c) return RLHF_EINVAL;
     if (!c->roles[RLHF_ACTOR].bound) return c->fail(RLHF_ESTATE, "rlhf_generate_step: Actor weights not loaded");
     if (c->waiting.empty() && c->active.empty()) return c->fail(RLHF_ESTATE, "rlhf_generate_step: nothing to generate");
-    // admission: FIFO, reservation must fit, first misfit blocks the queue
+    // admission: FIFO, first misfit blocks the queue.  The test is the reservation at the cap, or,
+    // under optimistic admission, the pages needed now plus one spare page per running sample.
     std::vector<int> newcomers;
+    int free_now = (int)c->free_list.size();
     while (!c->waiting.empty() && (int)(c->active.size() + newcomers.size()) < c->ec.max_active) {
         const int i = c->waiting.front();
-        if (c->reserved + c->smp[i].reserve > c->pool_pages) break;
+        if (c->ec.optimistic_admission) {
+            const int need = ceil_div(prefill_rows(c->smp[i]) + 1, c->ec.page_tokens);
+            const int running = (int)(c->active.size() + newcomers.size());
+            if (need > free_now || (running > 0 && free_now - need < running)) break;
+            free_now -= need;
+        } else if (c->reserved + c->smp[i].reserve > c->pool_pages) {
+            break;
+        }
         c->waiting.pop_front();
         c->reserved += c->smp[i].reserve;
         newcomers.push_back(i);
@@ -953,6 +980,25 @@ extern "C" int rlhf_generate_step(rlhf_ctx* c, rlhf_step_info* out) {
         g0 = g1;
     }
     for (int i : newcomers) c->active.push_back(i);
+    int n_preempted = 0;
+    if (c->ec.optimistic_admission) {
+        // the decode below takes a page for every sample that sits on a page boundary: if they are
+        // not all there, the most recently admitted unfinished samples give theirs back
+        std::vector<int> victims;
+        for (;;) {
+            int need = 0, last = -1;
+            for (int i : c->active)
+                if (!sample_done(c->smp[i])) {
+                    need += c->smp[i].ctx % c->ec.page_tokens == 0;
+                    last = i;
+                }
+            if (need <= (int)c->free_list.size()) break;
+            release_samples(c, &last, 1);
+            victims.push_back(last);
+        }
+        for (int v : victims) c->waiting.push_front(v);   // earliest admitted victim ends up first
+        n_preempted = (int)victims.size();
+    }
     std::vector<int> rows;
     for (int i : c->active)
         if (!sample_done(c->smp[i])) rows.push_back(i);
@@ -968,6 +1014,7 @@ extern "C" int rlhf_generate_step(rlhf_ctx* c, rlhf_step_info* out) {
         out->n_prefill_tokens = n_prefill;
         out->n_decoded = (int)rows.size();
         out->n_active = (int)c->active.size();
+        out->n_preempted = n_preempted;
     }
     c->step += 1;
     return RLHF_OK;
@@ -1011,17 +1058,7 @@ extern "C" int rlhf_migrate(rlhf_ctx* c, const int32_t* ids, int32_t n, int32_t 
     }
     // work already enqueued on the decode stream that reads these pages runs before whatever is
     // enqueued later and writes them again: stream order is the only ordering needed
-    for (int k = 0; k < n; ++k) {
-        Sample& s = c->smp[ids[k]];
-        for (auto it = s.pages.rbegin(); it != s.pages.rend(); ++it) c->free_list.push_back(*it);
-        s.pages.clear();
-        s.ctx = 0;
-        c->reserved -= s.reserve;
-    }
-    std::vector<int> keep;
-    for (int i : c->active)
-        if (!listed[i]) keep.push_back(i);
-    c->active.swap(keep);
+    release_samples(c, ids, n);
     if (to_back)
         for (int k = 0; k < n; ++k) c->waiting.push_back(ids[k]);
     else

@@ -66,7 +66,8 @@ class GpuStage:
 
     def __init__(self, cfg: WorkloadCfg, inp: dict, pool_pages: Optional[int] = None,
                  max_active: Optional[int] = None, max_batch_tokens: Optional[int] = None,
-                 stop_on_eos: bool = False, max_new_cap: Optional[int] = None, corun_decode_cus: int = 0):
+                 stop_on_eos: bool = False, max_new_cap: Optional[int] = None, corun_decode_cus: int = 0,
+                 optimistic: bool = False):
         import paper_2409_13221_amd as R
         self.R = R
         self.cfg = cfg
@@ -81,11 +82,12 @@ class GpuStage:
         need = int(np.ceil((self.plen + self.max_new) / cfg.page_tokens).sum())
         self.pool_pages = need if pool_pages is None else pool_pages
         self.max_active = self.n if max_active is None else max_active
+        self.optimistic = optimistic
         mc = R.model_cfg_of(m)
         mc.n_layers = ly
         ec = R.rlhf_engine_cfg(cfg.page_tokens, self.pool_pages * page_bytes(cfg, ly), self.n, self.max_ctx,
                                self.max_active,
-                               max(self.max_ctx, max_batch_tokens or 0), cfg.eos_id, int(stop_on_eos), corun_decode_cus, 0, None, None)
+                               max(self.max_ctx, max_batch_tokens or 0), cfg.eos_id, int(stop_on_eos), corun_decode_cus, int(optimistic), None, None)
         self.dev_weights = [{k: v.to("cuda").contiguous() for k, v in w.items()} for w in inp["weights"]]
         self.ctx = R.rlhf_create(mc, ec)
         for role, w in enumerate(self.dev_weights):
@@ -191,7 +193,7 @@ def compare_stage(cfg: WorkloadCfg, ref: dict, got: dict, check_rescored: bool =
 
 def scheduler_model_for(g: GpuStage) -> SchedulerModel:
     return SchedulerModel(g.plen, g.max_new, g.inp["out_len"], g.pool_pages, g.cfg.page_tokens,
-                          max_active=g.max_active)
+                          max_active=g.max_active, optimistic=g.optimistic)
 
 
 def check_samples_by_teacher_forcing(cfg: WorkloadCfg, inp: dict, got: dict, sample_ids, dtype=np.float32,

@@ -106,6 +106,42 @@ def test_tiny_migration_by_reprefill(tiny_ref, to_back, pool_factor):
     H.compare_stage(cfg, ref, got)
 
 
+@pytest.mark.parametrize("pool_pages,max_new_cap,n_preempted", [(48, 64, 0), (16, 64, 0), (9, 64, 1), (7, 64, 2),
+                                                                 (16, None, 0)])
+def test_tiny_optimistic_admission_and_preemption(tiny_ref, pool_pages, max_new_cap, n_preempted):
+    """Admission on present need with preemption by re-prefill: under pools from ample down to one
+    page more than a single sample's cap, every step's bookkeeping (who is admitted, who is preempted,
+    which pages) equals the scheduler model's, and the outputs are those of the undisturbed run."""
+    cfg, ref = tiny_ref
+    pool = pool_pages          # the cap reservations of the 8 samples add up to 48 (33 at their own lengths)
+    with H.GpuStage(cfg, ref, pool_pages=pool, max_new_cap=max_new_cap, optimistic=True) as g:
+        g.submit(ref["forced"])
+        model = H.scheduler_model_for(g)
+        preempted = 0
+        while not model.generation_done():
+            info = g.R.rlhf_generate_step(g.ctx)
+            before = model.n_preempted
+            want = model.generate_step()
+            assert (info.step, info.n_admitted, info.n_prefill_tokens, info.n_decoded, info.n_active) == \
+                   (want.step, want.n_admitted, want.n_prefill_tokens, want.n_decoded, want.n_active)
+            assert info.n_preempted == model.n_preempted - before
+            preempted += info.n_preempted
+            assert g.R.rlhf_retire(g.ctx, g.n).tolist() == model.retire()
+            snap, ms = g.snapshot(), model.snapshot()
+            for k in ("step", "n_waiting", "active", "ctx", "gen_len", "pages", "free", "reserved", "retired"):
+                assert snap[k] == ms[k], k
+        assert preempted == n_preempted
+        g.R.rlhf_score(g.ctx, model.retired, H.ALL_ROLES, True)
+        got = g.results()
+    H.compare_stage(cfg, ref, got)
+    # the whole-stage entry point runs the same policy
+    with H.GpuStage(cfg, ref, pool_pages=pool, max_new_cap=max_new_cap, optimistic=True) as g:
+        g.submit(ref["forced"])
+        stats, _ = g.R.rlhf_run_stage(g.ctx, True, g.n + 1, 64, H.ALL_ROLES)
+        assert stats.n_steps == model.step
+        H.compare_stage(cfg, ref, g.results())
+
+
 @pytest.mark.parametrize("fused,R_t,chunk", [(True, 9, 64), (True, 3, 64), (False, 0, 100), (True, 9, 1)])
 def test_tiny_run_stage_batches_match_scheduler_model(tiny_ref, fused, R_t, chunk):
     cfg, ref = tiny_ref

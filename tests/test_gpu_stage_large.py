@@ -83,6 +83,35 @@ def test_gpt2s_full_config_sampled_outputs_and_bookkeeping():
     assert np.abs(got["lp_actor"] - got["lp_actor_rescored"]).max() <= 4e-2
 
 
+def test_gpt2s_full_config_optimistic_admission_under_memory_pressure():
+    """The same workload with a KV pool of 300 pages (the cap reservations add up to 5120, the
+    samples' own lengths to 1751): admission on present need and preemption by re-prefill.  The
+    scheduler model predicts every step (10 preemptions, 1267 steps instead of the 3729 of cap
+    reservations); the longest sample and two others are checked through the oracle; and for ALL
+    samples the log-probs captured while decoding (over caches that were partly rebuilt by
+    prefill) agree with a full forward."""
+    cfg = CONFIGS["gpt2s"]
+    inp = H.make_inputs(cfg, weight_device="cuda")
+    with H.GpuStage(cfg, inp, pool_pages=300, max_new_cap=cfg.length_cap, max_batch_tokens=8192,
+                    optimistic=True) as g:
+        g.submit(None)
+        model = H.scheduler_model_for(g)
+        trace = model.run_stage(True, g.n + 1, 6144)
+        stats, tr = g.R.rlhf_run_stage(g.ctx, True, g.n + 1, 6144, H.ALL_ROLES, trace_cap=4096)
+        snap = g.snapshot()
+        got = g.results()
+    assert model.n_preempted == 10 and len(trace) == 1267
+    assert stats.n_steps == len(trace) and snap["batches"] == model.batches
+    assert snap["retired"] == model.retired and snap["free"] == model.free
+    assert tr["decoded"].tolist() == [t[0].n_decoded for t in trace]
+    assert tr["prefill_tokens"].tolist() == [t[0].n_prefill_tokens for t in trace]
+    assert got["gen_len"].tolist() == inp["out_len"].tolist()
+    ids = sorted({int(np.argmax(inp["out_len"])), 5, 40})
+    worst = H.check_samples_by_teacher_forcing(cfg, inp, got, ids, dtype=np.float64)
+    print("gpt2s full config, optimistic admission, sampled:", ids, worst, flush=True)
+    assert np.abs(got["lp_actor"] - got["lp_actor_rescored"]).max() <= 4e-2
+
+
 def test_7b_full_config_properties():
     """The 7B-shape workload at full size in bench.py's configuration: bookkeeping bit-exact
     against the scheduler model (admission is gated by the KV pool here), fused and serial plans
