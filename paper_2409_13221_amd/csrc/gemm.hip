@@ -305,11 +305,15 @@ namespace {
 // compute-bound tilings of prefill / scoring passes.  Measured at M = 8192 on the 7B layer
 // shapes (half activations): 5: 650-820, 6: 800-900, 7: 950-1050 TFLOP/s.  Tried and dropped:
 // 256x256 with four 128x128 wave tiles (750-830), global loads two tiles ahead (no change: L2
-// latency is already hidden), fragment loads software-pipelined against the MFMAs (-5 %).
+// latency is already hidden), fragment loads software-pipelined against the MFMAs (-5 %),
+// 256x256 with 32-wide K tiles (half the LDS and fewer registers, so that a decode workgroup fits
+// beside it on a compute unit: 740-890 alone, no net gain for the fused stage).  For 16 and 32
+// rows, 64-column tiles (20-24 KB of LDS, 52-56 registers) stream slightly faster than
+// 128-column ones (36-40 KB, 68-76), and 32-wide K tiles (64-byte row pieces) slower.
 struct TileCfg { int variant, tm, tn, tk; bool xcd; };
 constexpr TileCfg kCfgs[] = {
     {0, 0, 0, 0, false},
-    {1, 16, 128, 64, false}, {2, 32, 128, 64, false}, {3, 64, 128, 64, false}, {4, 128, 128, 64, false},
+    {1, 16, 64, 64, false}, {2, 32, 64, 64, false}, {3, 64, 128, 64, false}, {4, 128, 128, 64, false},
     {5, 128, 128, 64, true}, {6, 256, 128, 32, true}, {7, 256, 256, 64, true},
 };
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
@@ -380,8 +384,8 @@ static hipError_t launch_bf16(hipStream_t st, int variant, const bf16_t* a, cons
     k_gemm_bf16<TM, TN, TK, WM, WN, AF16, XCD, false><<<grid, WM * WN * 64, 0, st>>>(a, w, C, M, N, K, kchunk, \
                                                                                      tiles_m, tiles_n)
     switch (variant) {
-        case 1: RLHF_GEMM(16, 128, 64, 1, 4, false); break;
-        case 2: RLHF_GEMM(32, 128, 64, 1, 4, false); break;
+        case 1: RLHF_GEMM(16, 64, 64, 1, 4, false); break;
+        case 2: RLHF_GEMM(32, 64, 64, 1, 4, false); break;
         case 3: RLHF_GEMM(64, 128, 64, 2, 2, false); break;
         case 4: RLHF_GEMM(128, 128, 64, 2, 2, false); break;
         case 5: RLHF_GEMM(128, 128, 64, 2, 2, true); break;
