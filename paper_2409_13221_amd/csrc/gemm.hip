@@ -77,7 +77,13 @@ __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int& 
 // lane ends up with gate and up of the same output column in neighbouring fragments; the
 // epilogue writes act = silu(gate) * up as 16-bit [M, f] (of the activation type) to C and the
 // float [M, 2f] intermediate never exists.
-template <int TM, int TN, int TK, int WM, int WN, bool AF16, bool XCD, bool SWIGLU>
+//
+// ADMA: the activation tile, which never needs converting, goes from global memory straight
+// into LDS (global_load_lds, 16 bytes per lane, 1 KB per wave and instruction: the lane picks
+// the global chunk whose swizzled place it fills).  That frees its staging registers, which
+// is what lets a decode workgroup sit beside one of these on a compute unit.  Needs whole K
+// tiles (K a multiple of TK, no split); rows past M are clamped (computed, never stored).
+template <int TM, int TN, int TK, int WM, int WN, bool AF16, bool XCD, bool SWIGLU, bool ADMA = false>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __restrict__ A,
                                                            const bf16_t* __restrict__ W,
                                                            float* __restrict__ C, int M, int N, int K,
@@ -101,11 +107,35 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     const int wm = w / WN, wn = w - wm * WN;
 
-    uint4 ra[A_IT], rb[B_IT];
+    // direct path: wave w fills the 1 KB blocks w * D_IT .. of the A tile (1024 / (2 TK) rows each)
+    constexpr int D_RPB = 512 / TK, D_IT = ADMA ? TM / D_RPB / (NT / 64) : 1;
+    static_assert(!ADMA || (TM / D_RPB) % (NT / 64) == 0, "A tile blocks must divide among the waves");
+    size_t da[D_IT];
+    if (ADMA) {
+#pragma unroll
+        for (int i = 0; i < D_IT; ++i) {
+            const int row = (w * D_IT + i) * D_RPB + lane / CH, p = lane % CH;
+            // LDS chunk p of this row holds global chunk c with swz(row, c) == p; the swizzle is an XOR
+            const int c = swz<TK>(row, p);
+            da[i] = (size_t)min(m0 + row, M - 1) * K + c * 8;
+        }
+    }
+    typedef __attribute__((address_space(3))) void* lds_ptr_t;
+    typedef const __attribute__((address_space(1))) void* glb_ptr_t;
+
+    uint4 ra[ADMA ? 1 : A_IT], rb[B_IT];
     auto gload = [&](int kt, uint4* ra, uint4* rb) {
         const int k0 = kbeg + kt * TK;
+        if (ADMA) {
+            // issued first: the wait the compiler places before the next LDS reads then covers
+            // these and leaves the weight loads below in flight
 #pragma unroll
-        for (int i = 0; i < A_IT; ++i) {
+            for (int i = 0; i < D_IT; ++i)
+                __builtin_amdgcn_global_load_lds((glb_ptr_t)(A + da[i] + k0),
+                                                 (lds_ptr_t)&sA[kt & 1][(w * D_IT + i) * 512], 16, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < (ADMA ? 0 : A_IT); ++i) {
             const int idx = t + i * NT;
             const int row = idx / CH, c = idx % CH;
             const int gm = m0 + row, gk = k0 + c * 8;
@@ -132,7 +162,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
     };
     auto sstore = [&](int buf, uint4* ra, uint4* rb) {
 #pragma unroll
-        for (int i = 0; i < A_IT; ++i) {
+        for (int i = 0; i < (ADMA ? 0 : A_IT); ++i) {
             const int idx = t + i * NT;
             const int row = idx / CH, c = idx % CH;
             if (idx < A_CH)
@@ -159,6 +189,48 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
 
     const int fr = lane & 15, fq = lane >> 4;
     auto compute = [&](int buf) {
+        if constexpr (ADMA) {
+            // The fragment reads and their waits are written out by hand.  If the compiler saw LDS
+            // reads here it would first wait for the global -> LDS loads of the NEXT tile issued just
+            // above (it cannot tell the two buffers apart), and the prefetch would overlap nothing.
+            // As it is, those loads are waited for where the loop needs them: by the weight tile's
+            // LDS stores and by the fence of the barrier at the end of the step.
+            static_assert(!ADMA || (FM == 4 && FN == 8 && TK == 64), "hand-placed reads are for the 64 x 128 wave tile");
+            typedef typename Mfma<AF16>::frag frag;
+            const uint32_t xr = (fr >> 1) & 7;       // row part of the swizzle: row bases are multiples of 16
+            const uint32_t pa0 = (uint32_t)(size_t)(lds_ptr_t)&sA[buf][0] + (wm * (TM / WM) + fr) * (TK * 2);
+            const uint32_t pb0 = (uint32_t)(size_t)(lds_ptr_t)&sB[buf][0] + (wn * (TN / WN) + fr) * (TK * 2);
+#define RLHF_DS_READ(dst, addr, off) asm volatile("ds_read_b128 %0, %1 offset:" #off : "=v"(dst) : "v"(addr) : "memory")
+#define RLHF_LGKM0(...) asm volatile("s_waitcnt lgkmcnt(0)" : __VA_ARGS__ : : "memory")
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                frag fa[4], fb[8];
+                const uint32_t co = ((uint32_t)(s * 4 + fq) ^ xr) * 16;
+                const uint32_t pa = pa0 + co, pb = pb0 + co;
+                RLHF_DS_READ(fa[0], pa, 0); RLHF_DS_READ(fa[1], pa, 2048);
+                RLHF_DS_READ(fa[2], pa, 4096); RLHF_DS_READ(fa[3], pa, 6144);
+                RLHF_DS_READ(fb[0], pb, 0); RLHF_DS_READ(fb[1], pb, 2048);
+                RLHF_DS_READ(fb[2], pb, 4096); RLHF_DS_READ(fb[3], pb, 6144);
+                RLHF_LGKM0("+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]),
+                           "+v"(fb[3]));
+                RLHF_DS_READ(fb[4], pb, 8192); RLHF_DS_READ(fb[5], pb, 10240);
+                RLHF_DS_READ(fb[6], pb, 12288); RLHF_DS_READ(fb[7], pb, 14336);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[i][j] = Mfma<AF16>::run(fb[j], fa[i], acc[i][j]);
+                __builtin_amdgcn_sched_barrier(0);
+                RLHF_LGKM0("+v"(fb[4]), "+v"(fb[5]), "+v"(fb[6]), "+v"(fb[7]));
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 4; j < 8; ++j) acc[i][j] = Mfma<AF16>::run(fb[j], fa[i], acc[i][j]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#undef RLHF_DS_READ
+#undef RLHF_LGKM0
+            return;
+        }
 #pragma unroll
         for (int s = 0; s < TK / 32; ++s) {
             typename Mfma<AF16>::frag fa[FM], fb[FN];
@@ -390,7 +462,13 @@ static hipError_t launch_bf16(hipStream_t st, int variant, const bf16_t* a, cons
         case 4: RLHF_GEMM(128, 128, 64, 2, 2, false); break;
         case 5: RLHF_GEMM(128, 128, 64, 2, 2, true); break;
         case 6: RLHF_GEMM(256, 128, 32, 2, 2, true); break;
-        case 7: RLHF_GEMM(256, 256, 64, 4, 2, true); break;      // eight waves, wave tile 64 x 128
+        case 7:                                                  // eight waves, wave tile 64 x 128
+            if (K % 64 == 0)
+                k_gemm_bf16<256, 256, 64, 4, 2, AF16, true, false, true><<<grid, 512, 0, st>>>(a, w, C, M, N, K, kchunk,
+                                                                                             tiles_m, tiles_n);
+            else
+                RLHF_GEMM(256, 256, 64, 4, 2, true);
+            break;
         default: return hipErrorInvalidValue;
     }
 #undef RLHF_GEMM
@@ -409,12 +487,13 @@ hipError_t launch_gemm_swiglu(hipStream_t st, int wdt, int adt, const void* A, c
     const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
     dim3 grid((tiles_m * tiles_n + 7) / 8 * 8, 1);
     const int kchunk = (K + 63) / 64 * 64;
-    if (adt == kF16)
-        k_gemm_bf16<TM, TN, 64, 4, 2, true, true, true><<<grid, 512, 0, st>>>(
-            (const bf16_t*)A, (const bf16_t*)W_gate_up, (float*)act, M, N, K, kchunk, tiles_m, tiles_n);
-    else
-        k_gemm_bf16<TM, TN, 64, 4, 2, false, true, true><<<grid, 512, 0, st>>>(
-            (const bf16_t*)A, (const bf16_t*)W_gate_up, (float*)act, M, N, K, kchunk, tiles_m, tiles_n);
+#define RLHF_SWIGLU(AF, DMA)                                               \
+    k_gemm_bf16<TM, TN, 64, 4, 2, AF, true, true, DMA><<<grid, 512, 0, st>>>( \
+        (const bf16_t*)A, (const bf16_t*)W_gate_up, (float*)act, M, N, K, kchunk, tiles_m, tiles_n)
+    const bool dma = K % 64 == 0;
+    if (adt == kF16) { if (dma) RLHF_SWIGLU(true, true); else RLHF_SWIGLU(true, false); }
+    else { if (dma) RLHF_SWIGLU(false, true); else RLHF_SWIGLU(false, false); }
+#undef RLHF_SWIGLU
     return hipGetLastError();
 }
 
