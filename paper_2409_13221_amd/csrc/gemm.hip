@@ -379,13 +379,14 @@ namespace {
 // 256x256 with four 128x128 wave tiles (750-830), global loads two tiles ahead (no change: L2
 // latency is already hidden), fragment loads software-pipelined against the MFMAs (-5 %),
 // 256x256 with 32-wide K tiles (half the LDS and fewer registers, so that a decode workgroup fits
-// beside it on a compute unit: 740-890 alone, no net gain for the fused stage).  For 16 and 32
-// rows, 64-column tiles (20-24 KB of LDS, 52-56 registers) stream slightly faster than
-// 128-column ones (36-40 KB, 68-76), and 32-wide K tiles (64-byte row pieces) slower.
+// beside it on a compute unit: 740-890 alone, no net gain for the fused stage).  For up to 64
+// rows, 64-column tiles (20-32 KB of LDS, 52-72 registers) stream as fast as or slightly faster
+// than 128-column ones (36-48 KB, 68-108) and fit beside a 256x256 workgroup on a compute unit;
+// 32-wide K tiles (64-byte row pieces) are slower.
 struct TileCfg { int variant, tm, tn, tk; bool xcd; };
 constexpr TileCfg kCfgs[] = {
     {0, 0, 0, 0, false},
-    {1, 16, 64, 64, false}, {2, 32, 64, 64, false}, {3, 64, 128, 64, false}, {4, 128, 128, 64, false},
+    {1, 16, 64, 64, false}, {2, 32, 64, 64, false}, {3, 64, 64, 64, false}, {4, 128, 128, 64, false},
     {5, 128, 128, 64, true}, {6, 256, 128, 32, true}, {7, 256, 256, 64, true},
 };
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
@@ -458,7 +459,7 @@ static hipError_t launch_bf16(hipStream_t st, int variant, const bf16_t* a, cons
     switch (variant) {
         case 1: RLHF_GEMM(16, 64, 64, 1, 4, false); break;
         case 2: RLHF_GEMM(32, 64, 64, 1, 4, false); break;
-        case 3: RLHF_GEMM(64, 128, 64, 2, 2, false); break;
+        case 3: RLHF_GEMM(64, 64, 64, 2, 2, false); break;
         case 4: RLHF_GEMM(128, 128, 64, 2, 2, false); break;
         case 5: RLHF_GEMM(128, 128, 64, 2, 2, true); break;
         case 6: RLHF_GEMM(256, 128, 32, 2, 2, true); break;
