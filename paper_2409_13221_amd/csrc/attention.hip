@@ -149,6 +149,38 @@ __device__ __forceinline__ void block_merge(HeadState (&st)[G], int lane, int wa
     __syncthreads();
 }
 
+// After the waves' (max, sum, accumulator) sit in LDS: merge them and write either the output
+// row or this split's partial.
+template <typename T, int HD, int G>
+__device__ __forceinline__ void decode_block_finish(const float* s_m, const float* s_l, const float* s_acc,
+                                                    int r, int kh, int split, int nsplit, int Hq,
+                                                    T* __restrict__ out, float* __restrict__ part_acc,
+                                                    float* __restrict__ part_ml) {
+    for (int i = threadIdx.x; i < G * HD; i += 256) {
+        const int g = i / HD, e = i - g * HD;
+        float mt = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mt = fmaxf(mt, s_m[w * G + g]);
+        float lt = 0.f, at = 0.f;
+        if (mt > -INFINITY) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float f = __expf(s_m[w * G + g] - mt);
+                lt += s_l[w * G + g] * f;
+                at += s_acc[(w * G + g) * HD + e] * f;
+            }
+        }
+        const int h = kh * G + g;
+        if (nsplit == 1) {
+            out[((size_t)r * Hq + h) * HD + e] = from_f32<T>(at / lt);
+        } else {
+            const size_t slot = ((size_t)r * Hq + h) * nsplit + split;
+            part_acc[slot * HD + e] = at;
+            if (e == 0) { part_ml[slot * 2] = mt; part_ml[slot * 2 + 1] = lt; }
+        }
+    }
+}
+
 template <typename T, int HD, int G>
 __global__ __launch_bounds__(256) void k_decode_attn(const T* __restrict__ q,
                                                      const T* __restrict__ pool,
@@ -197,30 +229,140 @@ __global__ __launch_bounds__(256) void k_decode_attn(const T* __restrict__ q,
         attend_tile<T, HD, G>(kt, kt + v_off, (size_t)HD, n_valid, qf, st, lane);
     }
     block_merge<HD, G>(st, lane, wave, s_m, s_l, s_acc);
+    decode_block_finish<T, HD, G>(s_m, s_l, s_acc, r, kh, split, nsplit, Hq, out, part_acc, part_ml);
+}
 
-    for (int i = threadIdx.x; i < G * HD; i += 256) {
-        const int g = i / HD, e = i - g * HD;
-        float mt = -INFINITY;
+// ------------------------------------------------- decode attention for grouped KV heads, MFMA
+// With G query heads per KV head the VALU kernel above spends its time in the per-head dot
+// products and their shuffles.  Here a wave handles a 16-token page with matrix instructions:
+//   S^T[token][head] = K[token][:] . Q[head][:]      4 x mfma 16x16x32 (heads padded to 16)
+//   O^T[dim][head]  += V^T[dim][token] P^T[token][head]      8 x mfma 16x16x16, one per 16 dims
+// The first product leaves a lane with four consecutive tokens of ONE head (head = lane % 16),
+// which is both what the online softmax needs (a head's state lives in its own lanes; the row
+// maximum and sum cross the four token groups with two xor-shuffles) and, rounded to half, the
+// second product's right operand.  Its left operand wants four tokens of one dim per lane while
+// memory holds eight dims of one token per 16 bytes, so the V page is staged in LDS by rows
+// (row pitch 264 bytes: the four token groups of a read fall into different banks) and read back
+// transposed.  The second product leaves a lane with dims of its own head again, so rescaling by
+// the softmax correction needs no exchange.  Waves take pages round-robin and are merged, like the
+// splits, by (max, sum, accumulator).
+typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+
+template <int HD, int G>
+__global__ __launch_bounds__(256) void k_decode_attn_gqa(const f16_t* __restrict__ q,
+                                                         const f16_t* __restrict__ pool,
+                                                         const int* __restrict__ page_table, int pt_stride,
+                                                         const int* __restrict__ row_sample,
+                                                         const int* __restrict__ ctx_len,
+                                                         f16_t* __restrict__ out, float* __restrict__ part_acc,
+                                                         float* __restrict__ part_ml, int layer, int nsplit,
+                                                         int n_layers, int Hkv) {
+    static_assert(HD == 128 && G <= 16, "one 16-wide head block, eight 16-dim blocks");
+    constexpr int VROW = HD + 4;                       // halves per staged V row (264 bytes)
+    constexpr int kStage = 16 * VROW / 2;              // floats per wave of staging
+    constexpr int kBuf = 4 * G * HD > 4 * kStage ? 4 * G * HD : 4 * kStage;
+    __shared__ float s_m[4 * G], s_l[4 * G];
+    __shared__ __attribute__((aligned(16))) float s_buf[kBuf];   // V staging, then the waves' accumulators
+    const int r = blockIdx.x, kh = blockIdx.y, split = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int head = lane & 15, tg = lane >> 4;        // the lane's head (or token, or dim) and token group
+    const int Hq = Hkv * G;
+    const int ctx = ctx_len[r];
+    const int n_pages = (ctx + kPT - 1) / kPT;
+    const int pps = (n_pages + nsplit - 1) / nsplit;
+    const int pb = split * pps, pe = min(n_pages, pb + pps);
+    const int* pt = page_table + (size_t)row_sample[r] * pt_stride;
+    const float scale = rsqrtf((float)HD);
+    const size_t page_elems = (size_t)n_layers * 2 * Hkv * kPT * HD;
+    const size_t head_off = ((size_t)layer * 2 * Hkv + kh) * kPT * HD;
+    const size_t v_off = (size_t)Hkv * kPT * HD;
+
+    f16x8_t qb[4];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) mt = fmaxf(mt, s_m[w * G + g]);
-        float lt = 0.f, at = 0.f;
-        if (mt > -INFINITY) {
+    for (int ks = 0; ks < 4; ++ks) {
+        qb[ks] = f16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+        if (head < G)
+            qb[ks] = *reinterpret_cast<const f16x8_t*>(q + ((size_t)r * Hq + kh * G + head) * HD + ks * 32 + tg * 8);
+    }
+    float m = -INFINITY, l = 0.f;
+    f32x4_t o[8];
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const float f = __expf(s_m[w * G + g] - mt);
-                lt += s_l[w * G + g] * f;
-                at += s_acc[(w * G + g) * HD + e] * f;
-            }
+    for (int b = 0; b < 8; ++b) o[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    f16_t* vs = reinterpret_cast<f16_t*>(s_buf) + wave * 16 * VROW;
+
+    for (int pi = pb + wave; pi < pe; pi += 4) {
+        const f16_t* kt = pool + (size_t)pt[pi] * page_elems + head_off;
+        const f16_t* vt = kt + v_off;
+        const int n_valid = min(kPT, ctx - pi * kPT);
+        // tokens past the context are read from token 0 (finite data) and masked below
+        const int tk = head < n_valid ? head : 0;
+        f16x8_t ka[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            ka[ks] = *reinterpret_cast<const f16x8_t*>(kt + (size_t)tk * HD + ks * 32 + tg * 8);
+        uint2 vr[4][2];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int tok = i * 4 + tg;
+            const uint4 x = *reinterpret_cast<const uint4*>(vt + (size_t)(tok < n_valid ? tok : 0) * HD + head * 8);
+            vr[i][0] = make_uint2(x.x, x.y);
+            vr[i][1] = make_uint2(x.z, x.w);
         }
-        const int h = kh * G + g;
-        if (nsplit == 1) {
-            out[((size_t)r * Hq + h) * HD + e] = from_f32<T>(at / lt);
-        } else {
-            const size_t slot = ((size_t)r * Hq + h) * nsplit + split;
-            part_acc[slot * HD + e] = at;
-            if (e == 0) { part_ml[slot * 2] = mt; part_ml[slot * 2 + 1] = lt; }
+        f32x4_t st = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) st = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[ks], qb[ks], st, 0, 0, 0);
+        float sc[4], mx = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            sc[e] = tg * 4 + e < n_valid ? st[e] * scale : -INFINITY;
+            mx = fmaxf(mx, sc[e]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        const float m_new = fmaxf(m, mx);               // finite: token 0 of a page is valid
+        const float alpha = __expf(m - m_new);          // exp(-inf) = 0 on the first page
+        float ls = 0.f;
+        f16x4_t pa;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float p = __expf(sc[e] - m_new);
+            ls += p;
+            pa[e] = (f16_t)p;
+        }
+        ls += __shfl_xor(ls, 16, kWave);
+        ls += __shfl_xor(ls, 32, kWave);
+        l = l * alpha + ls;
+        m = m_new;
+#pragma unroll
+        for (int b = 0; b < 8; ++b)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[b][e] *= alpha;
+        // stage the page's V rows, then read them back with tokens along the lane's four values
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f16_t* dst = vs + (i * 4 + tg) * VROW + head * 8;
+            *reinterpret_cast<uint2*>(dst) = vr[i][0];
+            *reinterpret_cast<uint2*>(dst + 4) = vr[i][1];
+        }
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            f16x4_t va;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) va[e] = vs[(tg * 4 + e) * VROW + b * 16 + head];
+            o[b] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, pa, o[b], 0, 0, 0);
         }
     }
+    __syncthreads();                                    // every wave is done with its staging rows
+    float* s_acc = s_buf;
+    if (head < G) {
+        if (tg == 0) { s_m[wave * G + head] = m; s_l[wave * G + head] = l; }
+#pragma unroll
+        for (int b = 0; b < 8; ++b)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s_acc[(wave * G + head) * HD + b * 16 + tg * 4 + e] = o[b][e];
+    }
+    __syncthreads();
+    decode_block_finish<f16_t, HD, G>(s_m, s_l, s_acc, r, kh, split, nsplit, Hq, out, part_acc, part_ml);
 }
 
 // LSE merge of the split partials: one block per (row, head), HD threads.
@@ -273,7 +415,16 @@ hipError_t launch_decode_attn(hipStream_t st, int dtype, const void* q, const vo
         if (hd == 64 && G == 1) RLHF_DEC(bf16_t, 64, 1);
     } else if (dtype == kF16) {
         if (hd == 128 && G == 1) RLHF_DEC(f16_t, 128, 1);
-        if (hd == 128 && G == 8) RLHF_DEC(f16_t, 128, 8);
+        if (hd == 128 && G == 8) {
+            dim3 grid(rows, dm.n_kv_heads, nsplit);
+            k_decode_attn_gqa<128, 8><<<grid, 256, 0, st>>>((const f16_t*)q, (const f16_t*)pool, page_table, pt_stride,
+                                                            row_sample, ctx_len, (f16_t*)out, part_acc, part_ml, layer,
+                                                            nsplit, dm.n_layers, dm.n_kv_heads);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess || nsplit == 1) return e;
+            k_attn_merge<f16_t><<<rows * dm.n_q_heads, 128, 0, st>>>(part_acc, part_ml, (f16_t*)out, nsplit, 128);
+            return hipGetLastError();
+        }
         if (hd == 64 && G == 1) RLHF_DEC(f16_t, 64, 1);
     } else {
         if (hd == 128 && G == 1) RLHF_DEC(float, 128, 1);
