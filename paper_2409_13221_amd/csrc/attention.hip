@@ -9,6 +9,9 @@
 // merged by shuffles at the end, waves through LDS, splits by a small merge kernel (LSE
 // merge), so that a few long samples still spread over the whole chip.
 //
+// With eight query heads per KV head (half precision) the decode kernel is an MFMA one, see
+// k_decode_attn_gqa.
+//
 // Prefill / scoring of float models uses the same inner loop over 16-token tiles of contiguous
 // K/V (one workgroup per query row and KV head); bf16 models use the MFMA kernel at the end of
 // this file.
