@@ -1,11 +1,11 @@
 // C[m][n] = sum_k A[m][k] * W[n][k]   (activations times a row-major weight matrix, y = W x)
 //
 // bf16 weights: LDS-tiled MFMA kernel (v_mfma_f32_16x16x32_{bf16,f16}, float accumulate).
-// Activations are bf16 (decode) or half (prefill / scoring); in the second case the bf16
-// weight chunks are converted to half, exactly, between the global load and the LDS store.  One template
-// serves the decode regime (few rows: the weight matrix streams from HBM once, split along K
-// so that enough workgroups are in flight to saturate bandwidth) and the prefill / scoring
-// regime (thousands of rows: compute-bound 128x128 tiles).  Global loads are 16 bytes per lane,
+// Activations are half (what the stage uses for bf16 models) or bf16; for half the bf16 weight
+// chunks are converted to half, exactly, between the global load and the LDS store.  One
+// template serves the decode regime (few rows: the weight matrix streams from HBM once, split
+// along K so that enough workgroups are in flight to saturate bandwidth) and the prefill /
+// scoring regime (thousands of rows: compute-bound 256x256 tiles).  Global loads are 16 bytes per lane,
 // consecutive lanes along K; tiles sit in LDS with an XOR swizzle of the 16-byte chunk index
 // so that the MFMA-fragment reads (16 rows x one chunk per quarter wave) spread over the banks.
 // Split-K partials are written to separate buffers and summed by the consumer kernel, which
