@@ -98,6 +98,28 @@ def test_paged_decode_attention(dtype, Hq, Hkv, hd, nsplit):
     np.testing.assert_allclose(got, want, rtol=0, atol=tol)
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(16, 2), (4, 4)])
+@pytest.mark.parametrize("nsplit", [1, 5, 16])
+def test_paged_decode_attention_long_contexts(Hq, Hkv, nsplit):
+    """Contexts of thousands of tokens (many pages per wave, splits with and without pages), for
+    the grouped-head MFMA kernel and the one-head-per-KV-head kernel."""
+    R = _R()
+    ctx_lens = [4000, 33, 2047, 1000, 16, 3009]
+    rows, n_layers, layer, hd = len(ctx_lens), 2, 1, 128
+    q, pool, pt, rs, want = _paged_case(21, rows, Hq, Hkv, hd, n_layers, layer, ctx_lens, "half")
+    qd, pd = q.cuda().reshape(rows, Hq * hd).contiguous(), pool.cuda().contiguous()
+    out = torch.zeros_like(qd)
+    pa = torch.zeros(rows * Hq * nsplit * hd, device="cuda")
+    pm = torch.zeros(rows * Hq * nsplit * 2, device="cuda")
+    R.rlhf_op_paged_decode_attention(qd, pd, torch.from_numpy(pt).cuda(), torch.from_numpy(rs).cuda(),
+                                     torch.tensor(ctx_lens, dtype=torch.int32).cuda(), out, pa, pm, layer,
+                                     nsplit, n_layers, Hq, Hkv, hd)
+    torch.cuda.synchronize()
+    got = out.double().cpu().numpy().reshape(rows, Hq, hd)
+    # long contexts average many values: outputs are small and so is their half rounding
+    np.testing.assert_allclose(got, want, rtol=0, atol=2e-3)
+
+
 @pytest.mark.parametrize("Hq,Hkv,hd", [(4, 4, 128), (8, 1, 128), (3, 3, 64)])
 def test_flash_attention(Hq, Hkv, hd):
     """MFMA attention of bf16 models: several query tiles, ragged tails, tiny sequences."""
