@@ -36,6 +36,19 @@ int rlhf_op_gemm(int dtype, int act_half, const void* A, const void* W, float* C
 int rlhf_op_gemm_swiglu(int act_half, const void* A, const void* W_gate_up, void* act, int M, int ffn, int K,
                         void* stream);
 
+/* QKV projection of a prefill / scoring pass with the rotary embedding fused into the epilogue,
+ * as the stage runs it for bf16 models (Section 2.1, the attention input of a decoder block):
+ * row m of A [M, K] (IEEE half if act_half != 0, else bf16) times W_qkv bf16
+ * [(n_q_heads + 2*n_kv_heads)*head_dim, K] (query rows, key rows, value rows); query and key
+ * heads are rotated by position pos[m] (pair (i, i + head_dim/2), cosine and sine taken from
+ * table, float32 [max position][head_dim/2][cos, sin]); results are rounded to A's type and
+ * written to q [M, n_q_heads*head_dim] and, where non-NULL, to k, v [M, n_kv_heads*head_dim] and
+ * to the paged pool (layout as in rlhf_op_paged_decode_attention) at token slot kv_dst[m] =
+ * page*16 + offset.  Needs M >= 512, K a multiple of 64, head_dim 64 or 128 (else RLHF_EINVAL). */
+int rlhf_op_gemm_rope(int act_half, const void* A, const void* W_qkv, const int32_t* pos, const int32_t* kv_dst,
+                      const float* table, void* q, void* k, void* v, void* pool, int M, int K, int layer,
+                      int n_layers, int n_q_heads, int n_kv_heads, int head_dim, void* stream);
+
 /* Decode attention of one step (Section 2.1, decoding phase): row r holds one query
  * [n_q_heads * head_dim] and attends to the ctx_len[r] cached tokens of the sample whose
  * page-table row is row_sample[r].  pool layout: [page][layer][K|V][kv_head][16][head_dim].

@@ -125,11 +125,13 @@ def lib() -> C.CDLL:
         L.rlhf_op_varlen_attention.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp] + [C.c_int] * 4 + [vp]
         L.rlhf_op_flash_attention.argtypes = [vp] * 7 + [C.c_int] * 5 + [vp]
         L.rlhf_op_gemm_swiglu.argtypes = [C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp]
+        L.rlhf_op_gemm_rope.argtypes = [C.c_int] + [vp] * 9 + [C.c_int] * 7 + [vp]
         for name in ("rlhf_create", "rlhf_load_weights", "rlhf_submit", "rlhf_generate_step", "rlhf_retire",
                      "rlhf_migrate", "rlhf_score", "rlhf_run_stage", "rlhf_get_results", "rlhf_debug_snapshot", "rlhf_sync",
                      "rlhf_profile_begin", "rlhf_profile_end", "rlhf_compute_gae",
                      "rlhf_op_gemm_nsplit", "rlhf_op_gemm", "rlhf_op_paged_decode_attention",
-                     "rlhf_op_varlen_attention", "rlhf_op_flash_attention", "rlhf_op_gemm_swiglu"):
+                     "rlhf_op_varlen_attention", "rlhf_op_flash_attention", "rlhf_op_gemm_swiglu",
+                     "rlhf_op_gemm_rope"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -382,3 +384,26 @@ def rlhf_op_gemm_swiglu(A, W_gate_up, act) -> None:
     assert W_gate_up.dtype == torch.bfloat16 and act.dtype == A.dtype and tuple(act.shape) == (M, f)
     _op_check(lib().rlhf_op_gemm_swiglu(int(A.dtype == torch.float16), A.data_ptr(), W_gate_up.data_ptr(),
                                         act.data_ptr(), M, f, K, _stream_ptr()), "rlhf_op_gemm_swiglu")
+
+
+def rlhf_op_gemm_rope(A, W_qkv, pos, table, q, k=None, v=None, pool=None, kv_dst=None, layer=0, n_layers=1,
+                      n_q_heads=1, n_kv_heads=1, head_dim=64) -> None:
+    """A [M,K] float16 or bfloat16, W_qkv bfloat16 [(Hq+2Hkv)*hd, K], pos / kv_dst int32 [M], table float32
+    [max_pos, hd/2, 2]; q, k, v (and pool) of A's dtype."""
+    import torch
+    M, K = A.shape
+    assert W_qkv.dtype == torch.bfloat16 and tuple(W_qkv.shape) == ((n_q_heads + 2 * n_kv_heads) * head_dim, K)
+    assert pos.dtype == torch.int32 and pos.numel() == M and table.dtype == torch.float32
+    assert int(pos.max()) < table.shape[0] and tuple(table.shape[1:]) == (head_dim // 2, 2)
+    assert q.dtype == A.dtype and tuple(q.shape) == (M, n_q_heads * head_dim)
+    for t in (k, v):
+        assert t is None or (t.dtype == A.dtype and tuple(t.shape) == (M, n_kv_heads * head_dim))
+    if pool is not None:
+        assert pool.dtype == A.dtype and kv_dst is not None and kv_dst.dtype == torch.int32 and kv_dst.numel() == M
+        page_elems = n_layers * 2 * n_kv_heads * 16 * head_dim
+        assert pool.numel() % page_elems == 0 and 0 <= int(kv_dst.min()) and int(kv_dst.max()) < pool.numel() // page_elems * 16
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _op_check(lib().rlhf_op_gemm_rope(int(A.dtype == torch.float16), A.data_ptr(), W_qkv.data_ptr(), pos.data_ptr(),
+                                      ptr(kv_dst), table.data_ptr(), q.data_ptr(), ptr(k), ptr(v), ptr(pool), M, K,
+                                      layer, n_layers, n_q_heads, n_kv_heads, head_dim, _stream_ptr()),
+              "rlhf_op_gemm_rope")

@@ -330,12 +330,30 @@ int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
     for (int l = 0; l < m.n_layers; ++l) {
         HIPCK(c, launch_rmsnorm(st, adt, ws.h, ws.part, pns, pstride, nullptr, w.g_attn + (size_t)l * d,
                                 ws.xn, rows, d, m.rms_eps));
-        int ns = nsplit_for(c, ws, rows, qkv_w, d);
-        HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.xn, layer_ptr(w.wqkv, l, qkv_w, d, es), ws.part, rows, qkv_w, d, ns));
-        HIPCK(c, launch_rope_kv(st, qdt, adt, ws.part, ns, (size_t)rows * qkv_w, pm.pos, pm.kv_dst, c->d_rope,
-                                ws.q, mode == kModeBatch ? ws.k : nullptr,
-                                mode == kModeBatch ? ws.v : nullptr, pm.kv_dst ? c->pool : nullptr, l,
-                                rows, c->dm));
+        int ns = 0;
+        if (mode == kModeBatch && gemm_rope_supported(dt, adt, rows, d, c->dm)) {
+            // tall pass: rotary, rounding and the q / k / v / pool scatter ride in the GEMM's epilogue
+            RopeOut ro;
+            ro.pos = pm.pos;
+            ro.kv_dst = pm.kv_dst;
+            ro.table = c->d_rope;
+            ro.q = ws.q; ro.k = ws.k; ro.v = ws.v;
+            ro.pool = pm.kv_dst ? c->pool : nullptr;
+            ro.layer = l; ro.n_layers = m.n_layers;
+            ro.n_q_heads = m.n_q_heads; ro.n_kv_heads = m.n_kv_heads; ro.head_dim = m.head_dim;
+            ro.page_tokens = c->ec.page_tokens;
+            const double bytes = ((double)qkv_w * d + (double)rows * d) * es + (double)rows * qkv_w * es;
+            const void* wq = layer_ptr(w.wqkv, l, qkv_w, d, es);
+            HIPCK(c, profiled(c, st, gcls, bytes, 2.0 * rows * qkv_w * d,
+                              [&] { return launch_gemm_rope(st, dt, adt, ws.xn, wq, rows, d, ro); }));
+        } else {
+            ns = nsplit_for(c, ws, rows, qkv_w, d);
+            HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.xn, layer_ptr(w.wqkv, l, qkv_w, d, es), ws.part, rows, qkv_w, d, ns));
+            HIPCK(c, launch_rope_kv(st, qdt, adt, ws.part, ns, (size_t)rows * qkv_w, pm.pos, pm.kv_dst, c->d_rope,
+                                    ws.q, mode == kModeBatch ? ws.k : nullptr,
+                                    mode == kModeBatch ? ws.v : nullptr, pm.kv_dst ? c->pool : nullptr, l,
+                                    rows, c->dm));
+        }
         if (mode == kModeDecode) {
             HIPCK(c, profiled(c, st, kAttnDecode, pm.attn_bytes, pm.attn_flops, [&] {
                 return launch_decode_attn(st, adt, ws.q, c->pool, c->d_page_table, c->max_pages, pm.row_sample,

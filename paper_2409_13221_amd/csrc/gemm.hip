@@ -14,6 +14,7 @@
 // fp32: a plain LDS-tiled kernel for the float configuration (small model; not tuned).
 #include "common.cuh"
 #include "kernels.h"
+#include <type_traits>
 
 namespace rlhf {
 
@@ -83,11 +84,19 @@ __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int& 
 // the global chunk whose swizzled place it fills).  That frees its staging registers, which
 // is what lets a decode workgroup sit beside one of these on a compute unit.  Needs whole K
 // tiles (K a multiple of TK, no split); rows past M are clamped (computed, never stored).
-template <int TM, int TN, int TK, int WM, int WN, bool AF16, bool XCD, bool SWIGLU, bool ADMA = false>
+//
+// ROPE (= head_dim, 64 or 128; 0 = off): W is a layer's QKV matrix and the epilogue finishes the
+// projection: query and key heads are rotated (pair (k, k + head_dim/2); a wave tile of 128
+// columns holds whole heads, so both halves of a pair sit in one lane, in fragments head_dim/32
+// apart), everything is rounded to the activation type and written where attention reads it:
+// q, k, v row-major, and k, v also into the paged pool when the pass fills the cache.  The
+// float [M, (Hq + 2 Hkv) head_dim] intermediate and the separate rotary kernel disappear.
+template <int TM, int TN, int TK, int WM, int WN, bool AF16, bool XCD, bool SWIGLU, bool ADMA = false, int ROPE = 0>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __restrict__ A,
                                                            const bf16_t* __restrict__ W,
                                                            float* __restrict__ C, int M, int N, int K,
-                                                           int kchunk, int tiles_m, int tiles_n) {
+                                                           int kchunk, int tiles_m, int tiles_n,
+                                                           const RopeOut ro = RopeOut{}) {
     constexpr int NT = WM * WN * 64;
     constexpr int FM = TM / WM / 16, FN = TN / WN / 16;
     constexpr int CH = TK / 8;                            // 16-byte chunks per tile row
@@ -299,6 +308,73 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
         }
         return;
     }
+    if constexpr (ROPE > 0) {
+        static_assert(ROPE == 0 || ((TN / WN) % ROPE == 0 && TN % ROPE == 0), "a wave tile holds whole heads");
+        constexpr int HD = ROPE > 0 ? ROPE : 64, HALF = HD / 2, PF = HD / 32;   // PF: fragments between pair halves
+        typedef typename std::conditional<AF16, f16_t, bf16_t>::type TO;
+        TO* q_out = reinterpret_cast<TO*>(ro.q);
+        TO* k_out = reinterpret_cast<TO*>(ro.k);
+        TO* v_out = reinterpret_cast<TO*>(ro.v);
+        TO* pool = reinterpret_cast<TO*>(ro.pool);
+        const int Hq = ro.n_q_heads, Hkv = ro.n_kv_heads;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int m = m0 + wm * (TM / WM) + i * 16 + fr;
+            if (m >= M) continue;
+            const float* tab = ro.table + (size_t)ro.pos[m] * HD;
+            TO* prow = nullptr;                 // this token's K row of head 0 in the pool
+            if (pool) {
+                const int slot = ro.kv_dst[m];
+                prow = pool + ((size_t)(slot / ro.page_tokens) * ro.n_layers + ro.layer) * 2 * (size_t)Hkv * ro.page_tokens * HD +
+                       (size_t)(slot % ro.page_tokens) * HD;
+            }
+            const size_t head_stride = (size_t)ro.page_tokens * HD;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int n = n0 + wn * (TN / WN) + j * 16 + fq * 4;
+                if (n >= N) continue;            // N is a multiple of head_dim: a group of 4 is in or out
+                const int head = n / HD, c = n - head * HD;
+                const bool first = ((j % (2 * PF)) < PF);
+                float o[4];
+                if (head < Hq + Hkv) {
+                    const int jp = first ? j + PF : j - PF;
+                    const int k = first ? c : c - HALF;
+                    const float4 t0 = *reinterpret_cast<const float4*>(tab + 2 * k);
+                    const float4 t1 = *reinterpret_cast<const float4*>(tab + 2 * k + 4);
+                    const float cs[4] = {t0.x, t0.z, t1.x, t1.z}, sn[4] = {t0.y, t0.w, t1.y, t1.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float a = first ? acc[i][j][e] : acc[i][jp][e];
+                        const float b = first ? acc[i][jp][e] : acc[i][j][e];
+                        o[e] = first ? a * cs[e] - b * sn[e] : a * sn[e] + b * cs[e];
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = acc[i][j][e];
+                }
+                uint2 pk;
+                if (AF16) {
+                    fp16x2_t a = {(__fp16)o[0], (__fp16)o[1]}, b = {(__fp16)o[2], (__fp16)o[3]};
+                    pk.x = *reinterpret_cast<uint32_t*>(&a);
+                    pk.y = *reinterpret_cast<uint32_t*>(&b);
+                } else {
+                    pk.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
+                    pk.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
+                }
+                if (head < Hq) {
+                    *reinterpret_cast<uint2*>(q_out + ((size_t)m * Hq + head) * HD + c) = pk;
+                } else {
+                    const bool is_k = head < Hq + Hkv;
+                    const int kh = is_k ? head - Hq : head - Hq - Hkv;
+                    TO* dst = is_k ? k_out : v_out;
+                    if (dst) *reinterpret_cast<uint2*>(dst + ((size_t)m * Hkv + kh) * HD + c) = pk;
+                    if (prow)
+                        *reinterpret_cast<uint2*>(prow + (is_k ? 0 : (size_t)Hkv * head_stride) + kh * head_stride + c) = pk;
+                }
+            }
+        }
+        return;
+    }
     float* Cs = C + (size_t)split * M * N;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
@@ -495,6 +571,32 @@ hipError_t launch_gemm_swiglu(hipStream_t st, int wdt, int adt, const void* A, c
     if (adt == kF16) { if (dma) RLHF_SWIGLU(true, true); else RLHF_SWIGLU(true, false); }
     else { if (dma) RLHF_SWIGLU(false, true); else RLHF_SWIGLU(false, false); }
 #undef RLHF_SWIGLU
+    return hipGetLastError();
+}
+
+bool gemm_rope_supported(int wdt, int adt, int M, int K, const Dims& dm) {
+    return wdt == kBF16 && (adt == kF16 || adt == kBF16) && M >= 512 && K % 64 == 0 &&
+           (dm.head_dim == 64 || dm.head_dim == 128);
+}
+
+hipError_t launch_gemm_rope(hipStream_t st, int wdt, int adt, const void* A, const void* Wqkv, int M, int K,
+                            const RopeOut& ro) {
+    Dims dm{};
+    dm.head_dim = ro.head_dim;
+    if (!gemm_rope_supported(wdt, adt, M, K, dm) || !ro.pos || !ro.table || !ro.q || (ro.pool && !ro.kv_dst))
+        return hipErrorInvalidValue;
+    constexpr int TM = 256, TN = 256;
+    const int N = (ro.n_q_heads + 2 * ro.n_kv_heads) * ro.head_dim;
+    const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
+    dim3 grid((tiles_m * tiles_n + 7) / 8 * 8, 1);
+    const bf16_t* a = (const bf16_t*)A;
+    const bf16_t* w = (const bf16_t*)Wqkv;
+#define RLHF_ROPE(AF, HD)                                                                             \
+    k_gemm_bf16<TM, TN, 64, 4, 2, AF, true, false, true, HD><<<grid, 512, 0, st>>>(a, w, nullptr, M, N, K, K, \
+                                                                                   tiles_m, tiles_n, ro)
+    if (adt == kF16) { if (ro.head_dim == 128) RLHF_ROPE(true, 128); else RLHF_ROPE(true, 64); }
+    else { if (ro.head_dim == 128) RLHF_ROPE(false, 128); else RLHF_ROPE(false, 64); }
+#undef RLHF_ROPE
     return hipGetLastError();
 }
 

@@ -33,6 +33,23 @@ bool gemm_swiglu_supported(int wdt, int adt, int M, int ffn, int K);
 hipError_t launch_gemm_swiglu(hipStream_t st, int wdt, int adt, const void* A, const void* W_gate_up,
                               void* act, int M, int ffn, int K);
 
+// QKV projection of a tall pass with rotary embedding, type conversion and the scatter to q / k / v
+// (and to the paged pool, if given) in the epilogue: replaces launch_gemm + launch_rope_kv there.
+// Element type of q, k, v, pool = adt.  k, v may be NULL (nothing but the pool wants them).
+struct RopeOut {
+    const int* pos = nullptr;       // [M] rotary position of each row
+    const int* kv_dst = nullptr;    // [M] page * page_tokens + offset (needed with pool)
+    const float* table = nullptr;   // [max_pos][head_dim/2][cos, sin]
+    void* q = nullptr;              // [M, Hq*hd]
+    void* k = nullptr;              // [M, Hkv*hd] or NULL
+    void* v = nullptr;
+    void* pool = nullptr;           // paged KV pool or NULL
+    int layer = 0, n_layers = 0, n_q_heads = 0, n_kv_heads = 0, head_dim = 0, page_tokens = 16;
+};
+bool gemm_rope_supported(int wdt, int adt, int M, int K, const Dims& dm);
+hipError_t launch_gemm_rope(hipStream_t st, int wdt, int adt, const void* A, const void* Wqkv, int M, int K,
+                            const RopeOut& ro);
+
 // ---- elementwise / row kernels
 hipError_t launch_embed(hipStream_t st, int dtype, const int* tokens, const int* tok_idx,
                         const void* table, float* h, int rows, int d, int vocab);

@@ -73,3 +73,21 @@ extern "C" int rlhf_op_gemm_swiglu(int act_half, const void* A, const void* W_ga
     if (!gemm_swiglu_supported(kBF16, adt, M, ffn, K)) return RLHF_EINVAL;
     return status_of(launch_gemm_swiglu((hipStream_t)stream, kBF16, adt, A, W_gate_up, act, M, ffn, K));
 }
+
+extern "C" int rlhf_op_gemm_rope(int act_half, const void* A, const void* W_qkv, const int32_t* pos,
+                                 const int32_t* kv_dst, const float* table, void* q, void* k, void* v, void* pool,
+                                 int M, int K, int layer, int n_layers, int n_q_heads, int n_kv_heads, int head_dim,
+                                 void* stream) {
+    if (!A || !W_qkv || !pos || !table || !q || (pool && !kv_dst) || n_q_heads <= 0 || n_kv_heads <= 0 ||
+        n_q_heads % n_kv_heads || layer < 0 || layer >= n_layers)
+        return RLHF_EINVAL;
+    const int adt = act_half ? kF16 : kBF16;
+    Dims dm{n_layers, K, n_q_heads, n_kv_heads, head_dim, 0, 0, 16};
+    if (!gemm_rope_supported(kBF16, adt, M, K, dm)) return RLHF_EINVAL;
+    RopeOut ro;
+    ro.pos = pos; ro.kv_dst = kv_dst; ro.table = table;
+    ro.q = q; ro.k = k; ro.v = v; ro.pool = pool;
+    ro.layer = layer; ro.n_layers = n_layers;
+    ro.n_q_heads = n_q_heads; ro.n_kv_heads = n_kv_heads; ro.head_dim = head_dim;
+    return status_of(launch_gemm_rope((hipStream_t)stream, kBF16, adt, A, W_qkv, M, K, ro));
+}

@@ -204,3 +204,53 @@ def test_gemm_swiglu_fused(half_act, M, f, K):
     assert np.isfinite(got).all() and np.abs(want).max() > 0.3
     tol = (2 ** -11 if half_act else 2 ** -8) * np.maximum(np.abs(want), 1e-2) + 1e-4   # output rounding
     assert np.all(np.abs(got - want) <= tol), np.abs(got - want).max()
+
+
+@pytest.mark.parametrize("half_act", [True, False])
+@pytest.mark.parametrize("M,K,Hq,Hkv,hd,with_pool", [(512, 256, 4, 4, 64, False), (700, 320, 5, 1, 64, True),
+                                                     (1000, 192, 3, 1, 128, True), (1024, 512, 8, 2, 128, False)])
+def test_gemm_rope_fused(half_act, M, K, Hq, Hkv, hd, with_pool):
+    """QKV projection with rotary embedding, rounding and the q / k / v / paged-pool scatter in
+    the epilogue against float64 (ragged M and N edges, grouped heads, both head sizes)."""
+    R = _R()
+    r = np.random.default_rng(M + K)
+    base, n_layers, layer, max_pos = 10000.0, 3, 1, 300
+    N = (Hq + 2 * Hkv) * hd
+    a, w = r.normal(size=(M, K)), r.normal(size=(N, K)) * 0.06
+    A = torch.from_numpy(a.astype(np.float32)).half().cuda() if half_act else _bf16_round(a).cuda()
+    W = _bf16_round(w).cuda()
+    pos = r.integers(0, max_pos, size=M).astype(np.int32)
+    ang = np.arange(max_pos)[:, None] * base ** (-2.0 * np.arange(hd // 2) / hd)[None, :]
+    table = torch.from_numpy(np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32)).cuda()
+    z = A.double().cpu().numpy() @ W.double().cpu().numpy().T
+    want_q = OT.rope(z[:, :Hq * hd].reshape(M, Hq, hd), pos, base).reshape(M, -1)
+    want_k = OT.rope(z[:, Hq * hd:(Hq + Hkv) * hd].reshape(M, Hkv, hd), pos, base).reshape(M, -1)
+    want_v = z[:, (Hq + Hkv) * hd:]
+    nan = lambda *s: torch.full(s, float("nan"), dtype=A.dtype, device="cuda")
+    q, k, v = nan(M, Hq * hd), nan(M, Hkv * hd), nan(M, Hkv * hd)
+    n_pages = (M + 15) // 16 + 2
+    pool = nan(n_pages, n_layers, 2, Hkv, 16, hd) if with_pool else None
+    slots = r.permutation(n_pages * 16)[:M].astype(np.int32)          # every row its own token slot
+    R.rlhf_op_gemm_rope(A, W, torch.from_numpy(pos).cuda(), table, q, k if not with_pool else None,
+                        v if not with_pool else None, pool, torch.from_numpy(slots).cuda() if with_pool else None,
+                        layer, n_layers, Hq, Hkv, hd)
+    torch.cuda.synchronize()
+    eps = 2 ** -11 if half_act else 2 ** -8
+
+    def close(got, want):
+        got = got.double().cpu().numpy()
+        assert np.isfinite(got).all() and np.abs(want).max() > 0.3
+        assert np.all(np.abs(got - want) <= eps * np.maximum(np.abs(want), 1e-2) + 1e-4), np.abs(got - want).max()
+
+    close(q, want_q)
+    if with_pool:
+        p = pool.double().cpu().numpy()
+        got = p[slots // 16, layer, :, :, slots % 16, :]              # [M, 2, Hkv, hd]
+        close(torch.from_numpy(got[:, 0].reshape(M, -1)), want_k)
+        close(torch.from_numpy(got[:, 1].reshape(M, -1)), want_v)
+        p[slots // 16, layer, :, :, slots % 16, :] = np.nan
+        assert np.isnan(p).all()                                      # nothing else was written
+        assert torch.isnan(k).all() and torch.isnan(v).all()
+    else:
+        close(k, want_k)
+        close(v, want_v)
