@@ -149,7 +149,8 @@ def roofline_of(prof, dtype, traffic):
 def micro(args):
     """Kernel-level cases at the 7B layer shapes through the ops ABI, for rocprofv3 counter runs:
     a 1 GiB device copy (calibration of FETCH_SIZE / WRITE_SIZE), the four projections of a
-    scoring pass (M = --micro_rows, half activations, SwiGLU fused into gate||up as in the stage),
+    scoring pass (M = --micro_rows, half activations, rotary fused into QKV and SwiGLU into gate||up as
+    in the stage),
     the same four in the decode regime (M = 8), and paged decode attention (32 samples x 1024
     cached tokens, 32 heads x 128, half)."""
     import torch
@@ -186,6 +187,16 @@ def micro(args):
                 act = torch.empty(M, N // 2, device=dev, dtype=torch.float16)
                 timed(f"gemm_{name}_swiglu_M{M}", lambda: R.rlhf_op_gemm_swiglu(A, W, act),
                       (N * K + M * K) * 2.0 + M * (N // 2) * 2.0, 2.0 * M * N * K)
+                continue
+            if name == "qkv" and M >= 512:           # as the stage runs it: rotary and q/k/v scatter in the epilogue
+                Hq, hd = 32, 128
+                pos = torch.randint(0, 2048, (M,), device=dev, dtype=torch.int32)
+                ang = torch.arange(2048, device=dev)[:, None] * 10000.0 ** (-2.0 * torch.arange(hd // 2, device=dev) / hd)[None, :]
+                tab = torch.stack([torch.cos(ang), torch.sin(ang)], dim=-1).float().contiguous()
+                q, k, v = (torch.empty(M, Hq * hd, device=dev, dtype=torch.float16) for _ in range(3))
+                timed(f"gemm_{name}_rope_M{M}", lambda: R.rlhf_op_gemm_rope(A, W, pos, tab, q, k, v, n_q_heads=Hq,
+                                                                            n_kv_heads=Hq, head_dim=hd),
+                      (N * K + M * K) * 2.0 + M * N * 2.0, 2.0 * M * N * K)
                 continue
             ns = R.rlhf_op_gemm_nsplit(R.RLHF_BF16, M, N, K, 16)
             C = torch.empty(ns, M, N, device=dev)

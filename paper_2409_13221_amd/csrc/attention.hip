@@ -527,7 +527,7 @@ hipError_t launch_prefill_attn(hipStream_t st, int odt, const float* q, const fl
 constexpr int kFaBM = 128, kFaBN = 64, kFaVStride = kFaBN + 8;
 
 template <int HD>
-__global__ __launch_bounds__(256) void k_flash_attn(const f16_t* __restrict__ q,
+__global__ __launch_bounds__(256, 2) void k_flash_attn(const f16_t* __restrict__ q,
                                                     const f16_t* __restrict__ k,
                                                     const f16_t* __restrict__ v,
                                                     const int* __restrict__ tile_start,
@@ -548,7 +548,7 @@ __global__ __launch_bounds__(256) void k_flash_attn(const f16_t* __restrict__ q,
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int fr = lane & 15, g = lane >> 4;
     const size_t qstride = (size_t)Hq * HD, kstride = (size_t)Hkv * HD;
-    const float scale = rsqrtf((float)HD);
+    const float sl2e = rsqrtf((float)HD) * 1.44269504088896f;     // log2(e) / sqrt(HD)
 
     // Q fragments (B operand): query fr of each 16-row fragment, 8 dims at (s*32 + g*8)
     f16x8_t qf[2][KS];
@@ -569,36 +569,65 @@ __global__ __launch_bounds__(256) void k_flash_attn(const f16_t* __restrict__ q,
     const int q_last = min(q0 + kFaBM, L) - 1;
     const int n_kt = q_last / kFaBN + 1;
 
-    uint4 rk[LD_IT], rv[LD_IT];
-    auto gload = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < LD_IT; ++i) {
-            const int idx = t + i * 256;
-            const int row = idx / CH, c = idx % CH;
-            const size_t grow = (size_t)min(s0 + kt * kFaBN + row, T_total - 1);
-            rk[i] = *reinterpret_cast<const uint4*>(k + grow * kstride + (size_t)kh * HD + c * 8);
-            rv[i] = *reinterpret_cast<const uint4*>(v + grow * kstride + (size_t)kh * HD + c * 8);
-        }
+    // K: a thread takes 16-byte chunks of consecutive rows' pieces (coalesced), stored row-major.
+    // V: a thread takes the same chunk of two neighbouring keys, so that the transposed store
+    // writes whole 32-bit words [d][key pair]; the 32 pairs of a half wave land in 32 different
+    // banks and the other half wave (next chunk: 8 d rows = 288 words further) in the other 32.
+    constexpr int VP_IT = LD_IT / 2;
+    static_assert(LD_IT % 2 == 0 && kFaVStride % 2 == 0, "V is stored in key pairs");
+    static_assert(LD_IT == 2 || LD_IT == 4, "64 keys x 64 or 128 dims over 256 threads");
+    uint4 rk0, rk1, rk2 = make_uint4(0, 0, 0, 0), rk3 = rk2, rva0, rvb0, rva1 = rk2, rvb1 = rk2;
+    auto k_src = [&](int kt, int i) {
+        const int idx = t + i * 256;
+        const size_t grow = (size_t)min(s0 + kt * kFaBN + idx / CH, T_total - 1);
+        return reinterpret_cast<const uint4*>(k + grow * kstride + (size_t)kh * HD + (idx % CH) * 8);
     };
-    auto sstore = [&]() {
-#pragma unroll
-        for (int i = 0; i < LD_IT; ++i) {
-            const int idx = t + i * 256;
-            const int row = idx / CH, c = idx % CH;
-            const int pc = (CH == 16) ? (c ^ (row & 15)) : (c ^ ((row >> 1) & 7));
-            *reinterpret_cast<uint4*>(&sK[row * HD + pc * 8]) = rk[i];
-            const f16_t* ve = reinterpret_cast<const f16_t*>(&rv[i]);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) sVt[(c * 8 + e) * kFaVStride + row] = ve[e];
-        }
+    auto v_src = [&](int kt, int i, int u) {
+        const int item = t + i * 256;
+        const size_t grow = (size_t)min(s0 + kt * kFaBN + 2 * (item & 31) + u, T_total - 1);
+        return reinterpret_cast<const uint4*>(v + grow * kstride + (size_t)kh * HD + (item >> 5) * 8);
     };
+    auto k_dst = [&](int i) {
+        const int idx = t + i * 256;
+        const int row = idx / CH, c = idx % CH;
+        const int pc = (CH == 16) ? (c ^ (row & 15)) : (c ^ ((row >> 1) & 7));
+        return reinterpret_cast<uint4*>(&sK[row * HD + pc * 8]);
+    };
+    auto v_store = [&](int i, const uint4& va, const uint4& vb) {
+        uint32_t* sVt32 = reinterpret_cast<uint32_t*>(sVt);
+        const int item = t + i * 256;
+        const int pr = item & 31, c = item >> 5;
+        uint32_t* d0 = sVt32 + (c * 8) * (kFaVStride / 2) + pr;
+        d0[0 * (kFaVStride / 2)] = (va.x & 0xFFFFu) | (vb.x << 16);
+        d0[1 * (kFaVStride / 2)] = (va.x >> 16) | (vb.x & 0xFFFF0000u);
+        d0[2 * (kFaVStride / 2)] = (va.y & 0xFFFFu) | (vb.y << 16);
+        d0[3 * (kFaVStride / 2)] = (va.y >> 16) | (vb.y & 0xFFFF0000u);
+        d0[4 * (kFaVStride / 2)] = (va.z & 0xFFFFu) | (vb.z << 16);
+        d0[5 * (kFaVStride / 2)] = (va.z >> 16) | (vb.z & 0xFFFF0000u);
+        d0[6 * (kFaVStride / 2)] = (va.w & 0xFFFFu) | (vb.w << 16);
+        d0[7 * (kFaVStride / 2)] = (va.w >> 16) | (vb.w & 0xFFFF0000u);
+    };
+#define RLHF_FA_GLOAD(kt_)                                                       \
+    do {                                                                         \
+        rk0 = *k_src(kt_, 0); rk1 = *k_src(kt_, 1);                              \
+        if (LD_IT == 4) { rk2 = *k_src(kt_, 2); rk3 = *k_src(kt_, 3); }          \
+        rva0 = *v_src(kt_, 0, 0); rvb0 = *v_src(kt_, 0, 1);                      \
+        if (LD_IT == 4) { rva1 = *v_src(kt_, 1, 0); rvb1 = *v_src(kt_, 1, 1); }  \
+    } while (0)
+#define RLHF_FA_SSTORE()                                                         \
+    do {                                                                         \
+        *k_dst(0) = rk0; *k_dst(1) = rk1;                                        \
+        if (LD_IT == 4) { *k_dst(2) = rk2; *k_dst(3) = rk3; }                    \
+        v_store(0, rva0, rvb0);                                                  \
+        if (LD_IT == 4) v_store(1, rva1, rvb1);                                  \
+    } while (0)
 
-    gload(0);
+    RLHF_FA_GLOAD(0);
     for (int kt = 0; kt < n_kt; ++kt) {
         __syncthreads();                       // the previous tile has been consumed
-        sstore();
+        RLHF_FA_SSTORE();
         __syncthreads();
-        if (kt + 1 < n_kt) gload(kt + 1);
+        if (kt + 1 < n_kt) RLHF_FA_GLOAD(kt + 1);
 
         // ---- S^T = K Q^T
         f32x4_t sacc[4][2];
@@ -618,32 +647,38 @@ __global__ __launch_bounds__(256) void k_flash_attn(const f16_t* __restrict__ q,
                     sacc[f][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qf[m][s], sacc[f][m], 0, 0, 0);
             }
         }
-        // ---- mask, online softmax (per query = per lane column)
+        // ---- mask, online softmax (per query = per lane column).  Running maxima are kept on the
+        // raw scores; 1/sqrt(HD) and log2(e) are folded into one multiply-add in front of exp2.
+        // Only tiles that reach past this wave's first query need the causal mask (a valid query
+        // never sees keys past the end of its sequence: key <= query < L).
+        const bool diag = kt * kFaBN + kFaBN - 1 > q0 + wave * 32;
         f16x8_t pb[2][2];
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
             const int qrow = q0 + wave * 32 + m * 16 + fr;
-            float mx = -INFINITY;
+            if (diag) {
 #pragma unroll
-            for (int f = 0; f < 4; ++f)
+                for (int f = 0; f < 4; ++f)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int key = kt * kFaBN + f * 16 + g * 4 + r;
-                    const float sv = (key <= qrow) ? sacc[f][m][r] * scale : -INFINITY;
-                    sacc[f][m][r] = sv;
-                    mx = fmaxf(mx, sv);
-                }
+                    for (int r = 0; r < 4; ++r)
+                        if (kt * kFaBN + f * 16 + g * 4 + r > qrow) sacc[f][m][r] = -INFINITY;
+            }
+            float mx = fmaxf(fmaxf(sacc[0][m][0], sacc[0][m][1]), fmaxf(sacc[0][m][2], sacc[0][m][3]));
+#pragma unroll
+            for (int f = 1; f < 4; ++f)
+                mx = fmaxf(mx, fmaxf(fmaxf(sacc[f][m][0], sacc[f][m][1]), fmaxf(sacc[f][m][2], sacc[f][m][3])));
             mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
             mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
             const float m_new = fmaxf(m_run[m], mx);
-            const float alpha = __expf(m_run[m] - m_new);
+            const float alpha = __builtin_amdgcn_exp2f((m_run[m] - m_new) * sl2e);
             m_run[m] = m_new;
+            const float mc = m_new * sl2e;
             float ls = 0.f;
 #pragma unroll
             for (int f = 0; f < 4; ++f)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const float p = __expf(sacc[f][m][r] - m_new);
+                    const float p = __builtin_amdgcn_exp2f(fmaf(sacc[f][m][r], sl2e, -mc));
                     ls += p;
                     pb[m][f >> 1][(f & 1) * 4 + r] = (f16_t)p;
                 }
@@ -687,6 +722,9 @@ __global__ __launch_bounds__(256) void k_flash_attn(const f16_t* __restrict__ q,
         }
     }
 }
+
+#undef RLHF_FA_GLOAD
+#undef RLHF_FA_SSTORE
 
 hipError_t launch_flash_attn(hipStream_t st, const void* q, const void* k, const void* v,
                              const int* tile_start, const int* tile_q0, const int* tile_len, void* out,
