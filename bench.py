@@ -195,7 +195,8 @@ def micro(args):
                 tab = torch.stack([torch.cos(ang), torch.sin(ang)], dim=-1).float().contiguous()
                 q, k, v = (torch.empty(M, Hq * hd, device=dev, dtype=torch.float16) for _ in range(3))
                 timed(f"gemm_{name}_rope_M{M}", lambda: R.rlhf_op_gemm_rope(A, W, pos, tab, q, k, v, n_q_heads=Hq,
-                                                                            n_kv_heads=Hq, head_dim=hd),
+                                                                            n_kv_heads=Hq, head_dim=hd,
+                                                                            check_indices=False),
                       (N * K + M * K) * 2.0 + M * N * 2.0, 2.0 * M * N * K)
                 continue
             ns = R.rlhf_op_gemm_nsplit(R.RLHF_BF16, M, N, K, 16)
