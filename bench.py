@@ -350,7 +350,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the stage shards by sample across GPUs with no collective "
-              "inside it; see DESIGN.md).  Run with --gpus 1.", file=sys.stderr)
+              "inside it, so N GPUs are N independent copies of this run).  Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
 
