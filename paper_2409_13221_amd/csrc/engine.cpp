@@ -465,7 +465,7 @@ static int create_impl(rlhf_ctx* c) {
         HIPCK(c, hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
     }
     if (e.corun_decode_cus < 0 || e.corun_decode_cus >= n_cus || e.corun_decode_cus % 32 || (e.optimistic_admission != 0 && e.optimistic_admission != 1))
-        return c->fail(RLHF_EINVAL, "corun_decode_cus must be a multiple of 32 in [0, %d) and reserved must be 0", n_cus);
+        return c->fail(RLHF_EINVAL, "corun_decode_cus must be a multiple of 32 in [0, %d) and optimistic_admission 0 or 1", n_cus);
     auto make_masked = [&](hipStream_t* st, int lo, int hi) -> hipError_t {   // CU-mask bits [lo, hi)
         std::vector<uint32_t> mask((n_cus + 31) / 32, 0u);
         for (int bit = lo; bit < hi; ++bit) mask[bit >> 5] |= 1u << (bit & 31);
