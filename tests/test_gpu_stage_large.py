@@ -112,19 +112,22 @@ def test_gpt2s_full_config_optimistic_admission_under_memory_pressure():
     assert np.abs(got["lp_actor"] - got["lp_actor_rescored"]).max() <= 4e-2
 
 
-def test_7b_full_config_properties():
-    """The 7B-shape workload at full size in bench.py's configuration: bookkeeping bit-exact
-    against the scheduler model (admission is gated by the KV pool here), fused and serial plans
-    give identical tokens, and the Actor log-probs captured by cached decoding agree with their
-    re-scoring by a full forward (cached decode = full recompute)."""
+@pytest.mark.parametrize("optimistic", [True, False])
+def test_7b_full_config_properties(optimistic):
+    """The 7B-shape workload at full size in bench.py's configuration (optimistic admission is
+    what bench.py times by default; cap reservations, where the KV pool gates admission, is its
+    --admission reserve): bookkeeping bit-exact against the scheduler model, fused and serial
+    plans give identical tokens, and the Actor log-probs captured by cached decoding agree with
+    their re-scoring by a full forward (cached decode = full recompute)."""
     import torch
     cfg = CONFIGS["7b"]
     inp = H.make_inputs(cfg, weight_device="cuda")
     print("[7b full] weights ready", flush=True)
     free_b, _ = torch.cuda.mem_get_info()
     pool_pages = int((free_b - (24 << 30)) // H.page_bytes(cfg))
-    with H.GpuStage(cfg, inp, pool_pages=pool_pages, max_new_cap=cfg.length_cap, max_batch_tokens=8192) as g:
-        assert g.pool_pages < int(np.ceil((g.plen + g.max_new) / 16).sum())      # the pool really gates
+    with H.GpuStage(cfg, inp, pool_pages=pool_pages, max_new_cap=cfg.length_cap, max_batch_tokens=8192,
+                    optimistic=optimistic) as g:
+        assert g.pool_pages < int(np.ceil((g.plen + g.max_new) / 16).sum())      # cap reservations would not fit
         g.submit(None)
         model = H.scheduler_model_for(g)
         trace = model.run_stage(True, g.n + 1, 6144)
@@ -136,7 +139,11 @@ def test_7b_full_config_properties():
         assert snap["retired"] == model.retired and snap["free"] == model.free
         assert tr["decoded"].tolist() == [t[0].n_decoded for t in trace]
         assert tr["active"].tolist() == [t[0].n_active - len(t[1]) for t in trace]
-        assert max(t[0].n_admitted for t in trace[1:]) > 0                        # late admissions happened
+        assert tr["prefill_tokens"].tolist() == [t[0].n_prefill_tokens for t in trace]   # re-prefills included
+        if optimistic:
+            assert trace[0][0].n_admitted == g.n                                  # nobody waits for a reservation
+        else:
+            assert max(t[0].n_admitted for t in trace[1:]) > 0                    # late admissions happened
         g.submit(None)
         stats2, _ = g.R.rlhf_run_stage(g.ctx, False, 0, 6144, 0b1110, trace_cap=0)
         serial = g.results()
