@@ -277,17 +277,15 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
     }
 
     if (SWIGLU) {
-        static_assert(!SWIGLU || (FN % 2 == 0), "gate and up fragments come in pairs");
+        static_assert(!SWIGLU || (FN % 4 == 0), "gate and up fragments come in pairs, pairs are stored two at a time");
         const int f = N >> 1;
         uint16_t* act = reinterpret_cast<uint16_t*>(C);
+        const bool odd = fq & 1;
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
             const int m = m0 + wm * (TM / WM) + i * 16 + fr;
-            if (m >= M) continue;
-#pragma unroll
-            for (int j = 0; j < FN; j += 2) {
-                const int oc = (n0 >> 1) + ((wn * (TN / WN) + j * 16) >> 1) + fq * 4;
-                if (oc >= f) continue;       // f is a multiple of 8: a group of 4 is in or out
+            // silu(gate) * up of fragment pair (j, j + 1): four consecutive output columns in 8 bytes
+            auto packed = [&](int j) {
                 float o[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -303,7 +301,21 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
                     pk.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
                     pk.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
                 }
-                *reinterpret_cast<uint2*>(act + (size_t)m * f + oc) = pk;
+                return pk;
+            };
+            // Two fragment pairs cover 32 consecutive output columns; neighbouring quarter waves swap
+            // one of them each, so that a lane stores eight consecutive columns (16 bytes).
+#pragma unroll
+            for (int j = 0; j < FN; j += 4) {
+                const uint2 p0 = packed(j), p1 = packed(j + 2);
+                const uint2 give = odd ? p0 : p1;
+                uint2 got;
+                got.x = (uint32_t)__shfl_xor((int)give.x, 16, kWave);
+                got.y = (uint32_t)__shfl_xor((int)give.y, 16, kWave);
+                const uint4 pk = odd ? make_uint4(got.x, got.y, p1.x, p1.y) : make_uint4(p0.x, p0.y, got.x, got.y);
+                const int oc = (n0 >> 1) + ((wn * (TN / WN) + (odd ? j + 2 : j) * 16) >> 1) + (fq & 2) * 4;
+                if (m >= M || oc >= f) continue;       // f is a multiple of 8: a group of 8 is in or out
+                *reinterpret_cast<uint4*>(act + (size_t)m * f + oc) = pk;
             }
         }
         return;
@@ -317,26 +329,27 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
         TO* v_out = reinterpret_cast<TO*>(ro.v);
         TO* pool = reinterpret_cast<TO*>(ro.pool);
         const int Hq = ro.n_q_heads, Hkv = ro.n_kv_heads;
+        static_assert(ROPE == 0 || FN % 2 == 0, "fragments are stored in pairs");
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
             const int m = m0 + wm * (TM / WM) + i * 16 + fr;
-            if (m >= M) continue;
-            const float* tab = ro.table + (size_t)ro.pos[m] * HD;
+            const bool row_ok = m < M;
+            const int mc = row_ok ? m : M - 1;
+            const float* tab = ro.table + (size_t)ro.pos[mc] * HD;
             TO* prow = nullptr;                 // this token's K row of head 0 in the pool
             if (pool) {
-                const int slot = ro.kv_dst[m];
+                const int slot = ro.kv_dst[mc];
                 prow = pool + ((size_t)(slot / ro.page_tokens) * ro.n_layers + ro.layer) * 2 * (size_t)Hkv * ro.page_tokens * HD +
                        (size_t)(slot % ro.page_tokens) * HD;
             }
             const size_t head_stride = (size_t)ro.page_tokens * HD;
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const int n = n0 + wn * (TN / WN) + j * 16 + fq * 4;
-                if (n >= N) continue;            // N is a multiple of head_dim: a group of 4 is in or out
-                const int head = n / HD, c = n - head * HD;
+            // rotated, rounded and packed fragment j of this row: four consecutive columns in 8 bytes
+            auto packed = [&](int j) {
+                const int c = (wn * (TN / WN) + j * 16 + fq * 4) % HD;
+                const bool rot = n0 + wn * (TN / WN) + j * 16 < (Hq + Hkv) * HD;
                 const bool first = ((j % (2 * PF)) < PF);
                 float o[4];
-                if (head < Hq + Hkv) {
+                if (rot) {
                     const int jp = first ? j + PF : j - PF;
                     const int k = first ? c : c - HALF;
                     const float4 t0 = *reinterpret_cast<const float4*>(tab + 2 * k);
@@ -361,15 +374,32 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
                     pk.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
                     pk.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
                 }
+                return pk;
+            };
+            // Fragments j and j + 1 cover 32 consecutive columns, four at a time per quarter wave.
+            // Neighbouring quarter waves swap one fragment each, after which a lane holds eight
+            // consecutive columns (16 bytes) and a row's 64 bytes are written by four lanes.
+            const bool odd = fq & 1;
+#pragma unroll
+            for (int j = 0; j < FN; j += 2) {
+                const uint2 p0 = packed(j), p1 = packed(j + 1);
+                const uint2 give = odd ? p0 : p1;
+                uint2 got;
+                got.x = (uint32_t)__shfl_xor((int)give.x, 16, kWave);
+                got.y = (uint32_t)__shfl_xor((int)give.y, 16, kWave);
+                const uint4 pk = odd ? make_uint4(got.x, got.y, p1.x, p1.y) : make_uint4(p0.x, p0.y, got.x, got.y);
+                const int n = n0 + wn * (TN / WN) + (odd ? j + 1 : j) * 16 + (fq & 2) * 4;
+                if (!row_ok || n >= N) continue;     // N is a multiple of head_dim: a group of 8 is in or out
+                const int head = n / HD, c = n - head * HD;
                 if (head < Hq) {
-                    *reinterpret_cast<uint2*>(q_out + ((size_t)m * Hq + head) * HD + c) = pk;
+                    *reinterpret_cast<uint4*>(q_out + ((size_t)m * Hq + head) * HD + c) = pk;
                 } else {
                     const bool is_k = head < Hq + Hkv;
                     const int kh = is_k ? head - Hq : head - Hq - Hkv;
                     TO* dst = is_k ? k_out : v_out;
-                    if (dst) *reinterpret_cast<uint2*>(dst + ((size_t)m * Hkv + kh) * HD + c) = pk;
+                    if (dst) *reinterpret_cast<uint4*>(dst + ((size_t)m * Hkv + kh) * HD + c) = pk;
                     if (prow)
-                        *reinterpret_cast<uint2*>(prow + (is_k ? 0 : (size_t)Hkv * head_stride) + kh * head_stride + c) = pk;
+                        *reinterpret_cast<uint4*>(prow + (is_k ? 0 : (size_t)Hkv * head_stride) + kh * head_stride + c) = pk;
                 }
             }
         }
