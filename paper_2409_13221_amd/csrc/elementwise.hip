@@ -62,7 +62,9 @@ template <> __device__ __forceinline__ void store4<f16_t>(f16_t* p, float4 v) {
     *reinterpret_cast<h4*>(p) = r;
 }
 
-template <typename T>
+// NS >= 0: exactly NS partial planes, all of them requested back to back (the usual counts are
+// instantiated); NS < 0: `nsplit` planes in a loop.  Either way the planes are added in order.
+template <typename T, int NS>
 __global__ __launch_bounds__(1024) void k_rmsnorm(float* __restrict__ h, const float* __restrict__ part,
                                                   int nsplit, size_t sstride,
                                                   const int* __restrict__ row_idx,
@@ -72,22 +74,29 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(float* __restrict__ h, const f
     const int r = blockIdx.x;
     const int src = row_idx ? row_idx[r] : r;
     float* hrow = h + (size_t)src * d;
-    float4 v[kRmsMaxIter];
+    float4 v[kRmsMaxIter], gg[kRmsMaxIter];
     float ss = 0.f;
 #pragma unroll
     for (int it = 0; it < kRmsMaxIter; ++it) {
         const int i = (it * blockDim.x + threadIdx.x) * 4;
-        v[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+        v[it] = gg[it] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (i < d) {
-            float4 p[kMaxPlanes];
             const float* pp = part + (size_t)src * d + i;
-#pragma unroll
-            for (int s = 0; s < kMaxPlanes; ++s)
-                p[s] = s < nsplit ? *reinterpret_cast<const float4*>(pp + s * sstride)
-                                  : make_float4(0.f, 0.f, 0.f, 0.f);
             float4 a = *reinterpret_cast<const float4*>(hrow + i);
+            if constexpr (NS >= 0) {
+                float4 p[NS > 0 ? NS : 1];
 #pragma unroll
-            for (int s = 0; s < kMaxPlanes; ++s) { a.x += p[s].x; a.y += p[s].y; a.z += p[s].z; a.w += p[s].w; }
+                for (int s = 0; s < NS; ++s) p[s] = *reinterpret_cast<const float4*>(pp + s * sstride);
+                gg[it] = *reinterpret_cast<const float4*>(g + i);      // in flight with the planes
+#pragma unroll
+                for (int s = 0; s < NS; ++s) { a.x += p[s].x; a.y += p[s].y; a.z += p[s].z; a.w += p[s].w; }
+            } else {
+                gg[it] = *reinterpret_cast<const float4*>(g + i);
+                for (int s = 0; s < nsplit; ++s) {
+                    const float4 q = *reinterpret_cast<const float4*>(pp + s * sstride);
+                    a.x += q.x; a.y += q.y; a.z += q.z; a.w += q.w;
+                }
+            }
             if (nsplit > 0 && !row_idx) *reinterpret_cast<float4*>(hrow + i) = a;
             v[it] = a;
             ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
@@ -98,30 +107,43 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(float* __restrict__ h, const f
 #pragma unroll
     for (int it = 0; it < kRmsMaxIter; ++it) {
         const int i = (it * blockDim.x + threadIdx.x) * 4;
-        if (i < d) {
-            const float4 gg = *reinterpret_cast<const float4*>(g + i);
+        if (i < d)
             store4<T>(xn + (size_t)r * d + i,
-                      make_float4(v[it].x * inv * gg.x, v[it].y * inv * gg.y, v[it].z * inv * gg.z,
-                                  v[it].w * inv * gg.w));
-        }
+                      make_float4(v[it].x * inv * gg[it].x, v[it].y * inv * gg[it].y, v[it].z * inv * gg[it].z,
+                                  v[it].w * inv * gg[it].w));
     }
+}
+
+template <typename T>
+static hipError_t rmsnorm_launch(hipStream_t st, float* h, const float* part, int nsplit, size_t sstride,
+                                 const int* row_idx, const float* g, T* xn, int rows, int threads, int d, float eps) {
+#define RLHF_RMS(NS) k_rmsnorm<T, NS><<<rows, threads, 0, st>>>(h, part, nsplit, sstride, row_idx, g, xn, d, eps)
+    switch (nsplit) {
+        case 0: RLHF_RMS(0); break;
+        case 1: RLHF_RMS(1); break;
+        case 2: RLHF_RMS(2); break;
+        case 3: RLHF_RMS(3); break;
+        case 4: RLHF_RMS(4); break;
+        case 6: RLHF_RMS(6); break;
+        case 8: RLHF_RMS(8); break;
+        case 16: RLHF_RMS(16); break;
+        default: RLHF_RMS(-1); break;
+    }
+#undef RLHF_RMS
+    return hipGetLastError();
 }
 
 hipError_t launch_rmsnorm(hipStream_t st, int adt, float* h, const float* part, int nsplit,
                           size_t sstride, const int* row_idx, const float* g, void* xn, int rows,
                           int d, float eps) {
     if (rows <= 0) return hipSuccess;
-    if (d > 1024 * 4 * kRmsMaxIter || d % 8 || nsplit > kMaxPlanes) return hipErrorInvalidValue;
+    if (d > 1024 * 4 * kRmsMaxIter || d % 8 || nsplit < 0 || nsplit > kMaxPlanes) return hipErrorInvalidValue;
     const int quads = d / 4;
     const int iters = (quads + 1023) / 1024;
     const int threads = ((quads + iters - 1) / iters + 63) / 64 * 64;
-    if (adt == kBF16)
-        k_rmsnorm<bf16_t><<<rows, threads, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (bf16_t*)xn, d, eps);
-    else if (adt == kF16)
-        k_rmsnorm<f16_t><<<rows, threads, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (f16_t*)xn, d, eps);
-    else
-        k_rmsnorm<float><<<rows, threads, 0, st>>>(h, part, nsplit, sstride, row_idx, g, (float*)xn, d, eps);
-    return hipGetLastError();
+    if (adt == kBF16) return rmsnorm_launch<bf16_t>(st, h, part, nsplit, sstride, row_idx, g, (bf16_t*)xn, rows, threads, d, eps);
+    if (adt == kF16) return rmsnorm_launch<f16_t>(st, h, part, nsplit, sstride, row_idx, g, (f16_t*)xn, rows, threads, d, eps);
+    return rmsnorm_launch<float>(st, h, part, nsplit, sstride, row_idx, g, (float*)xn, rows, threads, d, eps);
 }
 
 // ---------------------------------------------------------------- rotary + KV-cache append
