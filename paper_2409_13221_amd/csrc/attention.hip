@@ -602,7 +602,6 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(const f16_t* __restrict__
     // V: a thread takes the same chunk of two neighbouring keys, so that the transposed store
     // writes whole 32-bit words [d][key pair]; the 32 pairs of a half wave land in 32 different
     // banks and the other half wave (next chunk: 8 d rows = 288 words further) in the other 32.
-    constexpr int VP_IT = LD_IT / 2;
     static_assert(LD_IT % 2 == 0 && kFaVStride % 2 == 0, "V is stored in key pairs");
     static_assert(LD_IT == 2 || LD_IT == 4, "64 keys x 64 or 128 dims over 256 threads");
     uint4 rk0, rk1, rk2 = make_uint4(0, 0, 0, 0), rk3 = rk2, rva0, rvb0, rva1 = rk2, rvb1 = rk2;
