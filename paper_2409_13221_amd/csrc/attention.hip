@@ -15,7 +15,7 @@
 // Prefill / scoring of float models uses the same inner loop over 16-token tiles of contiguous
 // K/V (one workgroup per query row and KV head); bf16 models use the MFMA kernel at the end of
 // this file.
-#include "common.cuh"
+#include "common.h"
 #include "kernels.h"
 
 namespace rlhf {

@@ -2,7 +2,7 @@
 // with the residual add of split-K partials), rotary + KV-cache append, SwiGLU, the greedy
 // pick / log-softmax gather over the vocabulary, and the value / reward head.
 // All are HBM-bound; each reads its input once and writes its output once.
-#include "common.cuh"
+#include "common.h"
 #include "kernels.h"
 
 namespace rlhf {

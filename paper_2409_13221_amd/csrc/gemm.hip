@@ -12,7 +12,7 @@
 // keeps the result deterministic (no float atomics).
 //
 // fp32: a plain LDS-tiled kernel for the float configuration (small model; not tuned).
-#include "common.cuh"
+#include "common.h"
 #include "kernels.h"
 #include <type_traits>
 
