@@ -62,6 +62,20 @@ int rlhf_op_paged_decode_attention(int dtype, const void* q, const void* pool, c
                                    int nsplit, int n_layers, int n_q_heads, int n_kv_heads, int head_dim,
                                    void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same decode attention with the split-KV partials
+ * kept in a scratch array built into the library instead of caller-supplied part_acc / part_ml.
+ * The call allocates nothing.  Limits: rows * n_q_heads * nsplit <= 16384 and head_dim <= 128
+ * (the scratch is 16384 * 130 floats = 8.1 MiB per GPU, held until the process ends); beyond them
+ * RLHF_EINVAL, with the reason available from rlhf_last_error(NULL).  All calls on one GPU share
+ * that scratch: two such calls whose work overlaps in time on one GPU (different streams or
+ * threads) race; calls ordered on one stream are safe.  Same kernels, same results as
+ * rlhf_op_paged_decode_attention for the same nsplit. */
+int rlhf_op_paged_decode_attention_noalloc(int dtype, const void* q, const void* pool, const int32_t* page_table,
+                                           int pt_stride, const int32_t* row_sample, const int32_t* ctx_len,
+                                           void* out, int rows, int layer, int nsplit, int n_layers,
+                                           int n_q_heads, int n_kv_heads, int head_dim, void* stream);
+
 /* Packed variable-length causal attention of the prefill / inference forward (Section 2.1):
  * float32 q [T, n_q_heads*head_dim], k, v [T, n_kv_heads*head_dim]; row r belongs to the
  * sequence that starts at row row_start[r] and is its row_pos[r]-th token.  out is IEEE half

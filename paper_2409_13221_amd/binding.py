@@ -122,6 +122,7 @@ def lib() -> C.CDLL:
         L.rlhf_op_gemm_nsplit.argtypes = [C.c_int] * 5
         L.rlhf_op_gemm.argtypes = [C.c_int, C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp]
         L.rlhf_op_paged_decode_attention.argtypes = [C.c_int, vp, vp, vp, C.c_int, vp, vp, vp, vp, vp] + [C.c_int] * 7 + [vp]
+        L.rlhf_op_paged_decode_attention_noalloc.argtypes = [C.c_int, vp, vp, vp, C.c_int, vp, vp, vp] + [C.c_int] * 7 + [vp]
         L.rlhf_op_varlen_attention.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp] + [C.c_int] * 4 + [vp]
         L.rlhf_op_flash_attention.argtypes = [vp] * 7 + [C.c_int] * 5 + [vp]
         L.rlhf_op_gemm_swiglu.argtypes = [C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp]
@@ -130,6 +131,7 @@ def lib() -> C.CDLL:
                      "rlhf_migrate", "rlhf_score", "rlhf_run_stage", "rlhf_get_results", "rlhf_debug_snapshot", "rlhf_sync",
                      "rlhf_profile_begin", "rlhf_profile_end", "rlhf_compute_gae",
                      "rlhf_op_gemm_nsplit", "rlhf_op_gemm", "rlhf_op_paged_decode_attention",
+                     "rlhf_op_paged_decode_attention_noalloc",
                      "rlhf_op_varlen_attention", "rlhf_op_flash_attention", "rlhf_op_gemm_swiglu",
                      "rlhf_op_gemm_rope"):
             getattr(L, name).restype = C.c_int
@@ -348,6 +350,18 @@ def rlhf_op_paged_decode_attention(q, pool, page_table, row_sample, ctx_len, out
         ctx_len.data_ptr(), out.data_ptr(), part_acc.data_ptr() if part_acc is not None else None,
         part_ml.data_ptr() if part_ml is not None else None, rows, layer, nsplit, n_layers, n_q_heads,
         n_kv_heads, head_dim, _stream_ptr()), "rlhf_op_paged_decode_attention")
+
+
+def rlhf_op_paged_decode_attention_noalloc(q, pool, page_table, row_sample, ctx_len, out, layer: int, nsplit: int,
+                                           n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int):
+    """The same attention with the library's built-in scratch for the split partials (no allocation)."""
+    import torch
+    rc = lib().rlhf_op_paged_decode_attention_noalloc(
+        2 if q.dtype == torch.float16 else _dt(q), q.data_ptr(), pool.data_ptr(), page_table.data_ptr(),
+        page_table.shape[1], row_sample.data_ptr(), ctx_len.data_ptr(), out.data_ptr(), q.shape[0], layer, nsplit,
+        n_layers, n_q_heads, n_kv_heads, head_dim, _stream_ptr())
+    if rc != RLHF_OK:
+        raise RlhfError(rc, lib().rlhf_last_error(None).decode())
 
 
 def rlhf_op_varlen_attention(q, k, v, row_start, row_pos, out, n_q_heads: int, n_kv_heads: int, head_dim: int):

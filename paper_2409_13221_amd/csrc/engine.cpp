@@ -399,6 +399,10 @@ int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
 
 extern "C" const char* rlhf_last_error(const rlhf_ctx* ctx) { return ctx ? ctx->err : g_create_error; }
 
+// Message of a failed call that has no context (rlhf_create, the kernel-level entry points);
+// read back with rlhf_last_error(NULL) on the same thread.
+void rlhf::set_global_error(const char* msg) { snprintf(g_create_error, sizeof g_create_error, "%s", msg); }
+
 extern "C" void rlhf_destroy(rlhf_ctx* c) {
     if (!c) return;
     for (hipStream_t st : {c->sd_full, c->ss_full, c->sd_part, c->ss_part})

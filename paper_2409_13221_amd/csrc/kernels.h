@@ -119,4 +119,7 @@ hipError_t launch_flash_attn(hipStream_t st, const void* q, const void* k, const
 
 size_t pool_page_elems(const Dims& dm);  // elements of one page over all layers
 
+// Error text of a call without a context; rlhf_last_error(NULL) returns it (per thread).
+void set_global_error(const char* msg);
+
 }  // namespace rlhf

@@ -3,10 +3,47 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "../../include/rlhf.h"
 #include "kernels.h"
 
 using namespace rlhf;
+
+// Split-KV partials of rlhf_op_paged_decode_attention_noalloc: per (row, query head, split) one
+// float accumulator of up to 128 dims, then the (max, sum) pairs.  One copy per GPU, held until
+// the process ends; its device address is looked up once per device.
+constexpr size_t kNoAllocSlots = 16384;
+constexpr size_t kNoAllocMaxHd = 128;
+static __device__ __align__(256) float scratch[kNoAllocSlots * (kNoAllocMaxHd + 2)];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+float* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (the array's name is only a host-side
+// handle; every GPU has its own copy at its own address).
+int scratch_of_current_device(float** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        set_global_error("rlhf_op_paged_decode_attention_noalloc: cannot identify the current device");
+        return RLHF_EDEVICE;
+    }
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            set_global_error("rlhf_op_paged_decode_attention_noalloc: hipGetSymbolAddress failed");
+            return RLHF_EDEVICE;
+        }
+        g_scratch_ptr[dev] = (float*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return RLHF_OK;
+}
+}  // namespace
 
 static int status_of(hipError_t e) {
     if (e == hipSuccess) return RLHF_OK;
@@ -42,6 +79,35 @@ extern "C" int rlhf_op_paged_decode_attention(int dtype, const void* q, const vo
     return status_of(launch_decode_attn((hipStream_t)stream, dt, q, pool,
                                         page_table, pt_stride, row_sample, ctx_len, out, part_acc, part_ml,
                                         rows, layer, nsplit, dm));
+}
+
+extern "C" int rlhf_op_paged_decode_attention_noalloc(int dtype, const void* q, const void* pool,
+                                                      const int32_t* page_table, int pt_stride,
+                                                      const int32_t* row_sample, const int32_t* ctx_len,
+                                                      void* out, int rows, int layer, int nsplit, int n_layers,
+                                                      int n_q_heads, int n_kv_heads, int head_dim, void* stream) {
+    if (!q || !pool || !page_table || !row_sample || !ctx_len || !out || rows < 0 || nsplit < 1 ||
+        layer < 0 || layer >= n_layers || n_kv_heads <= 0 || n_q_heads <= 0 || n_q_heads % n_kv_heads) {
+        set_global_error("rlhf_op_paged_decode_attention_noalloc: bad argument");
+        return RLHF_EINVAL;
+    }
+    const size_t slots = (size_t)rows * n_q_heads * nsplit;
+    if (head_dim <= 0 || (size_t)head_dim > kNoAllocMaxHd || slots > kNoAllocSlots) {
+        set_global_error("rlhf_op_paged_decode_attention_noalloc: rows * n_q_heads * nsplit must not exceed 16384 "
+                         "and head_dim must not exceed 128 (the size of the built-in scratch)");
+        return RLHF_EINVAL;
+    }
+    float* sc = nullptr;
+    const int rc = scratch_of_current_device(&sc);
+    if (rc != RLHF_OK) return rc;
+    float* part_acc = sc;                                   // [slots][head_dim]
+    float* part_ml = sc + kNoAllocSlots * kNoAllocMaxHd;    // [slots][2]
+    Dims dm{n_layers, n_q_heads * head_dim, n_q_heads, n_kv_heads, head_dim, 0, 0, 16};
+    const int dt = dtype == 2 ? kF16 : dtype == RLHF_BF16 ? kBF16 : kF32;
+    const hipError_t e = launch_decode_attn((hipStream_t)stream, dt, q, pool, page_table, pt_stride, row_sample,
+                                            ctx_len, out, part_acc, part_ml, rows, layer, nsplit, dm);
+    if (e != hipSuccess) set_global_error("rlhf_op_paged_decode_attention_noalloc: unsupported shape or launch failure");
+    return status_of(e);
 }
 
 extern "C" int rlhf_op_varlen_attention(int out_half, const float* q, const float* k, const float* v,
