@@ -26,11 +26,14 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
+# what the arithmetic actually is: bf16 models keep bf16 weights, feed IEEE-half activations to
+# v_mfma_f32_16x16x32_f16 (same peak as bf16) and accumulate in float; the KV cache is half
+ARITH = {"bf16": "bf16 weights x f16 activations, f32 accumulate (f16 KV cache)", "fp32": "f32"}
 ROLE_MASK_DEFAULT = 0b1110      # Reference, Critic, Reward; Actor log-probs come from decoding
 
 # bounded oracle sample per workload: (samples, output-length cap, oracle dtype)
-CPU_SAMPLE = {"tiny": (8, 64, "float64"), "gpt2s": (4, 24, "float64"), "7b": (1, 6, "float32"),
-              "13b": (1, 4, "float32"), "70b_slice": (1, 6, "float32")}
+CPU_SAMPLE = {"tiny": (8, 64, "float64"), "gpt2s": (4, 24, "float64"), "7b": (4, 32, "float32"),
+              "13b": (1, 8, "float32"), "70b_slice": (1, 8, "float32")}
 
 
 def log(*a):
@@ -131,19 +134,38 @@ def cpu_baseline(cfg, weights):
                       f"scored tokens in {elapsed:.1f}s, numpy {dt}, full depth"}
 
 
-def roofline_of(prof, dtype, traffic):
-    est = {k: (v["sampled_ms"] / v["sampled"] * v["launches"] if v["sampled"] else 0.0) for k, v in prof.items()}
-    dom = max(est, key=est.get)
-    v = prof[dom]
-    if dom in ("gemm_decode", "attn_decode"):
-        ach = v["sampled_bytes"] / (v["sampled_ms"] * 1e-3) / 1e9
-        peak, unit, bound = HBM_PEAK_GBS, "GB/s", "hbm"
-    else:
-        ach = v["sampled_flops"] / (v["sampled_ms"] * 1e-3) / 1e12
-        peak, unit, bound = MFMA_PEAK_TFLOPS[dtype], "TFLOP/s", "mfma"
-    return {"bound": bound, "kernel": dom, "achieved": round(ach, 2), "peak": peak, "unit": unit,
-            "frac": round(ach / peak, 4), "traffic": traffic,
-            "avg_launch_us": round(v["sampled_ms"] / v["sampled"] * 1e3, 2), "launches": v["launches"]}, est
+CLASS_BOUND = {"gemm_decode": "hbm", "attn_decode": "hbm", "gemm_batch": "mfma", "attn_batch": "mfma"}
+
+
+def rooflines(prof, dtype, steps):
+    """One roofline object per kernel class.  Clock: HIP events on the stream the kernel runs on,
+    around every sample_every-th launch of the class over ALL timed stages (rlhf_profile_*); the
+    median bracket of an empty kernel (launch + signalling latency, measured on the same stream when
+    profiling starts) is taken off each bracket, which is what makes the average comparable with
+    the kernel durations rocprofv3 reports.  achieved = algorithmic bytes (or flops) of the sampled
+    launches / their corrected time."""
+    out = {}
+    for k, v in prof.items():
+        if not v["sampled"]:
+            continue
+        raw_ms = v["sampled_ms"]
+        ms = max(raw_ms - v["sampled"] * v["bracket_overhead_ms"], 1e-9)
+        if CLASS_BOUND[k] == "hbm":
+            ach, peak, unit = v["sampled_bytes"] / (ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = v["sampled_flops"] / (ms * 1e-3) / 1e12, MFMA_PEAK_TFLOPS[dtype], "TFLOP/s"
+        avg_us = ms / v["sampled"] * 1e3
+        out[k] = {"bound": CLASS_BOUND[k], "kernel": k, "achieved": round(ach, 2), "peak": peak, "unit": unit,
+                  "frac": round(ach / peak, 4), "traffic": None,
+                  "avg_launch_us": round(avg_us, 2), "avg_bracket_us": round(raw_ms / v["sampled"] * 1e3, 2),
+                  "bracket_overhead_us": round(v["bracket_overhead_ms"] * 1e3, 2),
+                  "launches_per_stage": int(v["launches"] // steps), "sampled": int(v["sampled"]),
+                  "dropped": int(v["dropped"]),
+                  "est_ms_per_stage": round(avg_us * v["launches"] / steps / 1e3, 1),
+                  "alg_bytes_per_stage": v["total_bytes"] / steps, "alg_flops_per_stage": v["total_flops"] / steps,
+                  "GBps": round(v["sampled_bytes"] / (ms * 1e-3) / 1e9, 1),
+                  "TFLOPs": round(v["sampled_flops"] / (ms * 1e-3) / 1e12, 2)}
+    return out
 
 
 def micro(args):
@@ -394,27 +416,25 @@ def main():
     G, S = int(st.generated_tokens), int(st.scored_tokens)
     value = (G + S) / (ms_per_step * 1e-3)
 
-    # HBM-side bytes per launch of the dominant kernel class, from the committed rocprofv3 counter summary
-    # (FETCH_SIZE and WRITE_SIZE runs, each scaled by a 1 GiB copy); null where no such run exists
-    roof, est = roofline_of(prof, cfg.model.dtype, None)
+    # one roofline object per kernel class; `roofline` is the class with the largest share of GPU time
+    roofs = rooflines(prof, cfg.model.dtype, args.steps)
+    for k, r in roofs.items():
+        if r["dropped"]:
+            log(f"[bench] WARNING: {r['dropped']} launches of {k} were due for timing but found no free event pair; "
+                f"raise --sample_every")
+    # HBM-side bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE and WRITE_SIZE runs
+    # over the kernel-level cases of --micro, each scaled by a 1 GiB copy): a per-kernel micro-case figure,
+    # not a counter run over this stage
     tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{cfg.name}.txt")
     if os.path.exists(tpath):
         for line in open(tpath):
             f = line.split()
-            if len(f) == 4 and f[0] == roof["kernel"]:
-                roof["traffic"] = float(f[1]) + float(f[2])
-                roof["traffic_detail"] = {"fetched_bytes": float(f[1]), "written_bytes": float(f[2]),
-                                          "algorithmic_bytes": float(f[3]),
-                                          "source": "profiles/gemm_7b_layer_shapes_hbm_traffic.md"}
-    kernels = {}
-    for k, v in prof.items():
-        if not v["sampled"]:
-            continue
-        sec = v["sampled_ms"] * 1e-3
-        kernels[k] = {"launches": v["launches"], "avg_us": round(v["sampled_ms"] / v["sampled"] * 1e3, 2),
-                      "est_total_ms": round(est[k] / args.steps, 1),
-                      "GBps": round(v["sampled_bytes"] / sec / 1e9, 1),
-                      "TFLOPs": round(v["sampled_flops"] / sec / 1e12, 2)}
+            if len(f) >= 4 and f[0] in roofs:
+                roofs[f[0]]["traffic"] = float(f[1]) + float(f[2])
+                roofs[f[0]]["traffic_detail"] = {"fetched_bytes": float(f[1]), "written_bytes": float(f[2]),
+                                                 "algorithmic_bytes": float(f[3]), "scope": "kernel-level micro cases",
+                                                 "source": f"profiles/hbm_traffic_{cfg.name}.txt"}
+    roof = max(roofs.values(), key=lambda r: r["est_ms_per_stage"]) if roofs else None
 
     # long-tail lens: steps with at most 20 % of the batch still active; decode-only steps
     lens = {}
@@ -432,12 +452,27 @@ def main():
                 "decode_stream_ms": round(st.decode_stream_ms, 1), "score_stream_ms": round(st.score_stream_ms, 1),
                 "generated_tokens": G, "scored_tokens": S, "scoring_batches": int(st.n_batches)}
 
+    # the serial plan (generate everything, then score) under the same conditions: profiler on, the same
+    # sampling stride; up to three runs, mean
     seq = None
-    if not args.no_sequential:
-        ms_seq, _, _ = run_stage(R, ctx, wl, max_new, False, args)
+    if not args.no_sequential and not args.sequential:
+        n_seq = min(args.steps, 3)
+        R.rlhf_profile_begin(ctx, args.sample_every)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n_seq):
+            ms_i, _, _ = run_stage(R, ctx, wl, max_new, False, args)
+            log(f"[bench] sequential generate-then-score {i}: {ms_i:.1f} ms")
+        torch.cuda.synchronize()
+        ms_seq = (time.perf_counter() - t0) * 1e3 / n_seq
+        prof_seq = R.rlhf_profile_end(ctx)
+        rs = rooflines(prof_seq, cfg.model.dtype, n_seq)
         seq = {"sequential_ms": round(ms_seq, 1), "fused_ms": round(ms_per_step, 1),
-               "speedup": round(ms_seq / ms_per_step, 3)}
-        log(f"[bench] sequential generate-then-score: {ms_seq:.1f} ms")
+               "speedup": round(ms_seq / ms_per_step, 3), "runs": {"fused": args.steps, "sequential": n_seq},
+               "profiler": "on in both, same stride",
+               "sequential_kernels": {k: {"avg_launch_us": r["avg_launch_us"], "achieved": r["achieved"],
+                                          "unit": r["unit"], "frac": r["frac"],
+                                          "est_ms_per_stage": r["est_ms_per_stage"]} for k, r in rs.items()}}
     R.rlhf_destroy(ctx)
 
     cpu = None
@@ -446,7 +481,7 @@ def main():
 
     out = {"metric": "gen+scored tokens/s per GPU (long-tail lens)", "value": round(value, 1), "unit": "tokens/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 2),
-           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.model.dtype,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": ARITH[cfg.model.dtype],
            "data": "synthetic",
            "config": {"workload": cfg.name, "n_samples": int(len(max_new)), "length_law": cfg.length_law,
                       "length_params": list(cfg.length_params), "length_cap": cfg.length_cap,
@@ -454,7 +489,10 @@ def main():
                       "corun_decode_cus": args.corun_decode_cus, "admission": args.admission,
                       "score_chunk_tokens": args.score_chunk_tokens, "R_t": args.R_t, "role_mask": args.role_mask,
                       "page_tokens": cfg.page_tokens},
-           "roofline": roof, "cpu_baseline": cpu, "fused_vs_sequential": seq, "kernels": kernels,
+           "roofline": roof, "cpu_baseline": cpu, "fused_vs_sequential": seq, "roofline_all": roofs,
+           "roofline_clock": "HIP events on the kernel's own stream around every "
+                             f"{args.sample_every}th launch of a class over all {args.steps} timed stages, minus the "
+                             "median bracket of an empty kernel",
            "long_tail": lens}
     print(json.dumps(out), flush=True)
 

@@ -37,7 +37,8 @@ enum rlhf_status {
     RLHF_EINVAL = -1,  /* bad argument, shape the kernels do not support, id out of range */
     RLHF_ENOMEM = -2,  /* KV pool cannot hold a sample's reservation; allocation failed    */
     RLHF_ESTATE = -3,  /* call out of order (e.g. scoring a sample still generating)       */
-    RLHF_EDEVICE = -4  /* a HIP call failed                                                */
+    RLHF_EDEVICE = -4, /* a HIP call failed                                                */
+    RLHF_ENONFINITE = -5 /* a result of the stage is not finite (rlhf_get_results)         */
 };
 
 /* The four models of Section 2.1 ("RLHF models"). */
@@ -128,7 +129,12 @@ typedef struct rlhf_step_info {
 typedef struct rlhf_stage_opts {
     int32_t fused;                 /* 1: score retired samples on the score stream while
                                       decoding goes on (Section 4); 0: generate everything,
-                                      then score (the serial plan of Figure 4, top)           */
+                                      then score (the serial plan of Figure 4, top); 2: the
+                                      library chooses: the serial plan when a decode step of this
+                                      model is bound by kernel launches rather than by streaming
+                                      its weights (small models, where a second stream has nothing
+                                      idle to fill), else the fused one; rlhf_stage_stats.fused_used
+                                      tells which                                               */
     int32_t R_t;                   /* Section 4.2 trigger: scoring is enabled once the number
                                       of samples still in generation is below R_t.  R_t >
                                       n_samples enables it from the first retirement          */
@@ -154,6 +160,7 @@ typedef struct rlhf_stage_stats {
     double score_stream_ms;        /* first to last work on the score stream (0 if none)      */
     int64_t decode_weight_bytes;   /* algorithmic bytes: weights read by all decode steps     */
     int64_t decode_kv_bytes;       /*   KV read + written by all decode steps                 */
+    int32_t fused_used;            /* the plan that ran: 1 fused, 0 serial                    */
 } rlhf_stage_stats;
 
 /* Stage outputs, in sample-id order.  Any pointer may be NULL to skip it. */
@@ -277,8 +284,12 @@ int rlhf_sync(rlhf_ctx* ctx);
  * runs on.  Classes: 0 = projections of the decode step (weight-streaming, HBM-bound regime of
  * Section 4.2), 1 = projections of prefill / scoring passes (Section 2.1 inference forward),
  * 2 = paged decode attention, 3 = packed causal attention.  Bytes and flops are algorithmic:
- * operands read once, results written once, 2 flops per multiply-add.  rlhf_profile_end drains
- * both streams and fills out[4]. */
+ * operands read once, results written once, 2 flops per multiply-add.  The event pairs are
+ * folded into the sums whenever rlhf_run_stage returns, so any number of stages may run between
+ * begin and end and each is sampled alike.  An event bracket measures from the end of the work
+ * queued before the launch on that stream to the end of the launch: with a second stream busy it
+ * includes the time the kernel shares the chip with the other stream's kernels.
+ * rlhf_profile_end drains both streams and fills out[4]. */
 typedef struct rlhf_kernel_profile {
     int64_t launches;              /* launches of the class between begin and end             */
     int64_t sampled;               /* of which were timed                                     */
@@ -287,6 +298,11 @@ typedef struct rlhf_kernel_profile {
     double sampled_flops;
     double total_bytes;            /* algorithmic bytes of all launches                       */
     double total_flops;
+    int64_t dropped;               /* launches due for timing that found every event pair of the
+                                      running stage in use (65536 per stage): raise sample_every */
+    double bracket_overhead_ms;    /* median event bracket of an EMPTY kernel on the decode stream,
+                                      measured by rlhf_profile_begin: launch and signalling latency
+                                      that every bracket contains besides its kernel's run time  */
 } rlhf_kernel_profile;
 int rlhf_profile_begin(rlhf_ctx* ctx, int32_t sample_every);
 int rlhf_profile_end(rlhf_ctx* ctx, rlhf_kernel_profile* out /* [4] */);

@@ -93,6 +93,67 @@ int rlhf_op_flash_attention(const void* q, const void* k, const void* v, const i
                             const int32_t* tile_q0, const int32_t* tile_len, void* out, int n_tiles,
                             int rows, int n_q_heads, int n_kv_heads, int head_dim, void* stream);
 
+/* ---- row-wise kernels of the decoder block and of the heads.  act_dtype is the element type of
+ * the 16-bit (or float) activations a kernel writes or reads: RLHF_FP32, RLHF_BF16, or 2 = IEEE
+ * half.  "nsplit / sstride": a float input given as nsplit partial planes, plane s at x + s *
+ * sstride elements (the split-K output of rlhf_op_gemm, summed in plane order by the consumer). */
+
+/* RMSNorm of a decoder block (the reading of "LLaMA", Section 7: y = x * rsqrt(mean(x^2) + eps) * g,
+ * statistics in float), fused with the residual add: v = h[src] + sum of the partial planes at
+ * row src; xn[r] = norm(v) * g.  row_idx == NULL: src = r and v is written back to h (the residual
+ * stream); otherwise src = row_idx[r] and h is left alone.  d a multiple of 8, at most 8192;
+ * nsplit in [0, 16] (0: no planes). */
+int rlhf_op_rmsnorm(int act_dtype, float* h, const float* part, int nsplit, int64_t sstride,
+                    const int32_t* row_idx, const float* g, void* xn, int rows, int d, float eps, void* stream);
+
+/* Rotary embedding and KV-cache append of decode steps and short passes: qkv [rows, (Hq + 2 Hkv)
+ * * hd] float planes; query and key heads are rotated by pos[r] (pair (i, i + hd/2); table float32
+ * [max position][hd/2][cos, sin]); q [rows, Hq*hd] and, if non-NULL, k, v [rows, Hkv*hd] are
+ * written in act_dtype, and k, v also to token slot kv_dst[r] = page*16 + offset of `layer` in
+ * the paged pool when pool != NULL (layout as in rlhf_op_paged_decode_attention). */
+int rlhf_op_rope_kv(int act_dtype, const float* qkv, int nsplit, int64_t sstride, const int32_t* pos,
+                    const int32_t* kv_dst, const float* table, void* q, void* k, void* v, void* pool,
+                    int layer, int rows, int n_layers, int n_q_heads, int n_kv_heads, int head_dim,
+                    void* stream);
+
+/* SwiGLU of decode steps: gu [rows, 2*ffn] float planes (gate columns, then up columns);
+ * act[r][c] = silu(gate) * up in act_dtype.  ffn a multiple of 8. */
+int rlhf_op_swiglu(int act_dtype, const float* gu, int nsplit, int64_t sstride, void* act, int rows, int ffn,
+                   void* stream);
+
+/* Greedy choice of the generation stage (Section 2.1; lowest id on ties) over float logit planes
+ * [rows, vocab]: token y = argmax (or forced[r] if forced != NULL and forced[r] >= 0) is written to
+ * tokens[tok_dst[r]] (and picked[r] if non-NULL) and log_softmax(logits[r])[y] to lp[lp_dst[r]].
+ * scratch: rlhf_op_pick_scratch_floats(rows) floats. */
+int64_t rlhf_op_pick_scratch_floats(int rows);
+int rlhf_op_pick(const float* logits, int nsplit, int64_t sstride, int rows, int vocab, const int32_t* forced,
+                 int32_t* tokens, const int32_t* tok_dst, float* lp, const int32_t* lp_dst, int32_t* picked,
+                 float* scratch, void* stream);
+
+/* Log-prob of given tokens (inference stage, Section 2.1): out[out_dst[r]] =
+ * log_softmax(logits[r])[tokens[target_idx[r]]]. */
+int rlhf_op_gather_lp(const float* logits, int nsplit, int64_t sstride, int rows, int vocab,
+                      const int32_t* tokens, const int32_t* target_idx, float* out, const int32_t* out_dst,
+                      void* stream);
+
+/* LM head of the inference stage fused with the log-softmax gather (Section 2.1: the Reference
+ * and Actor log-probabilities of the generated tokens), as the stage runs it for bf16 models: for
+ * row m of A [M, K] (IEEE half if act_half != 0, else bf16) and W_head bf16 [vocab, K],
+ *   out[out_dst[m]] = log_softmax(W_head A[m])[tokens[target_idx[m]]]
+ * without the [M, vocab] logits ever being written: the GEMM's epilogue keeps, per row and per 128
+ * vocabulary columns, the maximum and the sum of exponentials, and a merge kernel finishes.
+ * scratch: rlhf_op_lm_head_logprob_scratch_floats(M, vocab) floats.  K a multiple of 64. */
+int64_t rlhf_op_lm_head_logprob_scratch_floats(int M, int vocab);
+int rlhf_op_lm_head_logprob(int act_half, const void* A, const void* W_head, const int32_t* tokens,
+                            const int32_t* target_idx, float* out, const int32_t* out_dst, float* scratch, int M,
+                            int vocab, int K, void* stream);
+
+/* Value / reward head (Section 2.1: the Critic evaluates each action, the Reward model scores the
+ * sample): out[out_dst[r]] = <xn[r], w>, xn [rows, d] in act_dtype, w [d] in w_dtype (RLHF_FP32 or
+ * RLHF_BF16).  Supported pairs: (fp32, fp32), (fp32, bf16), (half, bf16), (bf16, bf16). */
+int rlhf_op_head_dot(int act_dtype, int w_dtype, const void* xn, const void* w, int rows, int d, float* out,
+                     const int32_t* out_dst, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

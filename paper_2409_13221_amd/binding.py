@@ -14,10 +14,10 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librlhf.so")
 
-RLHF_OK, RLHF_EINVAL, RLHF_ENOMEM, RLHF_ESTATE, RLHF_EDEVICE = 0, -1, -2, -3, -4
+RLHF_OK, RLHF_EINVAL, RLHF_ENOMEM, RLHF_ESTATE, RLHF_EDEVICE, RLHF_ENONFINITE = 0, -1, -2, -3, -4, -5
 RLHF_ACTOR, RLHF_REF, RLHF_CRITIC, RLHF_REWARD = 0, 1, 2, 3
 RLHF_FP32, RLHF_BF16 = 0, 1
-_STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "ESTATE", -4: "EDEVICE"}
+_STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "ESTATE", -4: "EDEVICE", -5: "ENONFINITE"}
 
 
 def RLHF_ROLE_BIT(role: int) -> int:
@@ -65,7 +65,7 @@ class rlhf_stage_stats(C.Structure):
     _fields_ = [("n_steps", C.c_int32), ("n_batches", C.c_int32), ("generated_tokens", C.c_int64),
                 ("scored_tokens", C.c_int64), ("prefill_tokens", C.c_int64), ("wall_ms", C.c_double),
                 ("decode_stream_ms", C.c_double), ("score_stream_ms", C.c_double),
-                ("decode_weight_bytes", C.c_int64), ("decode_kv_bytes", C.c_int64)]
+                ("decode_weight_bytes", C.c_int64), ("decode_kv_bytes", C.c_int64), ("fused_used", C.c_int32)]
 
 
 class rlhf_results(C.Structure):
@@ -84,7 +84,7 @@ class rlhf_snapshot(C.Structure):
 class rlhf_kernel_profile(C.Structure):
     _fields_ = [("launches", C.c_int64), ("sampled", C.c_int64), ("sampled_ms", C.c_double),
                 ("sampled_bytes", C.c_double), ("sampled_flops", C.c_double), ("total_bytes", C.c_double),
-                ("total_flops", C.c_double)]
+                ("total_flops", C.c_double), ("dropped", C.c_int64), ("bracket_overhead_ms", C.c_double)]
 
 
 KERNEL_CLASSES = ("gemm_decode", "gemm_batch", "attn_decode", "attn_batch")
@@ -127,6 +127,22 @@ def lib() -> C.CDLL:
         L.rlhf_op_flash_attention.argtypes = [vp] * 7 + [C.c_int] * 5 + [vp]
         L.rlhf_op_gemm_swiglu.argtypes = [C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp]
         L.rlhf_op_gemm_rope.argtypes = [C.c_int] + [vp] * 9 + [C.c_int] * 7 + [vp]
+        f32 = C.c_float
+        L.rlhf_op_rmsnorm.argtypes = [C.c_int, vp, vp, C.c_int, i64, vp, vp, vp, C.c_int, C.c_int, f32, vp]
+        L.rlhf_op_rope_kv.argtypes = [C.c_int, vp, C.c_int, i64] + [vp] * 7 + [C.c_int] * 6 + [vp]
+        L.rlhf_op_swiglu.argtypes = [C.c_int, vp, C.c_int, i64, vp, C.c_int, C.c_int, vp]
+        L.rlhf_op_pick_scratch_floats.argtypes = [C.c_int]
+        L.rlhf_op_pick_scratch_floats.restype = i64
+        L.rlhf_op_pick.argtypes = [vp, C.c_int, i64, C.c_int, C.c_int] + [vp] * 8
+        L.rlhf_op_gather_lp.argtypes = [vp, C.c_int, i64, C.c_int, C.c_int] + [vp] * 5
+        L.rlhf_op_head_dot.argtypes = [C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp, vp, vp]
+        L.rlhf_op_lm_head_logprob_scratch_floats.argtypes = [C.c_int, C.c_int]
+        L.rlhf_op_lm_head_logprob_scratch_floats.restype = i64
+        L.rlhf_op_lm_head_logprob.argtypes = [C.c_int] + [vp] * 7 + [C.c_int] * 3 + [vp]
+        L.rlhf_op_lm_head_logprob.restype = C.c_int
+        for name in ("rlhf_op_rmsnorm", "rlhf_op_rope_kv", "rlhf_op_swiglu", "rlhf_op_pick", "rlhf_op_gather_lp",
+                     "rlhf_op_head_dot"):
+            getattr(L, name).restype = C.c_int
         for name in ("rlhf_create", "rlhf_load_weights", "rlhf_submit", "rlhf_generate_step", "rlhf_retire",
                      "rlhf_migrate", "rlhf_score", "rlhf_run_stage", "rlhf_get_results", "rlhf_debug_snapshot", "rlhf_sync",
                      "rlhf_profile_begin", "rlhf_profile_end", "rlhf_compute_gae",
@@ -221,8 +237,9 @@ def rlhf_score(ctx, sample_ids: Sequence[int], role_mask: int, on_score_stream: 
 
 def rlhf_run_stage(ctx, fused: bool, R_t: int, score_chunk_tokens: int, role_mask: int,
                    trace_cap: int = 0, trace_time: bool = False):
-    """Returns (rlhf_stage_stats, trace dict or None)."""
-    o = rlhf_stage_opts(int(fused), R_t, score_chunk_tokens, role_mask, None, None, None, None, None, 0)
+    """fused: True, False, or "auto" (the library picks the plan).  Returns (rlhf_stage_stats, trace dict or None)."""
+    o = rlhf_stage_opts(2 if fused == "auto" else int(fused), R_t, score_chunk_tokens, role_mask, None, None, None,
+                        None, None, 0)
     tr = None
     if trace_cap > 0:
         tr = {"active": np.zeros(trace_cap, np.int32), "decoded": np.zeros(trace_cap, np.int32),
@@ -425,3 +442,91 @@ def rlhf_op_gemm_rope(A, W_qkv, pos, table, q, k=None, v=None, pool=None, kv_dst
                                       ptr(kv_dst), table.data_ptr(), q.data_ptr(), ptr(k), ptr(v), ptr(pool), M, K,
                                       layer, n_layers, n_q_heads, n_kv_heads, head_dim, _stream_ptr()),
               "rlhf_op_gemm_rope")
+
+
+def _act_code(t) -> int:
+    import torch
+    return {torch.float32: RLHF_FP32, torch.bfloat16: RLHF_BF16, torch.float16: 2}[t.dtype]
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def rlhf_op_rmsnorm(h, part, g, xn, eps: float, row_idx=None) -> None:
+    """h float32 [*, d] (updated in place when row_idx is None); part float32 [nsplit, rows_h, d] or None;
+    g float32 [d]; xn [rows, d] float32 / bfloat16 / float16."""
+    rows, d = xn.shape
+    nsplit = 0 if part is None else part.shape[0]
+    sstride = 0 if part is None else part.stride(0)
+    _op_check(lib().rlhf_op_rmsnorm(_act_code(xn), h.data_ptr(), _ptr(part), nsplit, sstride, _ptr(row_idx),
+                                    g.data_ptr(), xn.data_ptr(), rows, d, eps, _stream_ptr()), "rlhf_op_rmsnorm")
+
+
+def rlhf_op_rope_kv(qkv, pos, table, q, k=None, v=None, pool=None, kv_dst=None, layer=0, n_layers=1, n_q_heads=1,
+                    n_kv_heads=1, head_dim=64) -> None:
+    """qkv float32 [nsplit, rows, (Hq+2Hkv)*hd]; q, k, v, pool of one activation dtype."""
+    nsplit, rows, width = qkv.shape
+    assert width == (n_q_heads + 2 * n_kv_heads) * head_dim and tuple(q.shape) == (rows, n_q_heads * head_dim)
+    assert int(pos.max()) < table.shape[0] and int(pos.min()) >= 0
+    if pool is not None:
+        page_elems = n_layers * 2 * n_kv_heads * 16 * head_dim
+        assert 0 <= int(kv_dst.min()) and int(kv_dst.max()) < pool.numel() // page_elems * 16
+    _op_check(lib().rlhf_op_rope_kv(_act_code(q), qkv.data_ptr(), nsplit, qkv.stride(0), pos.data_ptr(), _ptr(kv_dst),
+                                    table.data_ptr(), q.data_ptr(), _ptr(k), _ptr(v), _ptr(pool), layer, rows,
+                                    n_layers, n_q_heads, n_kv_heads, head_dim, _stream_ptr()), "rlhf_op_rope_kv")
+
+
+def rlhf_op_swiglu(gu, act) -> None:
+    """gu float32 [nsplit, rows, 2*ffn]; act [rows, ffn]."""
+    nsplit, rows, two_f = gu.shape
+    assert tuple(act.shape) == (rows, two_f // 2)
+    _op_check(lib().rlhf_op_swiglu(_act_code(act), gu.data_ptr(), nsplit, gu.stride(0), act.data_ptr(), rows,
+                                   two_f // 2, _stream_ptr()), "rlhf_op_swiglu")
+
+
+def rlhf_op_pick(logits, forced, tokens, tok_dst, lp, lp_dst, picked=None) -> None:
+    """logits float32 [nsplit, rows, vocab]; forced int32 [rows] or None; tokens int32 buffer indexed by
+    tok_dst [rows]; lp float32 buffer indexed by lp_dst [rows]."""
+    import torch
+    nsplit, rows, vocab = logits.shape
+    assert int(tok_dst.max()) < tokens.numel() and int(lp_dst.max()) < lp.numel()
+    scratch = torch.empty(max(1, lib().rlhf_op_pick_scratch_floats(rows)), device=logits.device)
+    _op_check(lib().rlhf_op_pick(logits.data_ptr(), nsplit, logits.stride(0), rows, vocab, _ptr(forced),
+                                 tokens.data_ptr(), tok_dst.data_ptr(), lp.data_ptr(), lp_dst.data_ptr(),
+                                 _ptr(picked), scratch.data_ptr(), _stream_ptr()), "rlhf_op_pick")
+    torch.cuda.current_stream().synchronize()          # scratch is released on return
+
+
+def rlhf_op_gather_lp(logits, tokens, target_idx, out, out_dst) -> None:
+    nsplit, rows, vocab = logits.shape
+    assert int(target_idx.max()) < tokens.numel() and int(out_dst.max()) < out.numel()
+    _op_check(lib().rlhf_op_gather_lp(logits.data_ptr(), nsplit, logits.stride(0), rows, vocab, tokens.data_ptr(),
+                                      target_idx.data_ptr(), out.data_ptr(), out_dst.data_ptr(), _stream_ptr()),
+              "rlhf_op_gather_lp")
+
+
+def rlhf_op_head_dot(xn, w, out, out_dst) -> None:
+    rows, d = xn.shape
+    assert w.numel() == d and int(out_dst.max()) < out.numel()
+    _op_check(lib().rlhf_op_head_dot(_act_code(xn), _dt(w), xn.data_ptr(), w.data_ptr(), rows, d, out.data_ptr(),
+                                     out_dst.data_ptr(), _stream_ptr()), "rlhf_op_head_dot")
+
+
+def rlhf_op_lm_head_logprob(A, W_head, tokens, target_idx, out, out_dst, scratch=None):
+    """A [M, K] float16 / bfloat16, W_head bfloat16 [vocab, K]; out[out_dst[m]] = log-prob of token
+    tokens[target_idx[m]] under row m's logits.  Returns the scratch tensor (keep it alive until the
+    stream has run)."""
+    import torch
+    M, K = A.shape
+    vocab = W_head.shape[0]
+    assert W_head.dtype == torch.bfloat16 and W_head.shape[1] == K and A.is_contiguous() and W_head.is_contiguous()
+    assert int(target_idx.max()) < tokens.numel() and int(out_dst.max()) < out.numel()
+    need = lib().rlhf_op_lm_head_logprob_scratch_floats(M, vocab)
+    if scratch is None:
+        scratch = torch.empty(max(need, 1), device=A.device)
+    assert scratch.numel() >= need
+    _op_check(lib().rlhf_op_lm_head_logprob(int(A.dtype == torch.float16), A.data_ptr(), W_head.data_ptr(),
+                                            tokens.data_ptr(), target_idx.data_ptr(), out.data_ptr(), out_dst.data_ptr(),
+                                            scratch.data_ptr(), M, vocab, K, _stream_ptr()), "rlhf_op_lm_head_logprob")
+    return scratch

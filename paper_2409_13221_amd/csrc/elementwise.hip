@@ -356,7 +356,7 @@ __global__ __launch_bounds__(64) void k_pick_stage2(const float* __restrict__ lo
                                                     const int* __restrict__ tok_dst,
                                                     float* __restrict__ lp,
                                                     const int* __restrict__ lp_dst,
-                                                    int* __restrict__ picked) {
+                                                    int* __restrict__ picked, int* __restrict__ nonfinite) {
     const int r = blockIdx.x, lane = threadIdx.x;
     const float* sc = scratch + (size_t)r * kPickChunks * 3;
     float mx = -INFINITY, se = 0.f;
@@ -375,22 +375,25 @@ __global__ __launch_bounds__(64) void k_pick_stage2(const float* __restrict__ lo
         int y = barg;
         const int f = forced ? forced[r] : -1;
         if (f >= 0 && f < vocab) y = f;
+        if ((unsigned)y >= (unsigned)vocab) y = 0;   // a row of NaNs has no maximum: stay in bounds, the log-prob below flags it
         const float z = logit_at(logits + (size_t)r * vocab, nsplit, sstride, y);
         tokens[tok_dst[r]] = y;
-        lp[lp_dst[r]] = z - best - logf(tot);
+        const float v = z - best - logf(tot);
+        lp[lp_dst[r]] = v;
         if (picked) picked[r] = y;
+        if (nonfinite && !isfinite(v)) *nonfinite = 1;
     }
 }
 
 hipError_t launch_pick(hipStream_t st, const float* logits, int nsplit, size_t sstride, int rows,
                        int vocab, const int* forced, int* tokens, const int* tok_dst, float* lp,
-                       const int* lp_dst, int* picked, float* scratch) {
+                       const int* lp_dst, int* picked, float* scratch, int* nonfinite) {
     if (rows <= 0) return hipSuccess;
     k_pick_stage1<<<dim3(rows, kPickChunks), 256, 0, st>>>(logits, nsplit, sstride, vocab, scratch);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     k_pick_stage2<<<rows, 64, 0, st>>>(logits, nsplit, sstride, vocab, scratch, forced, tokens, tok_dst, lp,
-                                       lp_dst, picked);
+                                       lp_dst, picked, nonfinite);
     return hipGetLastError();
 }
 
@@ -401,7 +404,7 @@ __global__ __launch_bounds__(256) void k_gather_lp(const float* __restrict__ log
                                                    const int* __restrict__ tokens,
                                                    const int* __restrict__ target_idx,
                                                    float* __restrict__ out,
-                                                   const int* __restrict__ out_dst) {
+                                                   const int* __restrict__ out_dst, int* __restrict__ nonfinite) {
     const int r = blockIdx.x;
     const float* row = logits + (size_t)r * vocab;
     float mx, se;
@@ -410,16 +413,53 @@ __global__ __launch_bounds__(256) void k_gather_lp(const float* __restrict__ log
     if (threadIdx.x == 0) {
         int y = tokens[target_idx[r]];
         y = min(max(y, 0), vocab - 1);
-        out[out_dst[r]] = logit_at(row, nsplit, sstride, y) - mx - logf(se);
+        const float v = logit_at(row, nsplit, sstride, y) - mx - logf(se);
+        out[out_dst[r]] = v;
+        if (nonfinite && !isfinite(v)) *nonfinite = 1;
     }
 }
 
 hipError_t launch_gather_lp(hipStream_t st, const float* logits, int nsplit, size_t sstride,
                             int rows, int vocab, const int* tokens, const int* target_idx,
-                            float* out, const int* out_dst) {
+                            float* out, const int* out_dst, int* nonfinite) {
     if (rows <= 0) return hipSuccess;
     k_gather_lp<<<rows, 256, 0, st>>>(logits, nsplit, sstride, vocab, tokens, target_idx, out,
-                                      out_dst);
+                                      out_dst, nonfinite);
+    return hipGetLastError();
+}
+
+// Merge of the per-128-column (max, sum exp) partials left by the LM-head GEMM of a scoring pass:
+// one wave per row; out[out_dst[r]] = tgt[r] - (max + log sum).
+__global__ __launch_bounds__(256) void k_lse_merge(const float* __restrict__ part_max,
+                                                   const float* __restrict__ part_sum,
+                                                   const float* __restrict__ tgt, int n_part, int rows,
+                                                   float* __restrict__ out, const int* __restrict__ out_dst,
+                                                   int* __restrict__ nonfinite) {
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int lane = threadIdx.x & 63;
+    const float* pm = part_max + (size_t)r * n_part;
+    const float* ps = part_sum + (size_t)r * n_part;
+    float mx = -INFINITY;
+    for (int i = lane; i < n_part; i += 64) mx = fmaxf(mx, pm[i]);
+    mx = wave_max(mx);
+    float se = 0.f;
+    for (int i = lane; i < n_part; i += 64) {
+        const float m = pm[i];
+        if (m > -INFINITY) se += ps[i] * __expf(m - mx);
+    }
+    se = wave_sum(se);
+    if (lane == 0) {
+        const float v = tgt[r] - mx - logf(se);
+        out[out_dst[r]] = v;
+        if (nonfinite && !isfinite(v)) *nonfinite = 1;
+    }
+}
+
+hipError_t launch_lse_merge(hipStream_t st, const float* part_max, const float* part_sum, const float* tgt,
+                            int n_part, int rows, float* out, const int* out_dst, int* nonfinite) {
+    if (rows <= 0) return hipSuccess;
+    k_lse_merge<<<(rows + 3) / 4, 256, 0, st>>>(part_max, part_sum, tgt, n_part, rows, out, out_dst, nonfinite);
     return hipGetLastError();
 }
 
@@ -428,7 +468,7 @@ hipError_t launch_gather_lp(hipStream_t st, const float* logits, int nsplit, siz
 template <typename T, typename TW>
 __global__ __launch_bounds__(256) void k_head_dot(const T* __restrict__ xn, const TW* __restrict__ w,
                                                   int rows, int d, float* __restrict__ out,
-                                                  const int* __restrict__ out_dst) {
+                                                  const int* __restrict__ out_dst, int* __restrict__ nonfinite) {
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= rows) return;
     const int lane = threadIdx.x & 63;
@@ -441,19 +481,24 @@ __global__ __launch_bounds__(256) void k_head_dot(const T* __restrict__ xn, cons
         for (int e = 0; e < 8; ++e) acc += a[e] * b[e];
     }
     acc = wave_sum(acc);
-    if (lane == 0) out[out_dst[r]] = acc;
+    if (lane == 0) {
+        out[out_dst[r]] = acc;
+        if (nonfinite && !isfinite(acc)) *nonfinite = 1;
+    }
 }
 
 hipError_t launch_head_dot(hipStream_t st, int adt, int wdt, const void* xn, const void* w,
-                           int rows, int d, float* out, const int* out_dst) {
+                           int rows, int d, float* out, const int* out_dst, int* nonfinite) {
     if (rows <= 0) return hipSuccess;
     const int grid = (rows + 3) / 4;
     if (adt == kBF16 && wdt == kBF16)
-        k_head_dot<bf16_t, bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)xn, (const bf16_t*)w, rows, d, out, out_dst);
+        k_head_dot<bf16_t, bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)xn, (const bf16_t*)w, rows, d, out, out_dst, nonfinite);
     else if (adt == kF16 && wdt == kBF16)
-        k_head_dot<f16_t, bf16_t><<<grid, 256, 0, st>>>((const f16_t*)xn, (const bf16_t*)w, rows, d, out, out_dst);
+        k_head_dot<f16_t, bf16_t><<<grid, 256, 0, st>>>((const f16_t*)xn, (const bf16_t*)w, rows, d, out, out_dst, nonfinite);
+    else if (adt == kF32 && wdt == kBF16)
+        k_head_dot<float, bf16_t><<<grid, 256, 0, st>>>((const float*)xn, (const bf16_t*)w, rows, d, out, out_dst, nonfinite);
     else if (adt == kF32 && wdt == kF32)
-        k_head_dot<float, float><<<grid, 256, 0, st>>>((const float*)xn, (const float*)w, rows, d, out, out_dst);
+        k_head_dot<float, float><<<grid, 256, 0, st>>>((const float*)xn, (const float*)w, rows, d, out, out_dst, nonfinite);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
@@ -469,6 +514,13 @@ __global__ void k_scatter_int(int* __restrict__ dst, const int* __restrict__ idx
 hipError_t launch_scatter_int(hipStream_t st, int* dst, const int* idx, const int* val, int n) {
     if (n <= 0) return hipSuccess;
     k_scatter_int<<<(n + 255) / 256, 256, 0, st>>>(dst, idx, val, n);
+    return hipGetLastError();
+}
+
+// An empty kernel: what two events around a launch measure beyond the kernel itself.
+__global__ void k_noop() {}
+hipError_t launch_noop(hipStream_t st) {
+    k_noop<<<1, 64, 0, st>>>();
     return hipGetLastError();
 }
 

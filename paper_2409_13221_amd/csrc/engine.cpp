@@ -90,7 +90,7 @@ struct Workspace {
     void* v = nullptr;
     void* attn = nullptr;     // [rows, Hq*hd]
     void* act = nullptr;      // [rows, ffn]
-    void* xsel = nullptr;     // [rows, d] final-norm rows selected for the head
+    void* xsel = nullptr;     // [rows, d] final-norm rows selected for the head (storage type; float for d -> 1 heads)
     float* logits = nullptr;  // [logit_rows, vocab] (batch passes; decode uses `part`)
     int logit_rows = 0;
     float* pick_scratch = nullptr;  // per-chunk partial results of the greedy pick
@@ -107,12 +107,18 @@ enum KClass { kGemmDecode = 0, kGemmBatch = 1, kAttnDecode = 2, kAttnBatch = 3, 
 struct Profiler {
     bool on = false;
     int every = 1;
-    static constexpr size_t kMaxSamples = 1 << 15;
+    // Event pairs in flight.  rlhf_run_stage folds them into the sums below once the stage has
+    // drained, so the cap bounds the samples of ONE stage; launches beyond it go untimed and are
+    // counted in `dropped` (a caller who sees dropped > 0 should raise sample_every).
+    static constexpr size_t kMaxSamples = 1 << 16;
     struct Rec { hipEvent_t a, b; int cls; double bytes, flops; };
     std::vector<Rec> recs;                 // recs[0..n_used) are live; events are reused across runs
     size_t n_used = 0;
     int64_t launches[kClassCount] = {};
     double tot_bytes[kClassCount] = {}, tot_flops[kClassCount] = {};
+    int64_t sampled[kClassCount] = {}, dropped[kClassCount] = {};
+    double bracket_overhead_ms = 0;        // median event bracket of an empty kernel, measured at begin
+    double s_ms[kClassCount] = {}, s_bytes[kClassCount] = {}, s_flops[kClassCount] = {};
 };
 
 struct Sample {
@@ -152,6 +158,7 @@ struct rlhf_ctx {
     float* d_values = nullptr;
     float* d_reward = nullptr;     // [max_samples]
     float* d_rope = nullptr;       // [max_ctx, hd/2, 2]
+    int* d_nonfinite = nullptr;    // set by the kernels that write results when one is not finite
     int* d_picked = nullptr;       // [max_active] tokens of the last pick (stop_on_eos)
     int* h_picked = nullptr;       // pinned
 
@@ -206,7 +213,8 @@ hipError_t profiled(rlhf_ctx* c, hipStream_t st, int cls, double bytes, double f
     const int64_t k = p.launches[cls]++;
     p.tot_bytes[cls] += bytes;
     p.tot_flops[cls] += flops;
-    if (k % p.every != 0 || p.n_used >= Profiler::kMaxSamples) return launch();
+    if (k % p.every != 0) return launch();
+    if (p.n_used >= Profiler::kMaxSamples) { p.dropped[cls] += 1; return launch(); }
     if (p.n_used == p.recs.size()) {
         Profiler::Rec r{};
         hipError_t e = hipEventCreate(&r.a);
@@ -224,6 +232,22 @@ hipError_t profiled(rlhf_ctx* c, hipStream_t st, int cls, double bytes, double f
     e = launch();
     if (e != hipSuccess) return e;
     return hipEventRecord(r.b, st);
+}
+
+// Fold the finished event pairs into the per-class sums (both streams must have drained).
+hipError_t profiler_fold(Profiler& p) {
+    for (size_t i = 0; i < p.n_used; ++i) {
+        float ms = 0.f;
+        hipError_t e = hipEventElapsedTime(&ms, p.recs[i].a, p.recs[i].b);
+        if (e != hipSuccess) return e;
+        const int k = p.recs[i].cls;
+        p.sampled[k] += 1;
+        p.s_ms[k] += ms;
+        p.s_bytes[k] += p.recs[i].bytes;
+        p.s_flops[k] += p.recs[i].flops;
+    }
+    p.n_used = 0;
+    return hipSuccess;
 }
 
 // Activation and KV-pool type: float for a float model, IEEE half for a bf16 model.
@@ -267,7 +291,7 @@ int alloc_workspace(rlhf_ctx* c, Workspace& ws, int rows, bool decode) {
     HIPCK(c, dev_alloc(&ws, (char**)&ws.q, rows * qd * es));
     HIPCK(c, dev_alloc(&ws, (char**)&ws.attn, rows * qd * es));
     HIPCK(c, dev_alloc(&ws, (char**)&ws.act, rows * f * es));
-    HIPCK(c, dev_alloc(&ws, (char**)&ws.xsel, rows * d * es));
+    HIPCK(c, dev_alloc(&ws, (char**)&ws.xsel, rows * d * 4));    // float rows for the value / reward head
     HIPCK(c, dev_alloc(&ws, &ws.pick_scratch, pick_scratch_floats(rows) * 4));
     if (decode) {
         HIPCK(c, dev_alloc(&ws, &ws.attn_acc, ws.attn_slots * m.head_dim * 4));
@@ -414,7 +438,7 @@ extern "C" void rlhf_destroy(rlhf_ctx* c) {
     c->meta_pre.destroy();
     c->meta_score.destroy();
     void* bufs[] = {c->pool, c->d_page_table, c->d_tokens, c->d_lp_actor, c->d_lp_rescored, c->d_lp_ref,
-                    c->d_values, c->d_reward, c->d_rope, c->d_picked};
+                    c->d_values, c->d_reward, c->d_rope, c->d_picked, c->d_nonfinite};
     for (void* p : bufs)
         if (p) (void)hipFree(p);
     if (c->h_picked) (void)hipHostFree(c->h_picked);
@@ -504,6 +528,8 @@ static int create_impl(rlhf_ctx* c) {
     HIPCK(c, hipMalloc((void**)&c->d_values, ns * mc * 4));
     HIPCK(c, hipMalloc((void**)&c->d_reward, ns * 4));
     HIPCK(c, hipMalloc((void**)&c->d_picked, (size_t)e.max_active * sizeof(int)));
+    HIPCK(c, hipMalloc((void**)&c->d_nonfinite, sizeof(int)));
+    HIPCK(c, hipMemset(c->d_nonfinite, 0, sizeof(int)));
     HIPCK(c, hipHostMalloc((void**)&c->h_picked, (size_t)e.max_active * sizeof(int), hipHostMallocDefault));
     HIPCK(c, hipMemset(c->d_page_table, 0, ns * c->max_pages * sizeof(int)));
 
@@ -647,6 +673,7 @@ extern "C" int rlhf_submit(rlhf_ctx* c, int32_t n, const int32_t* prompt_tokens,
     for (float* r : {c->d_lp_actor, c->d_lp_rescored, c->d_lp_ref, c->d_values})
         HIPCK(c, hipMemset(r, 0xFF, (size_t)c->ec.max_samples * mc * 4));
     HIPCK(c, hipMemset(c->d_reward, 0xFF, (size_t)c->ec.max_samples * 4));
+    HIPCK(c, hipMemset(c->d_nonfinite, 0, sizeof(int)));
     c->waiting.clear();
     for (int i = 0; i < n; ++i) c->waiting.push_back(i);
     c->active.clear();
@@ -701,10 +728,40 @@ int lm_head_chunks(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
         HIPCK(c, gemm_profiled(c, st, kGemmBatch, act_type(c, true), x, w.head, ws.logits, nr, V, d, 1));
         if (pick)
             HIPCK(c, launch_pick(st, ws.logits, 1, 0, nr, V, hp.forced + r0, c->d_tokens, hp.tok_dst + r0,
-                                 c->d_lp_actor, hp.lp_dst + r0, nullptr, ws.pick_scratch));
+                                 c->d_lp_actor, hp.lp_dst + r0, nullptr, ws.pick_scratch, c->d_nonfinite));
         else
             HIPCK(c, launch_gather_lp(st, ws.logits, 1, 0, nr, V, c->d_tokens, hp.target_idx + r0, hp.out,
-                                      hp.out_dst + r0));
+                                      hp.out_dst + r0, c->d_nonfinite));
+    }
+    return RLHF_OK;
+}
+
+// LM head of a scoring pass with the log-softmax gather fused into the GEMM's epilogue: the
+// [rows, vocab] logits never reach memory, only 2 * ceil(vocab / 256) (max, sum exp) pairs and the
+// target logit per row, which a merge kernel turns into log-probs.  The partials live in the
+// workspace's logits buffer.
+int lm_head_logprob_fused(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weights& w, const HeadPlan& hp) {
+    const rlhf_model_cfg& m = c->mc;
+    const int d = m.d_model, V = m.vocab, adt = act_type(c, true);
+    const int n_part = gemm_lse_partials(V);
+    const size_t per_row = (size_t)2 * n_part + 1;
+    const size_t cap_rows = (size_t)ws.logit_rows * V / per_row;
+    if (cap_rows < 1) return c->fail(RLHF_EINVAL, "internal: no room for the LM head's partials");
+    for (int r0 = 0; r0 < hp.n_sel; r0 += (int)std::min<size_t>(cap_rows, 1 << 30)) {
+        const int nr = (int)std::min<size_t>(cap_rows, (size_t)(hp.n_sel - r0));
+        LseOut lo;
+        lo.tokens = c->d_tokens;
+        lo.target_idx = hp.target_idx + r0;
+        lo.part_max = ws.logits;
+        lo.part_sum = ws.logits + (size_t)nr * n_part;
+        lo.tgt = ws.logits + (size_t)2 * nr * n_part;
+        lo.n_part = n_part;
+        const char* x = (const char*)ws.xsel + (size_t)r0 * d * c->esz;
+        const double bytes = ((double)V * d + (double)nr * d) * c->esz + (double)nr * per_row * 4;
+        HIPCK(c, profiled(c, st, kGemmBatch, bytes, 2.0 * nr * V * d,
+                          [&] { return launch_gemm_lse(st, c->dtype, adt, x, w.head, nr, V, d, lo); }));
+        HIPCK(c, launch_lse_merge(st, lo.part_max, lo.part_sum, lo.tgt, n_part, nr, hp.out, hp.out_dst + r0,
+                                  c->d_nonfinite));
     }
     return RLHF_OK;
 }
@@ -908,7 +965,7 @@ int decode_rows(rlhf_ctx* c, const std::vector<int>& rows_ids) {
     const int ns = nsplit_for(c, ws, R, V, d);
     HIPCK(c, gemm_profiled(c, c->sd, kGemmDecode, act_type(c, false), ws.xsel, w.head, ws.part, R, V, d, ns));
     HIPCK(c, launch_pick(c->sd, ws.part, ns, (size_t)R * V, R, V, dmeta + 7 * R, c->d_tokens, dmeta + 5 * R,
-                         c->d_lp_actor, dmeta + 6 * R, c->d_picked, ws.pick_scratch));
+                         c->d_lp_actor, dmeta + 6 * R, c->d_picked, ws.pick_scratch, c->d_nonfinite));
     // algorithmic bytes of this step
     const rlhf_model_cfg& m = c->mc;
     const int64_t qd = (int64_t)m.n_q_heads * m.head_dim, kvd = (int64_t)m.n_kv_heads * m.head_dim;
@@ -1153,20 +1210,26 @@ int score_pass(rlhf_ctx* c, hipStream_t st, MetaRing& meta, Workspace& ws, const
     if (rc) return rc;
     const int d = c->mc.d_model;
     // selected rows may exceed the workspace rows only if n_sel > T, which cannot happen
-    const int adt = act_type(c, true);
+    // The d -> 1 heads read the final-norm row in float (no rounding to the 16-bit activation type
+    // in front of a single dot product); the LM head's GEMM takes the activation type.
+    const bool scalar_head = role == RLHF_CRITIC || role == RLHF_REWARD;
+    const int adt = scalar_head ? kF32 : act_type(c, true);
     HIPCK(c, launch_rmsnorm(st, adt, ws.h, ws.part, pns, pstride, dmeta + 3 * T, w.g_final, ws.xsel, n_sel, d,
                             c->mc.rms_eps));
     if (role == RLHF_CRITIC)
-        HIPCK(c, launch_head_dot(st, adt, c->dtype, ws.xsel, w.head, n_sel, d, c->d_values, dmeta + 3 * T + 2 * n_sel));
+        HIPCK(c, launch_head_dot(st, adt, c->dtype, ws.xsel, w.head, n_sel, d, c->d_values, dmeta + 3 * T + 2 * n_sel,
+                                 c->d_nonfinite));
     else if (role == RLHF_REWARD)
-        HIPCK(c, launch_head_dot(st, adt, c->dtype, ws.xsel, w.head, n_sel, d, c->d_reward, dmeta + 3 * T + 2 * n_sel));
+        HIPCK(c, launch_head_dot(st, adt, c->dtype, ws.xsel, w.head, n_sel, d, c->d_reward, dmeta + 3 * T + 2 * n_sel,
+                                 c->d_nonfinite));
     else {
         HeadPlan hp;
         hp.n_sel = n_sel;
         hp.target_idx = dmeta + 3 * T + n_sel;
         hp.out_dst = dmeta + 3 * T + 2 * n_sel;
         hp.out = role == RLHF_REF ? c->d_lp_ref : c->d_lp_rescored;
-        rc = lm_head_chunks(c, st, ws, w, hp, false);
+        rc = gemm_lse_supported(c->dtype, adt, d) ? lm_head_logprob_fused(c, st, ws, w, hp)
+                                                  : lm_head_chunks(c, st, ws, w, hp, false);
         if (rc) return rc;
     }
     return RLHF_OK;
@@ -1257,9 +1320,29 @@ extern "C" int rlhf_score(rlhf_ctx* c, int32_t n, const int32_t* sample_ids, uin
 
 // ================================================================================ run stage
 
-extern "C" int rlhf_run_stage(rlhf_ctx* c, const rlhf_stage_opts* o, rlhf_stage_stats* out) {
+namespace {
+// A decode step is launch-bound when its chain of dependent kernels (about ten per layer, each
+// at least ~5 us however small) takes longer than streaming the step's weights at ~5 TB/s.  Then
+// a second stream has no idle bandwidth or matrix time to fill and only adds event traffic: the
+// serial plan is the faster one (measured: 0.81x and 0.93x for the fused plan on the two small
+// shapes, 1.03-1.05x on the three large ones).
+bool decode_is_launch_bound(const rlhf_ctx* c) {
+    const rlhf_model_cfg& m = c->mc;
+    const double qd = (double)m.n_q_heads * m.head_dim, kvd = (double)m.n_kv_heads * m.head_dim;
+    const double per_layer = (qd + 2 * kvd) * m.d_model + m.d_model * qd + 3.0 * m.d_model * m.ffn;
+    const double stream_us = (m.n_layers * per_layer + (double)m.vocab * m.d_model) * c->esz / 5.0e6;
+    const double launch_us = (10.0 * m.n_layers + 4) * 5.0;
+    return stream_us < launch_us;
+}
+}  // namespace
+
+extern "C" int rlhf_run_stage(rlhf_ctx* c, const rlhf_stage_opts* opts, rlhf_stage_stats* out) {
     if (!c) return RLHF_EINVAL;
-    if (!o) return c->fail(RLHF_EINVAL, "rlhf_run_stage: NULL options");
+    if (!opts) return c->fail(RLHF_EINVAL, "rlhf_run_stage: NULL options");
+    if (opts->fused < 0 || opts->fused > 2) return c->fail(RLHF_EINVAL, "rlhf_run_stage: fused must be 0, 1 or 2");
+    rlhf_stage_opts resolved = *opts;
+    if (resolved.fused == 2) resolved.fused = decode_is_launch_bound(c) ? 0 : 1;
+    const rlhf_stage_opts* o = &resolved;
     if (c->step != 0 || !c->retired.empty()) return c->fail(RLHF_ESTATE, "rlhf_run_stage: call rlhf_submit first");
     if (o->role_mask & ~0xFu) return c->fail(RLHF_EINVAL, "rlhf_run_stage: unknown role bits");
     const bool timing = o->trace_step_ms && o->trace_cap > 0;
@@ -1325,6 +1408,7 @@ extern "C" int rlhf_run_stage(rlhf_ctx* c, const rlhf_stage_opts* o, rlhf_stage_
     rc = rlhf_sync(c);
     if (rc) return rc;
     const auto t1 = std::chrono::steady_clock::now();
+    if (c->prof.on) HIPCK(c, profiler_fold(c->prof));
     if (timing)
         for (int s = 0; s < std::min(n_steps, o->trace_cap); ++s)
             HIPCK(c, hipEventElapsedTime(&o->trace_step_ms[s], c->step_events[2 * s], c->step_events[2 * s + 1]));
@@ -1347,6 +1431,7 @@ extern "C" int rlhf_run_stage(rlhf_ctx* c, const rlhf_stage_opts* o, rlhf_stage_
         }
         out->decode_weight_bytes = c->acc_weight_bytes;
         out->decode_kv_bytes = c->acc_kv_bytes;
+        out->fused_used = o->fused;
     }
     return RLHF_OK;
 }
@@ -1397,6 +1482,14 @@ extern "C" int rlhf_get_results(rlhf_ctx* c, rlhf_results* out) {
         }
     }
     if (out->reward && n) HIPCK(c, hipMemcpy(out->reward, c->d_reward, (size_t)n * 4, hipMemcpyDeviceToHost));
+    // The 16-bit activation path has no scaling: a model whose activations leave IEEE half's range
+    // (|x| > 65504) produces infinities and then NaNs.  Every kernel that writes a result raises
+    // this flag when the value is not finite; the outputs above are still delivered.
+    int bad = 0;
+    HIPCK(c, hipMemcpy(&bad, c->d_nonfinite, sizeof(int), hipMemcpyDeviceToHost));
+    if (bad)
+        return c->fail(RLHF_ENONFINITE, "rlhf_get_results: a log-prob, value or reward of this stage is not finite "
+                                        "(activations outside the range of the 16-bit path?)");
     return RLHF_OK;
 }
 
@@ -1505,7 +1598,26 @@ extern "C" int rlhf_profile_begin(rlhf_ctx* c, int32_t sample_every) {
     p.on = true;
     p.every = sample_every;
     p.n_used = 0;
-    for (int k = 0; k < kClassCount; ++k) { p.launches[k] = 0; p.tot_bytes[k] = p.tot_flops[k] = 0; }
+    for (int k = 0; k < kClassCount; ++k) {
+        p.launches[k] = p.sampled[k] = p.dropped[k] = 0;
+        p.tot_bytes[k] = p.tot_flops[k] = p.s_ms[k] = p.s_bytes[k] = p.s_flops[k] = 0;
+    }
+    {   // what a bracket costs beyond the kernel inside it: 33 brackets around an empty kernel, median
+        constexpr int kCal = 33;
+        hipEvent_t ev[2 * kCal];
+        for (hipEvent_t& e : ev) HIPCK(c, hipEventCreate(&e));
+        for (int i = 0; i < kCal; ++i) {
+            HIPCK(c, hipEventRecord(ev[2 * i], c->sd));
+            HIPCK(c, launch_noop(c->sd));
+            HIPCK(c, hipEventRecord(ev[2 * i + 1], c->sd));
+        }
+        HIPCK(c, hipStreamSynchronize(c->sd));
+        float ms[kCal];
+        for (int i = 0; i < kCal; ++i) HIPCK(c, hipEventElapsedTime(&ms[i], ev[2 * i], ev[2 * i + 1]));
+        std::sort(ms, ms + kCal);
+        p.bracket_overhead_ms = ms[kCal / 2];
+        for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+    }
     return RLHF_OK;
 }
 
@@ -1516,20 +1628,18 @@ extern "C" int rlhf_profile_end(rlhf_ctx* c, rlhf_kernel_profile* out) {
     if (rc) return rc;
     Profiler& p = c->prof;
     p.on = false;
+    HIPCK(c, profiler_fold(p));
     for (int k = 0; k < kClassCount; ++k) {
         memset(&out[k], 0, sizeof out[k]);
         out[k].launches = p.launches[k];
         out[k].total_bytes = p.tot_bytes[k];
         out[k].total_flops = p.tot_flops[k];
-    }
-    for (size_t i = 0; i < p.n_used; ++i) {
-        float ms = 0.f;
-        HIPCK(c, hipEventElapsedTime(&ms, p.recs[i].a, p.recs[i].b));
-        rlhf_kernel_profile& o = out[p.recs[i].cls];
-        o.sampled += 1;
-        o.sampled_ms += ms;
-        o.sampled_bytes += p.recs[i].bytes;
-        o.sampled_flops += p.recs[i].flops;
+        out[k].sampled = p.sampled[k];
+        out[k].sampled_ms = p.s_ms[k];
+        out[k].sampled_bytes = p.s_bytes[k];
+        out[k].sampled_flops = p.s_flops[k];
+        out[k].dropped = p.dropped[k];
+        out[k].bracket_overhead_ms = p.bracket_overhead_ms;
     }
     return RLHF_OK;
 }

@@ -91,12 +91,19 @@ __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int& 
 // apart), everything is rounded to the activation type and written where attention reads it:
 // q, k, v row-major, and k, v also into the paged pool when the pass fills the cache.  The
 // float [M, (Hq + 2 Hkv) head_dim] intermediate and the separate rotary kernel disappear.
-template <int TM, int TN, int TK, int WM, int WN, bool AF16, bool XCD, bool SWIGLU, bool ADMA = false, int ROPE = 0>
+//
+// LSE: W is an LM head [vocab, K] and the logits never leave the registers: the epilogue reduces
+// each wave's 128 columns of a row to (max, sum of exp(z - max)), writes that pair as one of the
+// row's 2 * tiles_n partials, and the lane that holds the row's target column stores that logit.
+// A small merge kernel turns the partials into log_softmax(z)[target] (k_lse_merge).
+template <int TM, int TN, int TK, int WM, int WN, bool AF16, bool XCD, bool SWIGLU, bool ADMA = false, int ROPE = 0,
+          bool LSE = false>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __restrict__ A,
                                                            const bf16_t* __restrict__ W,
                                                            float* __restrict__ C, int M, int N, int K,
                                                            int kchunk, int tiles_m, int tiles_n,
-                                                           const RopeOut ro = RopeOut{}) {
+                                                           const RopeOut ro = RopeOut{},
+                                                           const LseOut lo = LseOut{}) {
     constexpr int NT = WM * WN * 64;
     constexpr int FM = TM / WM / 16, FN = TN / WN / 16;
     constexpr int CH = TK / 8;                            // 16-byte chunks per tile row
@@ -405,6 +412,43 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
         }
         return;
     }
+    if constexpr (LSE) {
+        const int pcol = tn * WN + wn;                       // this wave's partial of the row
+        const int ncol0 = n0 + wn * (TN / WN) + fq * 4;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int m = m0 + wm * (TM / WM) + i * 16 + fr;
+            const bool row_ok = m < M;
+            int t = -1;
+            if (row_ok) t = min(max(lo.tokens[lo.target_idx[m]], 0), N - 1);
+            float mx = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int n = ncol0 + j * 16 + e;
+                    if (n < N) mx = fmaxf(mx, acc[i][j][e]);
+                    if (n == t) lo.tgt[m] = acc[i][j][e];
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            float se = 0.f;
+            if (mx > -INFINITY) {
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (ncol0 + j * 16 + e < N) se += __expf(acc[i][j][e] - mx);
+            }
+            se += __shfl_xor(se, 16, kWave);
+            se += __shfl_xor(se, 32, kWave);
+            if (row_ok && fq == 0) {
+                lo.part_max[(size_t)m * lo.n_part + pcol] = mx;
+                lo.part_sum[(size_t)m * lo.n_part + pcol] = se;
+            }
+        }
+        return;
+    }
     float* Cs = C + (size_t)split * M * N;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
@@ -630,6 +674,32 @@ hipError_t launch_gemm_rope(hipStream_t st, int wdt, int adt, const void* A, con
     return hipGetLastError();
 }
 
+bool gemm_lse_supported(int wdt, int adt, int K) {
+    return wdt == kBF16 && (adt == kF16 || adt == kBF16) && K % 64 == 0;
+}
+
+int gemm_lse_partials(int N) { return (N + 255) / 256 * 2; }
+
+hipError_t launch_gemm_lse(hipStream_t st, int wdt, int adt, const void* A, const void* W_head, int M, int N, int K,
+                           const LseOut& lo) {
+    if (M <= 0) return hipSuccess;
+    if (!gemm_lse_supported(wdt, adt, K) || N <= 0 || !lo.tokens || !lo.target_idx || !lo.part_max || !lo.part_sum ||
+        !lo.tgt || lo.n_part != gemm_lse_partials(N))
+        return hipErrorInvalidValue;
+    constexpr int TM = 256, TN = 256;
+    const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
+    dim3 grid((tiles_m * tiles_n + 7) / 8 * 8, 1);
+    const bf16_t* a = (const bf16_t*)A;
+    const bf16_t* w = (const bf16_t*)W_head;
+    if (adt == kF16)
+        k_gemm_bf16<TM, TN, 64, 4, 2, true, true, false, true, 0, true><<<grid, 512, 0, st>>>(
+            a, w, nullptr, M, N, K, K, tiles_m, tiles_n, RopeOut{}, lo);
+    else
+        k_gemm_bf16<TM, TN, 64, 4, 2, false, true, false, true, 0, true><<<grid, 512, 0, st>>>(
+            a, w, nullptr, M, N, K, K, tiles_m, tiles_n, RopeOut{}, lo);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm(hipStream_t st, int wdt, int adt, const void* A, const void* W, float* C,
                        int M, int N, int K, int nsplit, int variant) {
     if (M <= 0 || N <= 0) return hipSuccess;
@@ -641,7 +711,6 @@ hipError_t launch_gemm(hipStream_t st, int wdt, int adt, const void* A, const vo
             variant = pick_variant(M, N);
             if (kCfgs[variant].xcd && nsplit != 1) variant = 4;   // a caller-imposed split of a tall GEMM
         }
-        if (kCfgs[variant].xcd && nsplit != 1) return hipErrorInvalidValue;
         const bf16_t* a = (const bf16_t*)A;
         const bf16_t* w = (const bf16_t*)W;
         return adt == kF16 ? launch_bf16<true>(st, variant, a, w, C, M, N, K, nsplit)

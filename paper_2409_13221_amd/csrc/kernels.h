@@ -50,6 +50,26 @@ bool gemm_rope_supported(int wdt, int adt, int M, int K, const Dims& dm);
 hipError_t launch_gemm_rope(hipStream_t st, int wdt, int adt, const void* A, const void* Wqkv, int M, int K,
                             const RopeOut& ro);
 
+// LM head of a scoring pass fused with the log-softmax gather: the logits stay in registers.  Per
+// row m the GEMM leaves n_part = gemm_lse_partials(N) pairs (max, sum of exp(z - max)), one per 128
+// columns (a pair whose columns all lie beyond N is (-inf, 0)), and the logit of the row's target
+// token tokens[target_idx[m]] in tgt[m]; launch_lse_merge finishes
+// out[out_dst[m]] = tgt[m] - log sum_n exp(z[m][n]).
+struct LseOut {
+    const int* tokens = nullptr;       // token buffer
+    const int* target_idx = nullptr;   // [M] index into tokens of each row's target
+    float* part_max = nullptr;         // [M, n_part]
+    float* part_sum = nullptr;         // [M, n_part]
+    float* tgt = nullptr;              // [M]
+    int n_part = 0;
+};
+bool gemm_lse_supported(int wdt, int adt, int K);
+int gemm_lse_partials(int N);
+hipError_t launch_gemm_lse(hipStream_t st, int wdt, int adt, const void* A, const void* W_head, int M, int N, int K,
+                           const LseOut& lo);
+hipError_t launch_lse_merge(hipStream_t st, const float* part_max, const float* part_sum, const float* tgt,
+                            int n_part, int rows, float* out, const int* out_dst, int* nonfinite = nullptr);
+
 // ---- elementwise / row kernels
 hipError_t launch_embed(hipStream_t st, int dtype, const int* tokens, const int* tok_idx,
                         const void* table, float* h, int rows, int d, int vocab);
@@ -70,18 +90,20 @@ hipError_t launch_swiglu(hipStream_t st, int adt, const float* gu, int nsplit, s
                          void* act, int rows, int ffn);
 // Greedy choice per logit row (lowest id on ties), optional imposed token forced[r] >= 0;
 // writes the emitted token to tokens[tok_dst[r]] and picked[r], its log-prob to lp[lp_dst[r]].
+// nonfinite (here and below, may be NULL): *nonfinite is set to 1 when a written result is not finite.
 // scratch: pick_scratch_floats(rows) floats.
 hipError_t launch_pick(hipStream_t st, const float* logits, int nsplit, size_t sstride, int rows,
                        int vocab, const int* forced, int* tokens, const int* tok_dst, float* lp,
-                       const int* lp_dst, int* picked, float* scratch);
+                       const int* lp_dst, int* picked, float* scratch, int* nonfinite = nullptr);
 size_t pick_scratch_floats(int rows);
 // lp[out_dst[r]] = log_softmax(logits[r])[tokens[target_idx[r]]]
 hipError_t launch_gather_lp(hipStream_t st, const float* logits, int nsplit, size_t sstride,
                             int rows, int vocab, const int* tokens, const int* target_idx,
-                            float* out, const int* out_dst);
-// out[out_dst[r]] = <xn[r], w>;  xn of type adt, w of type wdt
+                            float* out, const int* out_dst, int* nonfinite = nullptr);
+// out[out_dst[r]] = <xn[r], w>;  xn of type adt (or float), w of type wdt
 hipError_t launch_head_dot(hipStream_t st, int adt, int wdt, const void* xn, const void* w, int rows,
-                           int d, float* out, const int* out_dst);
+                           int d, float* out, const int* out_dst, int* nonfinite = nullptr);
+hipError_t launch_noop(hipStream_t st);   // empty kernel (calibrates event brackets)
 // page_table[upd_idx[i]] = upd_val[i]
 hipError_t launch_scatter_int(hipStream_t st, int* dst, const int* idx, const int* val, int n);
 

@@ -157,3 +157,93 @@ extern "C" int rlhf_op_gemm_rope(int act_half, const void* A, const void* W_qkv,
     ro.n_q_heads = n_q_heads; ro.n_kv_heads = n_kv_heads; ro.head_dim = head_dim;
     return status_of(launch_gemm_rope((hipStream_t)stream, kBF16, adt, A, W_qkv, M, K, ro));
 }
+
+// ---- row-wise kernels
+
+static int act_of(int act_dtype) { return act_dtype == 2 ? kF16 : act_dtype == RLHF_BF16 ? kBF16 : act_dtype == RLHF_FP32 ? kF32 : -1; }
+
+extern "C" int rlhf_op_rmsnorm(int act_dtype, float* h, const float* part, int nsplit, int64_t sstride,
+                               const int32_t* row_idx, const float* g, void* xn, int rows, int d, float eps,
+                               void* stream) {
+    const int adt = act_of(act_dtype);
+    if (adt < 0 || !h || !g || !xn || rows < 0 || d <= 0 || nsplit < 0 || (nsplit > 0 && (!part || sstride < 0)))
+        return RLHF_EINVAL;
+    return status_of(launch_rmsnorm((hipStream_t)stream, adt, h, part, nsplit, (size_t)sstride, row_idx, g, xn, rows,
+                                    d, eps));
+}
+
+extern "C" int rlhf_op_rope_kv(int act_dtype, const float* qkv, int nsplit, int64_t sstride, const int32_t* pos,
+                               const int32_t* kv_dst, const float* table, void* q, void* k, void* v, void* pool,
+                               int layer, int rows, int n_layers, int n_q_heads, int n_kv_heads, int head_dim,
+                               void* stream) {
+    const int adt = act_of(act_dtype);
+    if (adt < 0 || !qkv || !pos || !table || !q || nsplit < 1 || sstride < 0 || rows < 0 || (pool && !kv_dst) ||
+        n_q_heads <= 0 || n_kv_heads <= 0 || head_dim <= 0 || head_dim % 2 || layer < 0 || layer >= n_layers)
+        return RLHF_EINVAL;
+    Dims dm{n_layers, n_q_heads * head_dim, n_q_heads, n_kv_heads, head_dim, 0, 0, 16};
+    return status_of(launch_rope_kv((hipStream_t)stream, adt, adt, qkv, nsplit, (size_t)sstride, pos, kv_dst, table,
+                                    q, k, v, pool, layer, rows, dm));
+}
+
+extern "C" int rlhf_op_swiglu(int act_dtype, const float* gu, int nsplit, int64_t sstride, void* act, int rows,
+                              int ffn, void* stream) {
+    const int adt = act_of(act_dtype);
+    if (adt < 0 || !gu || !act || nsplit < 1 || sstride < 0 || rows < 0 || ffn <= 0) return RLHF_EINVAL;
+    return status_of(launch_swiglu((hipStream_t)stream, adt, gu, nsplit, (size_t)sstride, act, rows, ffn));
+}
+
+extern "C" int64_t rlhf_op_pick_scratch_floats(int rows) { return rows > 0 ? (int64_t)pick_scratch_floats(rows) : 0; }
+
+extern "C" int rlhf_op_pick(const float* logits, int nsplit, int64_t sstride, int rows, int vocab,
+                            const int32_t* forced, int32_t* tokens, const int32_t* tok_dst, float* lp,
+                            const int32_t* lp_dst, int32_t* picked, float* scratch, void* stream) {
+    if (!logits || !tokens || !tok_dst || !lp || !lp_dst || !scratch || nsplit < 1 || sstride < 0 || rows < 0 ||
+        vocab < 1)
+        return RLHF_EINVAL;
+    return status_of(launch_pick((hipStream_t)stream, logits, nsplit, (size_t)sstride, rows, vocab, forced, tokens,
+                                 tok_dst, lp, lp_dst, picked, scratch));
+}
+
+extern "C" int rlhf_op_gather_lp(const float* logits, int nsplit, int64_t sstride, int rows, int vocab,
+                                 const int32_t* tokens, const int32_t* target_idx, float* out,
+                                 const int32_t* out_dst, void* stream) {
+    if (!logits || !tokens || !target_idx || !out || !out_dst || nsplit < 1 || sstride < 0 || rows < 0 || vocab < 1)
+        return RLHF_EINVAL;
+    return status_of(launch_gather_lp((hipStream_t)stream, logits, nsplit, (size_t)sstride, rows, vocab, tokens,
+                                      target_idx, out, out_dst));
+}
+
+extern "C" int rlhf_op_head_dot(int act_dtype, int w_dtype, const void* xn, const void* w, int rows, int d,
+                                float* out, const int32_t* out_dst, void* stream) {
+    const int adt = act_of(act_dtype);
+    if (adt < 0 || (w_dtype != RLHF_FP32 && w_dtype != RLHF_BF16) || !xn || !w || !out || !out_dst || rows < 0 ||
+        d <= 0 || d % 8)
+        return RLHF_EINVAL;
+    return status_of(launch_head_dot((hipStream_t)stream, adt, w_dtype == RLHF_BF16 ? kBF16 : kF32, xn, w, rows, d,
+                                     out, out_dst));
+}
+
+extern "C" int64_t rlhf_op_lm_head_logprob_scratch_floats(int M, int vocab) {
+    if (M <= 0 || vocab <= 0) return 0;
+    return (int64_t)M * (2 * gemm_lse_partials(vocab) + 1);
+}
+
+extern "C" int rlhf_op_lm_head_logprob(int act_half, const void* A, const void* W_head, const int32_t* tokens,
+                                       const int32_t* target_idx, float* out, const int32_t* out_dst,
+                                       float* scratch, int M, int vocab, int K, void* stream) {
+    if (!A || !W_head || !tokens || !target_idx || !out || !out_dst || !scratch || M < 0 || vocab < 1 || K <= 0)
+        return RLHF_EINVAL;
+    const int adt = act_half ? kF16 : kBF16;
+    if (!gemm_lse_supported(kBF16, adt, K)) return RLHF_EINVAL;
+    LseOut lo;
+    lo.n_part = gemm_lse_partials(vocab);
+    lo.tokens = tokens;
+    lo.target_idx = target_idx;
+    lo.part_max = scratch;
+    lo.part_sum = scratch + (size_t)M * lo.n_part;
+    lo.tgt = scratch + (size_t)2 * M * lo.n_part;
+    hipError_t e = launch_gemm_lse((hipStream_t)stream, kBF16, adt, A, W_head, M, vocab, K, lo);
+    if (e == hipSuccess)
+        e = launch_lse_merge((hipStream_t)stream, lo.part_max, lo.part_sum, lo.tgt, lo.n_part, M, out, out_dst);
+    return status_of(e);
+}

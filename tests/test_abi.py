@@ -36,10 +36,10 @@ def test_binding_structs_match_header_sizes():
     assert ctypes.sizeof(B.rlhf_weights) == 9 * 8
     assert ctypes.sizeof(B.rlhf_step_info) == 6 * 4
     assert ctypes.sizeof(B.rlhf_stage_opts) == 4 * 4 + 5 * 8 + 8
-    assert ctypes.sizeof(B.rlhf_stage_stats) == 8 + 3 * 8 + 3 * 8 + 2 * 8
+    assert ctypes.sizeof(B.rlhf_stage_stats) == 8 + 3 * 8 + 3 * 8 + 2 * 8 + 8      # fused_used + padding
     assert ctypes.sizeof(B.rlhf_results) == 9 * 8
     assert ctypes.sizeof(B.rlhf_snapshot) == 10 * 4 + 9 * 8 + 3 * 4 + 4
-    assert ctypes.sizeof(B.rlhf_kernel_profile) == 2 * 8 + 5 * 8
+    assert ctypes.sizeof(B.rlhf_kernel_profile) == 2 * 8 + 5 * 8 + 8 + 8
 
 
 def test_create_rejects_bad_arguments_without_a_gpu():

@@ -360,3 +360,74 @@ def test_degenerate_workloads(tiny_ref):
     H.compare_stage(cfg, ref, a)
     for k in ("tokens", "lp_actor", "lp_ref", "values", "reward"):
         np.testing.assert_array_equal(a[k], b[k])
+
+
+# ------------------------------------------------- exact logit ties, non-finite results
+
+@pytest.mark.parametrize("which", ["tiny", "gpt2s"])
+def test_exact_logit_ties_emit_the_lower_id(which):
+    """Every odd row of the Actor's LM head is a copy of the even row before it, so every
+    position's best logit is an exact tie between ids 2k and 2k + 1.  Both picks (the one after
+    prefill, over one logit plane, and the one of a decode step, over split-K planes) must emit
+    the even id.  Nothing is teacher-forced; the oracle checks the path by teacher forcing."""
+    import copy
+    if which == "tiny":
+        cfg = CONFIGS["tiny"].with_(gain_jitter=0.05)
+        inp = H.make_inputs(cfg, n=6, max_len=14)
+    else:
+        cfg = CONFIGS["gpt2s"].with_(gain_jitter=0.05)
+        inp = H.make_inputs(cfg, n=4, max_len=10, weight_device="cuda")
+    inp = dict(inp)
+    inp["weights"] = [dict(w) for w in inp["weights"]]
+    head = inp["weights"][0]["head"].clone()
+    head[1::2] = head[0::2]
+    inp["weights"][0]["head"] = head
+    with H.GpuStage(cfg, inp) as g:
+        g.submit(None)
+        g.R.rlhf_run_stage(g.ctx, True, g.n + 1, 64, 0b0001)
+        got = g.results()
+    toks = H.unpack(got, "tokens")
+    assert sum(len(t) for t in toks) == int(inp["out_len"].sum())
+    for i, t in enumerate(toks):
+        assert np.all(t % 2 == 0), f"sample {i} emitted an odd id: {t}"
+        assert t[-1] == cfg.eos_id
+    # first tokens come from the prefill pick, the others from decode picks
+    assert all(len(t) >= 3 for t in toks)
+    H.check_samples_by_teacher_forcing(cfg, inp, got, list(range(g.n)), dtype=np.float64, roles=(0,))
+
+
+def test_non_finite_results_are_reported():
+    """A model whose activations leave the range of the 16-bit path: the stage still runs to its
+    end (every kernel stays in bounds), and rlhf_get_results reports RLHF_ENONFINITE."""
+    import paper_2409_13221_amd as R
+    cfg = CONFIGS["gpt2s"].with_(gain_jitter=0.0)
+    inp = H.make_inputs(cfg, n=3, max_len=5, n_layers=2, weight_device="cuda")
+    ok = H.run_gpu_stage(cfg, inp, fused=True, R_t=4, chunk_tokens=64)           # finite as drawn
+    assert np.isfinite(ok["lp_actor"]).all() and np.isfinite(ok["values"]).all()
+    inp = dict(inp)
+    inp["weights"] = [dict(w) for w in inp["weights"]]
+    inp["weights"][1]["g_final"] = inp["weights"][1]["g_final"] * 1.0e6          # Reference: final-norm rows overflow half
+    with H.GpuStage(cfg, inp) as g:
+        g.submit(None)
+        g.R.rlhf_run_stage(g.ctx, True, g.n + 1, 64, H.ALL_ROLES)
+        with pytest.raises(R.RlhfError) as e:
+            g.results()
+        assert e.value.code == R.RLHF_ENONFINITE
+        # the flag belongs to the stage: a new submit clears it
+        g.submit(None)
+        g.R.rlhf_run_stage(g.ctx, True, g.n + 1, 64, 0b1101)                     # without the Reference
+        assert np.isfinite(g.results()["values"]).all()
+
+
+def test_auto_plan_picks_serial_for_launch_bound_models(tiny_ref, gpt2s_ref):
+    """fused = 2 leaves the plan to the library: both small shapes are launch-bound, so it runs
+    the serial plan (one scoring pass after generation), with the serial plan's batches."""
+    for cfg, ref in (tiny_ref, gpt2s_ref):
+        with H.GpuStage(cfg, ref) as g:
+            g.submit(ref["forced"])
+            model = H.scheduler_model_for(g)
+            model.run_stage(False, 0, 64)
+            stats, _ = g.R.rlhf_run_stage(g.ctx, "auto", g.n + 1, 64, H.ALL_ROLES)
+            assert stats.fused_used == 0
+            assert g.snapshot()["batches"] == model.batches
+            H.compare_stage(cfg, ref, g.results())

@@ -55,7 +55,7 @@ def test_7b_full_depth_matches_oracle():
         np.testing.assert_array_equal(H.unpack(got, "tokens")[i], g.tokens)
         assert np.abs(H.unpack(got, "lp_actor")[i] - g.logprob).max() <= 2e-2
         assert np.abs(H.unpack(got, "lp_actor_rescored")[i] - g.logprob).max() <= 2e-2
-    worst = H.check_samples_by_teacher_forcing(cfg, inp, got, [0, 1], roles=(2,))
+    worst = H.check_samples_by_teacher_forcing(cfg, inp, got, [0, 1], roles=(2,), value_tol=H.DEEP)
     print("[7b full depth] worst:", worst, flush=True)
 
 
@@ -118,7 +118,10 @@ def test_7b_full_config_properties(optimistic):
     what bench.py times by default; cap reservations, where the KV pool gates admission, is its
     --admission reserve): bookkeeping bit-exact against the scheduler model, fused and serial
     plans give identical tokens, and the Actor log-probs captured by cached decoding agree with
-    their re-scoring by a full forward (cached decode = full recompute)."""
+    their re-scoring by a full forward (cached decode = full recompute).  In the benchmark's
+    configuration the run is also checked against the oracle: the longest sample (more than a
+    thousand output tokens, context past 1500) and a short one go through the float32 oracle at
+    full depth for all four roles (teacher forcing on the GPU's own tokens)."""
     import torch
     cfg = CONFIGS["7b"]
     inp = H.make_inputs(cfg, weight_device="cuda")
@@ -158,3 +161,46 @@ def test_7b_full_config_properties(optimistic):
     print(f"[7b full] max |lp_actor - lp_actor_rescored| over {fused['lp_actor'].size} tokens: {gap:.4f}", flush=True)
     assert gap <= 4e-2
     assert np.all(np.isfinite(fused["reward"])) and np.all(fused["lp_ref"] <= 0)
+    if optimistic:
+        longest = int(np.argmax(inp["out_len"]))
+        short = int(np.argmin(np.where(inp["out_len"] >= 8, inp["out_len"] + np.diff(inp["prompt_offsets"]), 1 << 30)))
+        po = inp["prompt_offsets"]
+        print(f"[7b full] oracle check of sample {longest} (prompt {po[longest + 1] - po[longest]}, output "
+              f"{inp['out_len'][longest]}) and sample {short} (prompt {po[short + 1] - po[short]}, output "
+              f"{inp['out_len'][short]}), all four roles", flush=True)
+        worst = H.check_samples_by_teacher_forcing(cfg, inp, fused, [longest, short], dtype=np.float32,
+                                                   roles=(0, 1, 2, 3), value_tol=H.DEEP, deep_tokens=True)
+        print("[7b full] sampled outputs against the oracle:", worst, flush=True)
+
+
+def _deep_stage_against_oracle(name, n_layers, n, max_len, prompt_len, role_samples):
+    """A stage at (nearly) full depth of a wide shape on a few samples with contexts beyond a
+    thousand tokens: the GPU generates and scores (fused plan); every sample's tokens, Actor
+    log-probs and, per role_samples, Reference log-probs / values / rewards go through the float32
+    oracle by teacher forcing.  The serial plan must give the same tokens."""
+    cfg = CONFIGS[name].with_(gain_jitter=0.05) if prompt_len is None else \
+        CONFIGS[name].with_(gain_jitter=0.05, prompt_len=prompt_len)
+    inp = H.make_inputs(cfg, n=n, max_len=max_len, n_layers=n_layers, weight_device="cuda")
+    print(f"[{name} x{n_layers}] weights ready; outputs {inp['out_len'].tolist()}, prompts "
+          f"{np.diff(inp['prompt_offsets']).tolist()}", flush=True)
+    got = H.run_gpu_stage(cfg, inp, fused=True, R_t=n + 1, chunk_tokens=1024, max_batch_tokens=4096)
+    seq = H.run_gpu_stage(cfg, inp, fused=False, R_t=0, chunk_tokens=1024, max_batch_tokens=4096)
+    np.testing.assert_array_equal(got["tokens"], seq["tokens"])
+    np.testing.assert_array_equal(got["lp_actor"], seq["lp_actor"])
+    assert np.abs(got["lp_actor"] - got["lp_actor_rescored"]).max() <= 4e-2
+    worst = H.check_samples_by_teacher_forcing(cfg, inp, got, list(range(n)), dtype=np.float32, roles=(0, 1, 2, 3),
+                                               value_tol=H.DEEP, role_samples=role_samples, deep_tokens=True)
+    print(f"[{name} x{n_layers}] against the oracle:", worst, flush=True)
+    assert (np.diff(inp["prompt_offsets"]) + inp["out_len"]).max() >= 1000
+
+
+def test_70b_slice_full_depth_stage_matches_oracle():
+    """All 10 layers of the 70B-slice shape (64 query / 8 KV heads: the grouped-head MFMA decode
+    attention and the grouped flash attention inside a deep stage), prompts of 1024 tokens."""
+    _deep_stage_against_oracle("70b_slice", None, n=2, max_len=24, prompt_len=None,
+                               role_samples={1: [1], 2: [0], 3: [1]})
+
+
+def test_13b_eight_layer_stage_matches_oracle():
+    """8 of the 40 layers of the 13B shape (d 5120, 40 heads), one context beyond a thousand tokens."""
+    _deep_stage_against_oracle("13b", 8, n=2, max_len=200, prompt_len=(880, 900), role_samples={1: [0], 3: [0]})
