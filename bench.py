@@ -72,10 +72,14 @@ def build_stage(cfg, args):
     free_b, total_b = torch.cuda.mem_get_info()
     max_batch_tokens = max(args.max_batch_tokens, max_ctx)
     ws_est = 3 * max_batch_tokens * (12 * m.d_model + 8 * m.ffn + 16 * m.n_q_heads * m.head_dim) + (8 << 30)
-    pool_pages = int(min(need_pages, max(1, (free_b - ws_est) // page_b)))
+    # half copies of the matrices for the prefill / scoring passes (made by rlhf_load_weights, after the pool)
+    half_copies = int(args.half_weight_copies and m.dtype == "bf16")
+    copies_b = 4 * m.decode_weight_bytes() if half_copies else 0
+    pool_pages = int(min(need_pages, max(1, (free_b - ws_est - copies_b) // page_b)))
     mc = R.model_cfg_of(m)
     ec = R.rlhf_engine_cfg(cfg.page_tokens, pool_pages * page_b, n, max_ctx, min(n, args.max_active),
-                           max_batch_tokens, cfg.eos_id, 0, args.corun_decode_cus, int(args.admission == "optimistic"), None, None)
+                           max_batch_tokens, cfg.eos_id, 0, args.corun_decode_cus, int(args.admission == "optimistic"), None, None,
+                           half_copies)
     ctx = R.rlhf_create(mc, ec)
     for role, w in enumerate(weights):
         R.rlhf_load_weights(ctx, role, w)
@@ -90,7 +94,7 @@ def run_stage(R, ctx, wl, max_new, fused, args, trace=False):
     n = len(max_new)
     R_t = args.R_t if args.R_t >= 0 else n + 1
     t0 = time.perf_counter()
-    stats, tr = R.rlhf_run_stage(ctx, fused, R_t, args.score_chunk_tokens, args.role_mask,
+    stats, tr = R.rlhf_run_stage(ctx, "auto" if fused == "auto" else bool(fused), R_t, args.score_chunk_tokens, args.role_mask,
                                  trace_cap=(1 << 15) if trace else 0, trace_time=trace)
     return (time.perf_counter() - t0) * 1e3, stats, tr
 
@@ -351,6 +355,7 @@ def main():
                     help="compute units given to decoding while scoring is in flight (0 = no partition)")
     ap.add_argument("--sample_every", type=int, default=7,
                     help="time every n-th launch of a kernel class (co-prime with the 4 GEMMs per layer)")
+    ap.add_argument("--fused", action="store_true", help="force the fused plan (default: the library chooses)")
     ap.add_argument("--sequential", action="store_true",
                     help="time the serial generate-then-score plan instead (clean per-kernel figures)")
     ap.add_argument("--rt_sweep", action="store_true", help="fused stage time vs the trigger R_t")
@@ -358,6 +363,9 @@ def main():
     ap.add_argument("--admission", choices=["reserve", "optimistic"], default="optimistic",
                     help="reserve: a sample is admitted when its KV reservation at the length cap fits; "
                          "optimistic: on present need, with preemption by re-prefill")
+    ap.add_argument("--half_weight_copies", type=int, default=1,
+                    help="1: the library keeps IEEE-half copies of the bf16 matrices for prefill / scoring passes "
+                         "(both GEMM operands direct to LDS); 0: bf16 weights converted on the fly")
     ap.add_argument("--weights", choices=["seeded", "normal"], default="seeded",
                     help="seeded: the workload's counter-based generator; normal: torch's (profiler runs only)")
     ap.add_argument("--micro_rows", type=int, default=6144, help="rows of the scoring-pass cases of --micro")
@@ -395,16 +403,19 @@ def main():
         bs_curve(cfg, args)
         return
     R, ctx, weights, wl, max_new = build_stage(cfg, args)
+    # the library picks the plan (fused unless a decode step of this model is launch-bound) unless told otherwise
+    plan = False if args.sequential else True if args.fused else "auto"
 
     for i in range(args.warmup):
-        ms, st, _ = run_stage(R, ctx, wl, max_new, not args.sequential, args)
-        log(f"[bench] warmup {i}: {ms:.1f} ms, {st.n_steps} steps, {st.n_batches} scoring batches")
+        ms, st, _ = run_stage(R, ctx, wl, max_new, plan, args)
+        log(f"[bench] warmup {i}: {ms:.1f} ms, {st.n_steps} steps, {st.n_batches} scoring batches, "
+            f"plan {'fused' if st.fused_used else 'serial'}")
     R.rlhf_profile_begin(ctx, args.sample_every)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     times, last = [], None
     for i in range(args.steps):
-        ms, st, tr = run_stage(R, ctx, wl, max_new, not args.sequential, args, trace=(i == args.steps - 1))
+        ms, st, tr = run_stage(R, ctx, wl, max_new, plan, args, trace=(i == args.steps - 1))
         times.append(ms)
         last = (st, tr)
         log(f"[bench] step {i}: {ms:.1f} ms")
@@ -485,8 +496,9 @@ def main():
            "data": "synthetic",
            "config": {"workload": cfg.name, "n_samples": int(len(max_new)), "length_law": cfg.length_law,
                       "length_params": list(cfg.length_params), "length_cap": cfg.length_cap,
-                      "plan": "sequential" if args.sequential else "fused",
+                      "plan": "fused" if st.fused_used else "sequential",
                       "corun_decode_cus": args.corun_decode_cus, "admission": args.admission,
+                      "half_weight_copies": int(args.half_weight_copies and cfg.model.dtype == "bf16"),
                       "score_chunk_tokens": args.score_chunk_tokens, "R_t": args.R_t, "role_mask": args.role_mask,
                       "page_tokens": cfg.page_tokens},
            "roofline": roof, "cpu_baseline": cpu, "fused_vs_sequential": seq, "roofline_all": roofs,

@@ -17,8 +17,9 @@
  *     copied before it returns.  Result and snapshot buffers are caller-allocated host
  *     arrays filled before the call returns.
  *   - The library owns the paged KV pool, page tables, workspaces and (unless given) its
- *     two HIP streams.  It allocates device memory only in rlhf_create() (and temporaries
- *     inside rlhf_compute_gae()).
+ *     two HIP streams.  It allocates device memory only in rlhf_create(), in
+ *     rlhf_load_weights() when half_weight_copies is set, and for temporaries inside
+ *     rlhf_compute_gae().
  *   - One context may be used from one host thread at a time.
  */
 #ifndef RLHF_H
@@ -51,9 +52,12 @@ enum rlhf_dtype { RLHF_FP32 = 0, RLHF_BF16 = 1 };
  * pairs (k, k + head_dim/2), grouped KV heads, SwiGLU MLP, no biases.  dtype is the
  * storage type of the matrices.  The residual stream, norms, softmax and all accumulation
  * are float32 in either case.  With BF16 matrices, the activations fed to the matrix units
- * and the KV cache are IEEE half (2 bytes as well): the bf16 weights convert to half exactly
- * inside the kernels, and the 8 times finer rounding of half is what keeps log-probs within
- * 2e-2 and values / rewards within 1e-2 of a float64 evaluation at 32 layers.
+ * and the KV cache are IEEE half (2 bytes as well): the bf16 weights convert to half inside
+ * the kernels (exactly, for magnitudes of at least 2^-14; smaller ones land on half's subnormal
+ * grid, an absolute error below 2^-24), and the 8 times finer rounding of half is what keeps
+ * the rounding noise of log-probs, values and rewards near the stated tolerances at 32 layers.
+ * There is no scaling: activations beyond half's range (65504) overflow, and a stage whose
+ * results are not finite reports RLHF_ENONFINITE.
  * Requirements: head_dim in {64, 128}; d_model, ffn multiples of 8; n_q_heads a multiple
  * of n_kv_heads. */
 typedef struct rlhf_model_cfg {
@@ -93,6 +97,14 @@ typedef struct rlhf_engine_cfg {
                                       admission order) until it fits                            */
     void* decode_stream;           /* hipStream_t to use, or NULL: the library creates one    */
     void* score_stream;            /* hipStream_t to use, or NULL                             */
+    int32_t half_weight_copies;    /* 1 (bf16 models): rlhf_load_weights also makes an IEEE-half
+                                      copy of every matrix (library-owned device memory, as many
+                                      bytes again as the bf16 weights; RLHF_ENOMEM if they do not
+                                      fit beside the KV pool), which the prefill / scoring passes
+                                      read instead: both GEMM operands then go from memory straight
+                                      into LDS with no conversion in the loop.  Results are
+                                      bit-identical either way (the on-the-fly conversion yields
+                                      the same half values).  0: no copies                       */
 } rlhf_engine_cfg;
 
 /* One role's tensors (device pointers, element type per rlhf_model_cfg.dtype except the

@@ -25,6 +25,14 @@ extern "C" {
  * stage uses for M rows; a positive value forces one of the library's tilings (benchmarks;
  * RLHF_EINVAL if it does not exist or cannot split K).  rlhf_op_gemm_nsplit returns the split
  * the stage itself would choose for this shape, at most max_split. */
+/* Half copies of the weights: rlhf_op_bf16_to_half converts n (even) bf16 elements to IEEE half the
+ * way the kernels do on the fly (exact for magnitudes >= 2^-14, toward zero on half's subnormal
+ * grid below).  With such a copy as W, rlhf_op_gemm takes dtype = 2 (A must be half, K a multiple
+ * of 64; the 256 x 256 tiling with both operands loaded global -> LDS directly, any nsplit whose
+ * ranges are non-empty), and rlhf_op_gemm_swiglu / rlhf_op_gemm_rope / rlhf_op_lm_head_logprob take
+ * act_half = 2.  This is what the stage runs in prefill / scoring passes when the engine option
+ * half_weight_copies is set; results are bit-identical to the bf16-weight path. */
+int rlhf_op_bf16_to_half(const void* src, void* dst, int64_t n, void* stream);
 int rlhf_op_gemm_nsplit(int dtype, int M, int N, int K, int max_split);
 int rlhf_op_gemm(int dtype, int act_half, const void* A, const void* W, float* C, int M, int N, int K,
                  int nsplit, int variant, void* stream);

@@ -41,7 +41,7 @@ class rlhf_engine_cfg(C.Structure):
                 ("max_ctx", C.c_int32), ("max_active", C.c_int32), ("max_batch_tokens", C.c_int32),
                 ("eos_id", C.c_int32), ("stop_on_eos", C.c_int32), ("corun_decode_cus", C.c_int32),
                 ("optimistic_admission", C.c_int32), ("decode_stream", C.c_void_p),
-                ("score_stream", C.c_void_p)]
+                ("score_stream", C.c_void_p), ("half_weight_copies", C.c_int32)]
 
 
 class rlhf_weights(C.Structure):
@@ -140,6 +140,8 @@ def lib() -> C.CDLL:
         L.rlhf_op_lm_head_logprob_scratch_floats.restype = i64
         L.rlhf_op_lm_head_logprob.argtypes = [C.c_int] + [vp] * 7 + [C.c_int] * 3 + [vp]
         L.rlhf_op_lm_head_logprob.restype = C.c_int
+        L.rlhf_op_bf16_to_half.argtypes = [vp, vp, i64, vp]
+        L.rlhf_op_bf16_to_half.restype = C.c_int
         for name in ("rlhf_op_rmsnorm", "rlhf_op_rope_kv", "rlhf_op_swiglu", "rlhf_op_pick", "rlhf_op_gather_lp",
                      "rlhf_op_head_dot"):
             getattr(L, name).restype = C.c_int
@@ -341,6 +343,24 @@ def _op_check(rc: int, what: str):
         raise RlhfError(rc, what)
 
 
+def _half_code(A, W) -> int:
+    """act_half argument of the fused-epilogue GEMMs: 0 bf16 x bf16, 1 half x bf16, 2 half x half copy."""
+    import torch
+    if W.dtype == torch.float16:
+        assert A.dtype == torch.float16
+        return 2
+    return int(A.dtype == torch.float16)
+
+
+def rlhf_op_bf16_to_half(W):
+    """IEEE-half copy of a bfloat16 tensor, converted by the library's own kernel."""
+    import torch
+    assert W.dtype == torch.bfloat16 and W.is_contiguous() and W.numel() % 2 == 0
+    out = torch.empty_like(W, dtype=torch.float16)
+    _op_check(lib().rlhf_op_bf16_to_half(W.data_ptr(), out.data_ptr(), W.numel(), _stream_ptr()), "rlhf_op_bf16_to_half")
+    return out
+
+
 def rlhf_op_gemm_nsplit(dtype: int, M: int, N: int, K: int, max_split: int) -> int:
     return lib().rlhf_op_gemm_nsplit(dtype, M, N, K, max_split)
 
@@ -354,7 +374,8 @@ def rlhf_op_gemm(A, W, C_out, nsplit: int, variant: int = 0) -> None:
     assert W.shape[1] == K and tuple(C_out.shape) == (nsplit, M, N) and A.is_contiguous() and W.is_contiguous()
     half = A.dtype == torch.float16
     assert half or A.dtype == W.dtype
-    _op_check(lib().rlhf_op_gemm(_dt(W), int(half), A.data_ptr(), W.data_ptr(), C_out.data_ptr(), M, N, K, nsplit,
+    wcode = 2 if W.dtype == torch.float16 else _dt(W)            # float16 W: a half copy of bf16 weights
+    _op_check(lib().rlhf_op_gemm(wcode, int(half), A.data_ptr(), W.data_ptr(), C_out.data_ptr(), M, N, K, nsplit,
                                  variant, _stream_ptr()), "rlhf_op_gemm")
 
 
@@ -412,8 +433,8 @@ def rlhf_op_gemm_swiglu(A, W_gate_up, act) -> None:
     import torch
     M, K = A.shape
     f = W_gate_up.shape[0] // 2
-    assert W_gate_up.dtype == torch.bfloat16 and act.dtype == A.dtype and tuple(act.shape) == (M, f)
-    _op_check(lib().rlhf_op_gemm_swiglu(int(A.dtype == torch.float16), A.data_ptr(), W_gate_up.data_ptr(),
+    assert W_gate_up.dtype in (torch.bfloat16, torch.float16) and act.dtype == A.dtype and tuple(act.shape) == (M, f)
+    _op_check(lib().rlhf_op_gemm_swiglu(_half_code(A, W_gate_up), A.data_ptr(), W_gate_up.data_ptr(),
                                         act.data_ptr(), M, f, K, _stream_ptr()), "rlhf_op_gemm_swiglu")
 
 
@@ -425,7 +446,7 @@ def rlhf_op_gemm_rope(A, W_qkv, pos, table, q, k=None, v=None, pool=None, kv_dst
     and times the kernel passes False."""
     import torch
     M, K = A.shape
-    assert W_qkv.dtype == torch.bfloat16 and tuple(W_qkv.shape) == ((n_q_heads + 2 * n_kv_heads) * head_dim, K)
+    assert W_qkv.dtype in (torch.bfloat16, torch.float16) and tuple(W_qkv.shape) == ((n_q_heads + 2 * n_kv_heads) * head_dim, K)
     assert pos.dtype == torch.int32 and pos.numel() == M and table.dtype == torch.float32
     assert tuple(table.shape[1:]) == (head_dim // 2, 2)
     assert not check_indices or (0 <= int(pos.min()) and int(pos.max()) < table.shape[0])
@@ -438,7 +459,7 @@ def rlhf_op_gemm_rope(A, W_qkv, pos, table, q, k=None, v=None, pool=None, kv_dst
         assert pool.numel() % page_elems == 0
         assert not check_indices or (0 <= int(kv_dst.min()) and int(kv_dst.max()) < pool.numel() // page_elems * 16)
     ptr = lambda t: None if t is None else t.data_ptr()
-    _op_check(lib().rlhf_op_gemm_rope(int(A.dtype == torch.float16), A.data_ptr(), W_qkv.data_ptr(), pos.data_ptr(),
+    _op_check(lib().rlhf_op_gemm_rope(_half_code(A, W_qkv), A.data_ptr(), W_qkv.data_ptr(), pos.data_ptr(),
                                       ptr(kv_dst), table.data_ptr(), q.data_ptr(), ptr(k), ptr(v), ptr(pool), M, K,
                                       layer, n_layers, n_q_heads, n_kv_heads, head_dim, _stream_ptr()),
               "rlhf_op_gemm_rope")
@@ -520,13 +541,13 @@ def rlhf_op_lm_head_logprob(A, W_head, tokens, target_idx, out, out_dst, scratch
     import torch
     M, K = A.shape
     vocab = W_head.shape[0]
-    assert W_head.dtype == torch.bfloat16 and W_head.shape[1] == K and A.is_contiguous() and W_head.is_contiguous()
+    assert W_head.dtype in (torch.bfloat16, torch.float16) and W_head.shape[1] == K and A.is_contiguous() and W_head.is_contiguous()
     assert int(target_idx.max()) < tokens.numel() and int(out_dst.max()) < out.numel()
     need = lib().rlhf_op_lm_head_logprob_scratch_floats(M, vocab)
     if scratch is None:
         scratch = torch.empty(max(need, 1), device=A.device)
     assert scratch.numel() >= need
-    _op_check(lib().rlhf_op_lm_head_logprob(int(A.dtype == torch.float16), A.data_ptr(), W_head.data_ptr(),
+    _op_check(lib().rlhf_op_lm_head_logprob(_half_code(A, W_head), A.data_ptr(), W_head.data_ptr(),
                                             tokens.data_ptr(), target_idx.data_ptr(), out.data_ptr(), out_dst.data_ptr(),
                                             scratch.data_ptr(), M, vocab, K, _stream_ptr()), "rlhf_op_lm_head_logprob")
     return scratch

@@ -28,6 +28,10 @@ thread_local char g_create_error[512] = "";
 struct RoleWeights {
     bool bound = false;
     rlhf_weights w{};
+    // IEEE-half copies of the bf16 matrices for the tall (prefill / scoring) passes, owned by the
+    // library (engine option half_weight_copies); NULL members: no copy, the bf16 tensor is used
+    rlhf_weights h16{};
+    std::vector<void*> owned;
 };
 
 // Pinned host staging + one device arena for small per-pass integer metadata.  The host runs
@@ -254,10 +258,10 @@ hipError_t profiler_fold(Profiler& p) {
 int act_type(const rlhf_ctx* c, bool /*batch*/) { return c->dtype == kBF16 ? kF16 : kF32; }
 
 hipError_t gemm_profiled(rlhf_ctx* c, hipStream_t st, int cls, int adt, const void* A, const void* W, float* C,
-                         int M, int N, int K, int nsplit) {
+                         int M, int N, int K, int nsplit, bool w_is_half_copy = false) {
     const double bytes = ((double)N * K + (double)M * K) * c->esz + (double)M * N * 4;
     return profiled(c, st, cls, bytes, 2.0 * M * N * K,
-                    [&] { return launch_gemm(st, c->dtype, adt, A, W, C, M, N, K, nsplit); });
+                    [&] { return launch_gemm(st, w_is_half_copy ? kF16 : c->dtype, adt, A, W, C, M, N, K, nsplit); });
 }
 
 template <typename T>
@@ -339,9 +343,11 @@ struct PassMeta {         // device pointers into a MetaRing arena
 // Embedding and all decoder layers over `rows` rows.  On return ws.h holds the residual
 // stream except for the last down-projection, whose split-K partials are still in ws.part:
 // (*pend_ns, *pend_stride) describe them for the final norm.
-int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weights& w, int rows,
+int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const RoleWeights& rw, int rows,
                    const PassMeta& pm, AttnMode mode, int attn_nsplit, int* pend_ns,
                    size_t* pend_stride) {
+    const rlhf_weights& w = rw.w;
+    const rlhf_weights& wh = rw.h16;              // half copies (members may be NULL)
     const rlhf_model_cfg& m = c->mc;
     const int d = m.d_model, qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
     const int qkv_w = qd + 2 * kvd, f = m.ffn, es = c->esz, dt = c->dtype;
@@ -367,9 +373,10 @@ int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
             ro.n_q_heads = m.n_q_heads; ro.n_kv_heads = m.n_kv_heads; ro.head_dim = m.head_dim;
             ro.page_tokens = c->ec.page_tokens;
             const double bytes = ((double)qkv_w * d + (double)rows * d) * es + (double)rows * qkv_w * es;
-            const void* wq = layer_ptr(w.wqkv, l, qkv_w, d, es);
+            const bool hw = wh.wqkv && adt == kF16;
+            const void* wq = layer_ptr(hw ? wh.wqkv : w.wqkv, l, qkv_w, d, es);
             HIPCK(c, profiled(c, st, gcls, bytes, 2.0 * rows * qkv_w * d,
-                              [&] { return launch_gemm_rope(st, dt, adt, ws.xn, wq, rows, d, ro); }));
+                              [&] { return launch_gemm_rope(st, hw ? kF16 : dt, adt, ws.xn, wq, rows, d, ro); }));
         } else {
             ns = nsplit_for(c, ws, rows, qkv_w, d);
             HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.xn, layer_ptr(w.wqkv, l, qkv_w, d, es), ws.part, rows, qkv_w, d, ns));
@@ -394,14 +401,19 @@ int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
             }));
         }
         ns = nsplit_for(c, ws, rows, d, qd);
-        HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.attn, layer_ptr(w.wo, l, d, qd, es), ws.part, rows, d, qd, ns));
+        {
+            const bool hw = wh.wo && adt == kF16 && mode == kModeBatch && gemm_is_tall(rows, d, qd, ns);
+            HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.attn, layer_ptr(hw ? wh.wo : w.wo, l, d, qd, es), ws.part, rows,
+                                   d, qd, ns, hw));
+        }
         HIPCK(c, launch_rmsnorm(st, adt, ws.h, ws.part, ns, (size_t)rows * d, nullptr,
                                 w.g_mlp + (size_t)l * d, ws.xn, rows, d, m.rms_eps));
         if (gemm_swiglu_supported(dt, adt, rows, f, d)) {
-            const void* wgu = layer_ptr(w.w_gate_up, l, 2 * (size_t)f, d, es);
+            const bool hw = wh.w_gate_up && adt == kF16 && d % 64 == 0;
+            const void* wgu = layer_ptr(hw ? wh.w_gate_up : w.w_gate_up, l, 2 * (size_t)f, d, es);
             const double bytes = (2.0 * f * d + (double)rows * d) * es + (double)rows * f * es;
             HIPCK(c, profiled(c, st, gcls, bytes, 4.0 * rows * f * d,
-                              [&] { return launch_gemm_swiglu(st, dt, adt, ws.xn, wgu, ws.act, rows, f, d); }));
+                              [&] { return launch_gemm_swiglu(st, hw ? kF16 : dt, adt, ws.xn, wgu, ws.act, rows, f, d); }));
         } else {
             ns = nsplit_for(c, ws, rows, 2 * f, d);
             HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.xn, layer_ptr(w.w_gate_up, l, 2 * (size_t)f, d, es), ws.part,
@@ -410,7 +422,11 @@ int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
         }
         pns = nsplit_for(c, ws, rows, d, f);
         pstride = (size_t)rows * d;
-        HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.act, layer_ptr(w.w_down, l, d, f, es), ws.part, rows, d, f, pns));
+        {
+            const bool hw = wh.w_down && adt == kF16 && mode == kModeBatch && gemm_is_tall(rows, d, f, pns);
+            HIPCK(c, gemm_profiled(c, st, gcls, adt, ws.act, layer_ptr(hw ? wh.w_down : w.w_down, l, d, f, es), ws.part,
+                                   rows, d, f, pns, hw));
+        }
     }
     *pend_ns = pns;
     *pend_stride = pstride;
@@ -434,6 +450,10 @@ extern "C" void rlhf_destroy(rlhf_ctx* c) {
     free_workspace(c->ws_dec);
     free_workspace(c->ws_pre);
     free_workspace(c->ws_score);
+    for (RoleWeights& r : c->roles) {
+        for (void* p : r.owned) (void)hipFree(p);
+        r.owned.clear();
+    }
     c->meta_dec.destroy();
     c->meta_pre.destroy();
     c->meta_score.destroy();
@@ -492,6 +512,8 @@ static int create_impl(rlhf_ctx* c) {
         HIPCK(c, hipGetDevice(&dev));
         HIPCK(c, hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
     }
+    if (e.half_weight_copies != 0 && e.half_weight_copies != 1)
+        return c->fail(RLHF_EINVAL, "half_weight_copies must be 0 or 1");
     if (e.corun_decode_cus < 0 || e.corun_decode_cus >= n_cus || e.corun_decode_cus % 32 || (e.optimistic_admission != 0 && e.optimistic_admission != 1))
         return c->fail(RLHF_EINVAL, "corun_decode_cus must be a multiple of 32 in [0, %d) and optimistic_admission 0 or 1", n_cus);
     auto make_masked = [&](hipStream_t* st, int lo, int hi) -> hipError_t {   // CU-mask bits [lo, hi)
@@ -586,8 +608,45 @@ extern "C" int rlhf_load_weights(rlhf_ctx* c, int role, const rlhf_weights* w) {
     const void* ptrs[] = {w->embed, w->wqkv, w->wo, w->w_gate_up, w->w_down, w->g_attn, w->g_mlp, w->g_final, w->head};
     for (const void* p : ptrs)
         if (p && ((uintptr_t)p & 15)) return c->fail(RLHF_EINVAL, "rlhf_load_weights: tensors must be 16-byte aligned");
-    c->roles[role].w = *w;
-    c->roles[role].bound = true;
+    RoleWeights& rw = c->roles[role];
+    int rc = rlhf_sync(c);                       // nothing in flight may still read copies about to be freed
+    if (rc) return rc;
+    for (void* p : rw.owned) (void)hipFree(p);
+    rw.owned.clear();
+    rw.h16 = rlhf_weights{};
+    rw.w = *w;
+    rw.bound = true;
+    if (c->ec.half_weight_copies && c->dtype == kBF16) {
+        const rlhf_model_cfg& m = c->mc;
+        const size_t d = m.d_model, qd = (size_t)m.n_q_heads * m.head_dim, kvd = (size_t)m.n_kv_heads * m.head_dim;
+        const size_t L = m.n_layers, f = m.ffn;
+        struct Item { const void* src; const void** dst; size_t n; };
+        const Item items[] = {
+            {w->wqkv, &rw.h16.wqkv, L * (qd + 2 * kvd) * d},
+            {w->wo, &rw.h16.wo, L * d * qd},
+            {w->w_gate_up, &rw.h16.w_gate_up, L * 2 * f * d},
+            {w->w_down, &rw.h16.w_down, L * d * f},
+            {w->head, &rw.h16.head, (role == RLHF_ACTOR || role == RLHF_REF) ? (size_t)m.vocab * d : 0},
+        };
+        for (const Item& it : items) {
+            if (it.n == 0 || !it.src) continue;
+            void* p = nullptr;
+            if (hipMalloc(&p, it.n * 2) != hipSuccess) {
+                (void)hipGetLastError();
+                for (void* q : rw.owned) (void)hipFree(q);
+                rw.owned.clear();
+                rw.h16 = rlhf_weights{};
+                rw.bound = false;
+                return c->fail(RLHF_ENOMEM, "rlhf_load_weights: no device memory for the half copies of role %d "
+                                            "(%zu bytes); leave room beside kv_pool_bytes or turn half_weight_copies off",
+                               role, it.n * 2);
+            }
+            rw.owned.push_back(p);
+            HIPCK(c, launch_bf16_to_half(c->sd_full, it.src, p, it.n));
+            *it.dst = p;
+        }
+        HIPCK(c, hipStreamSynchronize(c->sd_full));
+    }
     return RLHF_OK;
 }
 
@@ -740,7 +799,10 @@ int lm_head_chunks(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weight
 // [rows, vocab] logits never reach memory, only 2 * ceil(vocab / 256) (max, sum exp) pairs and the
 // target logit per row, which a merge kernel turns into log-probs.  The partials live in the
 // workspace's logits buffer.
-int lm_head_logprob_fused(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf_weights& w, const HeadPlan& hp) {
+int lm_head_logprob_fused(rlhf_ctx* c, hipStream_t st, Workspace& ws, const RoleWeights& rw, const HeadPlan& hp) {
+    const bool hw = rw.h16.head != nullptr && act_type(c, true) == kF16;
+    const void* head = hw ? rw.h16.head : rw.w.head;
+    const int wdt = hw ? kF16 : c->dtype;
     const rlhf_model_cfg& m = c->mc;
     const int d = m.d_model, V = m.vocab, adt = act_type(c, true);
     const int n_part = gemm_lse_partials(V);
@@ -759,7 +821,7 @@ int lm_head_logprob_fused(rlhf_ctx* c, hipStream_t st, Workspace& ws, const rlhf
         const char* x = (const char*)ws.xsel + (size_t)r0 * d * c->esz;
         const double bytes = ((double)V * d + (double)nr * d) * c->esz + (double)nr * per_row * 4;
         HIPCK(c, profiled(c, st, kGemmBatch, bytes, 2.0 * nr * V * d,
-                          [&] { return launch_gemm_lse(st, c->dtype, adt, x, w.head, nr, V, d, lo); }));
+                          [&] { return launch_gemm_lse(st, wdt, adt, x, head, nr, V, d, lo); }));
         HIPCK(c, launch_lse_merge(st, lo.part_max, lo.part_sum, lo.tgt, n_part, nr, hp.out, hp.out_dst + r0,
                                   c->d_nonfinite));
     }
@@ -876,7 +938,7 @@ int prefill_group(rlhf_ctx* c, const std::vector<int>& group, int T) {
     Workspace& ws = c->ws_pre;
     int pns;
     size_t pstride;
-    int rc = forward_layers(c, c->sd, ws, w, T, pm, kModeBatch, 1, &pns, &pstride);
+    int rc = forward_layers(c, c->sd, ws, c->roles[RLHF_ACTOR], T, pm, kModeBatch, 1, &pns, &pstride);
     if (rc) return rc;
     if (n_sel > 0) {
         HIPCK(c, launch_rmsnorm(c->sd, act_type(c, true), ws.h, ws.part, pns, pstride, dm_ + 4 * T, w.g_final, ws.xsel,
@@ -957,7 +1019,7 @@ int decode_rows(rlhf_ctx* c, const std::vector<int>& rows_ids) {
     const rlhf_weights& w = c->roles[RLHF_ACTOR].w;
     int pns;
     size_t pstride;
-    int rc = forward_layers(c, c->sd, ws, w, R, pm, kModeDecode, asplit, &pns, &pstride);
+    int rc = forward_layers(c, c->sd, ws, c->roles[RLHF_ACTOR], R, pm, kModeDecode, asplit, &pns, &pstride);
     if (rc) return rc;
     const int d = c->mc.d_model, V = c->mc.vocab;
     HIPCK(c, launch_rmsnorm(c->sd, act_type(c, false), ws.h, ws.part, pns, pstride, nullptr, w.g_final, ws.xsel, R, d,
@@ -1206,7 +1268,7 @@ int score_pass(rlhf_ctx* c, hipStream_t st, MetaRing& meta, Workspace& ws, const
     const rlhf_weights& w = c->roles[role].w;
     int pns;
     size_t pstride;
-    int rc = forward_layers(c, st, ws, w, T, pm, kModeBatch, 1, &pns, &pstride);
+    int rc = forward_layers(c, st, ws, c->roles[role], T, pm, kModeBatch, 1, &pns, &pstride);
     if (rc) return rc;
     const int d = c->mc.d_model;
     // selected rows may exceed the workspace rows only if n_sel > T, which cannot happen
@@ -1228,7 +1290,7 @@ int score_pass(rlhf_ctx* c, hipStream_t st, MetaRing& meta, Workspace& ws, const
         hp.target_idx = dmeta + 3 * T + n_sel;
         hp.out_dst = dmeta + 3 * T + 2 * n_sel;
         hp.out = role == RLHF_REF ? c->d_lp_ref : c->d_lp_rescored;
-        rc = gemm_lse_supported(c->dtype, adt, d) ? lm_head_logprob_fused(c, st, ws, w, hp)
+        rc = gemm_lse_supported(c->dtype, adt, d) ? lm_head_logprob_fused(c, st, ws, c->roles[role], hp)
                                                   : lm_head_chunks(c, st, ws, w, hp, false);
         if (rc) return rc;
     }

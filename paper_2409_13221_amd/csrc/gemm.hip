@@ -96,8 +96,12 @@ __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int& 
 // each wave's 128 columns of a row to (max, sum of exp(z - max)), writes that pair as one of the
 // row's 2 * tiles_n partials, and the lane that holds the row's target column stores that logit.
 // A small merge kernel turns the partials into log_softmax(z)[target] (k_lse_merge).
+//
+// BDMA: W is IEEE half in memory (a copy of the bf16 matrix made when the weights were bound) and
+// takes the same direct global -> LDS path as the activations: no staging registers, no
+// conversion, no LDS stores in the loop.  Needs ADMA's conditions and half activations.
 template <int TM, int TN, int TK, int WM, int WN, bool AF16, bool XCD, bool SWIGLU, bool ADMA = false, int ROPE = 0,
-          bool LSE = false>
+          bool LSE = false, bool BDMA = false>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __restrict__ A,
                                                            const bf16_t* __restrict__ W,
                                                            float* __restrict__ C, int M, int N, int K,
@@ -136,10 +140,27 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
             da[i] = (size_t)min(m0 + row, M - 1) * K + c * 8;
         }
     }
+    static_assert(!BDMA || (ADMA && AF16), "half weights go with half activations on the direct path");
+    constexpr int DB_IT = BDMA ? TN / D_RPB / (NT / 64) : 1;
+    static_assert(!BDMA || (TN / D_RPB) % (NT / 64) == 0, "W tile blocks must divide among the waves");
+    size_t db[DB_IT];
+    if (BDMA) {
+#pragma unroll
+        for (int i = 0; i < DB_IT; ++i) {
+            const int row = (w * DB_IT + i) * D_RPB + lane / CH, p = lane % CH;
+            const int c = swz<TK>(row, p);
+            int gn = min(n0 + row, N - 1);        // rows past N are clamped (computed, never stored)
+            if (SWIGLU) {
+                const int oc = min((n0 >> 1) + (row >> 5) * 16 + (row & 15), (N >> 1) - 1);
+                gn = ((row >> 4) & 1) * (N >> 1) + oc;
+            }
+            db[i] = (size_t)gn * K + c * 8;
+        }
+    }
     typedef __attribute__((address_space(3))) void* lds_ptr_t;
     typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
-    uint4 ra[ADMA ? 1 : A_IT], rb[B_IT];
+    uint4 ra[ADMA ? 1 : A_IT], rb[BDMA ? 1 : B_IT];
     auto gload = [&](int kt, uint4* ra, uint4* rb) {
         const int k0 = kbeg + kt * TK;
         if (ADMA) {
@@ -149,6 +170,12 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
             for (int i = 0; i < D_IT; ++i)
                 __builtin_amdgcn_global_load_lds((glb_ptr_t)(A + da[i] + k0),
                                                  (lds_ptr_t)&sA[kt & 1][(w * D_IT + i) * 512], 16, 0, 0);
+        }
+        if (BDMA) {
+#pragma unroll
+            for (int i = 0; i < DB_IT; ++i)
+                __builtin_amdgcn_global_load_lds((glb_ptr_t)(W + db[i] + k0),
+                                                 (lds_ptr_t)&sB[kt & 1][(w * DB_IT + i) * 512], 16, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < (ADMA ? 0 : A_IT); ++i) {
@@ -160,7 +187,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
                 ra[i] = *reinterpret_cast<const uint4*>(A + (size_t)gm * K + gk);
         }
 #pragma unroll
-        for (int i = 0; i < B_IT; ++i) {
+        for (int i = 0; i < (BDMA ? 0 : B_IT); ++i) {
             const int idx = t + i * NT;
             const int row = idx / CH, c = idx % CH;
             int gn = n0 + row;
@@ -185,10 +212,10 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
                 *reinterpret_cast<uint4*>(&sA[buf][row * TK + swz<TK>(row, c) * 8]) = ra[i];
         }
 #pragma unroll
-        for (int i = 0; i < B_IT; ++i) {
+        for (int i = 0; i < (BDMA ? 0 : B_IT); ++i) {
             const int idx = t + i * NT;
             const int row = idx / CH, c = idx % CH;
-            if (AF16) {   // bf16 -> half, exact, once per element per workgroup
+            if (AF16) {   // bf16 -> half once per element per workgroup (exact in half's normal range)
                 rb[i].x = bf16x2_to_f16x2(rb[i].x); rb[i].y = bf16x2_to_f16x2(rb[i].y);
                 rb[i].z = bf16x2_to_f16x2(rb[i].z); rb[i].w = bf16x2_to_f16x2(rb[i].w);
             }
@@ -545,11 +572,32 @@ constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 // the 256 x 256 tiling, unless its tiles would leave much of the chip idle (a prefill of a few
 // hundred tokens, a narrow N): then 128 x 128 tiles with K split, which trades some efficiency
 // per workgroup for having all compute units busy.
-int pick_variant(int M, int N) {
+// 129..256 rows of a large matrix: one row of 256 x 256 tiles, K split so that the tiles times the
+// splits come close to, and never exceed, one workgroup per compute unit (a second round of such
+// workgroups costs more than it adds: at M = 256 the 7B-shape QKV takes 42.8 us with 4 splits = 192
+// workgroups, 60 us with 6 = 288; gate||up 71 us with 2 = 172, 96 us with 3 = 258; against 54 and
+// 97 us for 128 x 128 tiles).  Returns 0 when the tall tiling is not the better one.
+int tall_split_for_mid_rows(int M, int N, int K, int max_split) {
+    if (M <= 128 || M > 256 || K % 64 || (long)N * K < 40L * 1000 * 1000) return 0;
+    const int tiles = (N + 255) / 256;
+    int ns = 256 / tiles;
+    if (ns > K / 256) ns = K / 256;          // at least four K tiles per split
+    if (ns > 16) ns = 16;
+    if (ns > max_split) ns = max_split;
+    if (ns < 1 || tiles * ns < 160) return 0;
+    while (ns > 1) {                          // every split gets a K range
+        const int kchunk = ((K + ns - 1) / ns + 63) / 64 * 64;
+        if ((long)(ns - 1) * kchunk < K) break;
+        --ns;
+    }
+    return ns;
+}
+
+int pick_variant(int M, int N, int K = 0, int nsplit = 0) {
     if (M <= 16) return 1;
     if (M <= 32) return 2;
     if (M <= 64) return 3;
-    if (M <= 256) return 4;
+    if (M <= 256) return (K > 0 && nsplit > 0 && tall_split_for_mid_rows(M, N, K, nsplit) == nsplit) ? 7 : 4;
     const long tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
     const long rounds = (tiles + 255) / 256;            // one 256 x 256 tile per compute unit at a time
     return tiles * 10 >= rounds * 256 * 6 ? 7 : 4;      // at least 60 % of the tile slots filled
@@ -557,9 +605,28 @@ int pick_variant(int M, int N) {
 constexpr int kTargetBlocks = 1024;      // about four workgroups per compute unit (tiles of up to 64 rows)
 }  // namespace
 
+// True when launch_gemm would run the 256 x 256 tiling for this shape and split (the shapes for
+// which a half copy of the weights, if there is one, is the better operand).
+bool gemm_is_tall(int M, int N, int K, int nsplit) { return K % 64 == 0 && kCfgs[pick_variant(M, N, K, nsplit)].xcd; }
+
+// bf16 -> IEEE half, element by element (round toward zero; exact in half's normal range, values
+// below 2^-14 land on half's subnormal grid): the same conversion the kernels apply on the fly.
+__global__ void k_bf16_to_half(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, size_t n_pairs) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_pairs; i += (size_t)gridDim.x * 256)
+        dst[i] = bf16x2_to_f16x2(src[i]);
+}
+hipError_t launch_bf16_to_half(hipStream_t st, const void* src, void* dst, size_t n) {
+    if (n == 0) return hipSuccess;
+    if (n % 2) return hipErrorInvalidValue;
+    k_bf16_to_half<<<4096, 256, 0, st>>>((const uint32_t*)src, (uint32_t*)dst, n / 2);
+    return hipGetLastError();
+}
+
 int gemm_choose_nsplit(int wdt, int M, int N, int K, int max_split) {
     int tm, tn, kgran;
     if (wdt == kBF16) {
+        const int tall = tall_split_for_mid_rows(M, N, K, max_split);
+        if (tall > 0) return tall;
         const TileCfg& c = kCfgs[pick_variant(M, N)];
         if (c.xcd) return 1;
         tm = c.tm; tn = c.tn; kgran = c.tk;
@@ -626,8 +693,12 @@ static hipError_t launch_bf16(hipStream_t st, int variant, const bf16_t* a, cons
     return hipGetLastError();
 }
 
+// wdt == kF16: the matrix is a half copy of the bf16 weights and goes global -> LDS directly.
+static bool half_weights_ok(int wdt, int adt, int K) { return wdt != kF16 || (adt == kF16 && K % 64 == 0); }
+
 bool gemm_swiglu_supported(int wdt, int adt, int M, int ffn, int K) {
-    return wdt == kBF16 && (adt == kF16 || adt == kBF16) && M >= 512 && ffn % 8 == 0 && K % 8 == 0;
+    return (wdt == kBF16 || wdt == kF16) && half_weights_ok(wdt, adt, K) && (adt == kF16 || adt == kBF16) && M >= 512 &&
+           ffn % 8 == 0 && K % 8 == 0;
 }
 
 hipError_t launch_gemm_swiglu(hipStream_t st, int wdt, int adt, const void* A, const void* W_gate_up,
@@ -642,15 +713,18 @@ hipError_t launch_gemm_swiglu(hipStream_t st, int wdt, int adt, const void* A, c
     k_gemm_bf16<TM, TN, 64, 4, 2, AF, true, true, DMA><<<grid, 512, 0, st>>>( \
         (const bf16_t*)A, (const bf16_t*)W_gate_up, (float*)act, M, N, K, kchunk, tiles_m, tiles_n)
     const bool dma = K % 64 == 0;
-    if (adt == kF16) { if (dma) RLHF_SWIGLU(true, true); else RLHF_SWIGLU(true, false); }
+    if (wdt == kF16)
+        k_gemm_bf16<TM, TN, 64, 4, 2, true, true, true, true, 0, false, true><<<grid, 512, 0, st>>>(
+            (const bf16_t*)A, (const bf16_t*)W_gate_up, (float*)act, M, N, K, kchunk, tiles_m, tiles_n);
+    else if (adt == kF16) { if (dma) RLHF_SWIGLU(true, true); else RLHF_SWIGLU(true, false); }
     else { if (dma) RLHF_SWIGLU(false, true); else RLHF_SWIGLU(false, false); }
 #undef RLHF_SWIGLU
     return hipGetLastError();
 }
 
 bool gemm_rope_supported(int wdt, int adt, int M, int K, const Dims& dm) {
-    return wdt == kBF16 && (adt == kF16 || adt == kBF16) && M >= 512 && K % 64 == 0 &&
-           (dm.head_dim == 64 || dm.head_dim == 128);
+    return (wdt == kBF16 || wdt == kF16) && half_weights_ok(wdt, adt, K) && (adt == kF16 || adt == kBF16) && M >= 512 &&
+           K % 64 == 0 && (dm.head_dim == 64 || dm.head_dim == 128);
 }
 
 hipError_t launch_gemm_rope(hipStream_t st, int wdt, int adt, const void* A, const void* Wqkv, int M, int K,
@@ -668,14 +742,19 @@ hipError_t launch_gemm_rope(hipStream_t st, int wdt, int adt, const void* A, con
 #define RLHF_ROPE(AF, HD)                                                                             \
     k_gemm_bf16<TM, TN, 64, 4, 2, AF, true, false, true, HD><<<grid, 512, 0, st>>>(a, w, nullptr, M, N, K, K, \
                                                                                    tiles_m, tiles_n, ro)
-    if (adt == kF16) { if (ro.head_dim == 128) RLHF_ROPE(true, 128); else RLHF_ROPE(true, 64); }
+#define RLHF_ROPE_HALF_W(HD)                                                                                    \
+    k_gemm_bf16<TM, TN, 64, 4, 2, true, true, false, true, HD, false, true><<<grid, 512, 0, st>>>(a, w, nullptr, M, N, \
+                                                                                                  K, K, tiles_m, tiles_n, ro)
+    if (wdt == kF16) { if (ro.head_dim == 128) RLHF_ROPE_HALF_W(128); else RLHF_ROPE_HALF_W(64); }
+    else if (adt == kF16) { if (ro.head_dim == 128) RLHF_ROPE(true, 128); else RLHF_ROPE(true, 64); }
     else { if (ro.head_dim == 128) RLHF_ROPE(false, 128); else RLHF_ROPE(false, 64); }
 #undef RLHF_ROPE
+#undef RLHF_ROPE_HALF_W
     return hipGetLastError();
 }
 
 bool gemm_lse_supported(int wdt, int adt, int K) {
-    return wdt == kBF16 && (adt == kF16 || adt == kBF16) && K % 64 == 0;
+    return (wdt == kBF16 || wdt == kF16) && half_weights_ok(wdt, adt, K) && (adt == kF16 || adt == kBF16) && K % 64 == 0;
 }
 
 int gemm_lse_partials(int N) { return (N + 255) / 256 * 2; }
@@ -691,7 +770,10 @@ hipError_t launch_gemm_lse(hipStream_t st, int wdt, int adt, const void* A, cons
     dim3 grid((tiles_m * tiles_n + 7) / 8 * 8, 1);
     const bf16_t* a = (const bf16_t*)A;
     const bf16_t* w = (const bf16_t*)W_head;
-    if (adt == kF16)
+    if (wdt == kF16)
+        k_gemm_bf16<TM, TN, 64, 4, 2, true, true, false, true, 0, true, true><<<grid, 512, 0, st>>>(
+            a, w, nullptr, M, N, K, K, tiles_m, tiles_n, RopeOut{}, lo);
+    else if (adt == kF16)
         k_gemm_bf16<TM, TN, 64, 4, 2, true, true, false, true, 0, true><<<grid, 512, 0, st>>>(
             a, w, nullptr, M, N, K, K, tiles_m, tiles_n, RopeOut{}, lo);
     else
@@ -704,12 +786,23 @@ hipError_t launch_gemm(hipStream_t st, int wdt, int adt, const void* A, const vo
                        int M, int N, int K, int nsplit, int variant) {
     if (M <= 0 || N <= 0) return hipSuccess;
     if (nsplit < 1 || K <= 0) return hipErrorInvalidValue;
+    if (wdt == kF16) {
+        // half copy of a bf16 matrix: the tall tiling with both operands global -> LDS directly
+        if (adt != kF16 || K % 64 || (variant != 0 && variant != 7)) return hipErrorInvalidValue;
+        const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+        const int kchunk = ((K + nsplit - 1) / nsplit + 63) / 64 * 64;
+        if ((long)(nsplit - 1) * kchunk >= K) return hipErrorInvalidValue;
+        dim3 grid((tiles_m * tiles_n + 7) / 8 * 8, nsplit);
+        k_gemm_bf16<256, 256, 64, 4, 2, true, true, false, true, 0, false, true><<<grid, 512, 0, st>>>(
+            (const bf16_t*)A, (const bf16_t*)W, C, M, N, K, kchunk, tiles_m, tiles_n);
+        return hipGetLastError();
+    }
     if (wdt == kBF16) {
         if (adt != kBF16 && adt != kF16) return hipErrorInvalidValue;
         if (K % 8 || variant < 0 || variant >= kNumCfgs) return hipErrorInvalidValue;
         if (variant == 0) {
-            variant = pick_variant(M, N);
-            if (kCfgs[variant].xcd && nsplit != 1) variant = 4;   // a caller-imposed split of a tall GEMM
+            variant = pick_variant(M, N, K, nsplit);
+            if (kCfgs[variant].xcd && nsplit != 1 && M > 256) variant = 4;   // a caller-imposed split of a tall GEMM
         }
         const bf16_t* a = (const bf16_t*)A;
         const bf16_t* w = (const bf16_t*)W;

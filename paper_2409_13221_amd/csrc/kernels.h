@@ -23,6 +23,11 @@ struct Dims {
 // ---- GEMM: C[s][m][n] = sum over k in split s of A[m][k] * W[n][k];  C float, split stride M*N
 // (wdt, adt) in {(kF32,kF32), (kBF16,kBF16), (kBF16,kF16)}
 int gemm_choose_nsplit(int wdt, int M, int N, int K, int max_split);
+// wdt == kF16 (with adt == kF16, K a multiple of 64): W is a half copy of a bf16 matrix, made with
+// launch_bf16_to_half; the 256 x 256 tiling then loads both operands global -> LDS directly.  The
+// fused-epilogue launchers below accept it too.  gemm_is_tall: the shapes launch_gemm runs with that tiling.
+bool gemm_is_tall(int M, int N, int K, int nsplit);
+hipError_t launch_bf16_to_half(hipStream_t st, const void* src, void* dst, size_t n_elements);
 // variant 0 = the tiling chosen from M; > 0 forces one (tuning / benchmarks).
 hipError_t launch_gemm(hipStream_t st, int wdt, int adt, const void* A, const void* W, float* C,
                        int M, int N, int K, int nsplit, int variant = 0);

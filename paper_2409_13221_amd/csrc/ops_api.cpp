@@ -58,6 +58,10 @@ extern "C" int rlhf_op_gemm_nsplit(int dtype, int M, int N, int K, int max_split
 extern "C" int rlhf_op_gemm(int dtype, int act_half, const void* A, const void* W, float* C, int M, int N,
                             int K, int nsplit, int variant, void* stream) {
     if (!A || !W || !C || M < 0 || N < 0 || K <= 0 || nsplit < 1) return RLHF_EINVAL;
+    if (dtype == 2) {        // W is a half copy of a bf16 matrix (rlhf_op_bf16_to_half), A is half
+        if (!act_half) return RLHF_EINVAL;
+        return status_of(launch_gemm((hipStream_t)stream, kF16, kF16, A, W, C, M, N, K, nsplit, variant));
+    }
     if (dtype != RLHF_BF16 && dtype != RLHF_FP32) return RLHF_EINVAL;
     if (act_half && dtype != RLHF_BF16) return RLHF_EINVAL;
     const int wdt = dtype == RLHF_BF16 ? kBF16 : kF32;
@@ -135,9 +139,9 @@ extern "C" int rlhf_op_flash_attention(const void* q, const void* k, const void*
 extern "C" int rlhf_op_gemm_swiglu(int act_half, const void* A, const void* W_gate_up, void* act, int M, int ffn,
                                    int K, void* stream) {
     if (!A || !W_gate_up || !act) return RLHF_EINVAL;
-    const int adt = act_half ? kF16 : kBF16;
-    if (!gemm_swiglu_supported(kBF16, adt, M, ffn, K)) return RLHF_EINVAL;
-    return status_of(launch_gemm_swiglu((hipStream_t)stream, kBF16, adt, A, W_gate_up, act, M, ffn, K));
+    const int adt = act_half ? kF16 : kBF16, wdt = act_half == 2 ? kF16 : kBF16;
+    if (!gemm_swiglu_supported(wdt, adt, M, ffn, K)) return RLHF_EINVAL;
+    return status_of(launch_gemm_swiglu((hipStream_t)stream, wdt, adt, A, W_gate_up, act, M, ffn, K));
 }
 
 extern "C" int rlhf_op_gemm_rope(int act_half, const void* A, const void* W_qkv, const int32_t* pos,
@@ -147,15 +151,15 @@ extern "C" int rlhf_op_gemm_rope(int act_half, const void* A, const void* W_qkv,
     if (!A || !W_qkv || !pos || !table || !q || (pool && !kv_dst) || n_q_heads <= 0 || n_kv_heads <= 0 ||
         n_q_heads % n_kv_heads || layer < 0 || layer >= n_layers)
         return RLHF_EINVAL;
-    const int adt = act_half ? kF16 : kBF16;
+    const int adt = act_half ? kF16 : kBF16, wdt = act_half == 2 ? kF16 : kBF16;
     Dims dm{n_layers, K, n_q_heads, n_kv_heads, head_dim, 0, 0, 16};
-    if (!gemm_rope_supported(kBF16, adt, M, K, dm)) return RLHF_EINVAL;
+    if (!gemm_rope_supported(wdt, adt, M, K, dm)) return RLHF_EINVAL;
     RopeOut ro;
     ro.pos = pos; ro.kv_dst = kv_dst; ro.table = table;
     ro.q = q; ro.k = k; ro.v = v; ro.pool = pool;
     ro.layer = layer; ro.n_layers = n_layers;
     ro.n_q_heads = n_q_heads; ro.n_kv_heads = n_kv_heads; ro.head_dim = head_dim;
-    return status_of(launch_gemm_rope((hipStream_t)stream, kBF16, adt, A, W_qkv, M, K, ro));
+    return status_of(launch_gemm_rope((hipStream_t)stream, wdt, adt, A, W_qkv, M, K, ro));
 }
 
 // ---- row-wise kernels
@@ -233,8 +237,8 @@ extern "C" int rlhf_op_lm_head_logprob(int act_half, const void* A, const void* 
                                        float* scratch, int M, int vocab, int K, void* stream) {
     if (!A || !W_head || !tokens || !target_idx || !out || !out_dst || !scratch || M < 0 || vocab < 1 || K <= 0)
         return RLHF_EINVAL;
-    const int adt = act_half ? kF16 : kBF16;
-    if (!gemm_lse_supported(kBF16, adt, K)) return RLHF_EINVAL;
+    const int adt = act_half ? kF16 : kBF16, wdt = act_half == 2 ? kF16 : kBF16;
+    if (!gemm_lse_supported(wdt, adt, K)) return RLHF_EINVAL;
     LseOut lo;
     lo.n_part = gemm_lse_partials(vocab);
     lo.tokens = tokens;
@@ -242,8 +246,13 @@ extern "C" int rlhf_op_lm_head_logprob(int act_half, const void* A, const void* 
     lo.part_max = scratch;
     lo.part_sum = scratch + (size_t)M * lo.n_part;
     lo.tgt = scratch + (size_t)2 * M * lo.n_part;
-    hipError_t e = launch_gemm_lse((hipStream_t)stream, kBF16, adt, A, W_head, M, vocab, K, lo);
+    hipError_t e = launch_gemm_lse((hipStream_t)stream, wdt, adt, A, W_head, M, vocab, K, lo);
     if (e == hipSuccess)
         e = launch_lse_merge((hipStream_t)stream, lo.part_max, lo.part_sum, lo.tgt, lo.n_part, M, out, out_dst);
     return status_of(e);
+}
+
+extern "C" int rlhf_op_bf16_to_half(const void* src, void* dst, int64_t n, void* stream) {
+    if (!src || !dst || n < 0 || n % 2) return RLHF_EINVAL;
+    return status_of(launch_bf16_to_half((hipStream_t)stream, src, dst, (size_t)n));
 }

@@ -67,7 +67,7 @@ class GpuStage:
     def __init__(self, cfg: WorkloadCfg, inp: dict, pool_pages: Optional[int] = None,
                  max_active: Optional[int] = None, max_batch_tokens: Optional[int] = None,
                  stop_on_eos: bool = False, max_new_cap: Optional[int] = None, corun_decode_cus: int = 0,
-                 optimistic: bool = False):
+                 optimistic: bool = False, half_weight_copies: bool = False):
         import paper_2409_13221_amd as R
         self.R = R
         self.cfg = cfg
@@ -87,7 +87,8 @@ class GpuStage:
         mc.n_layers = ly
         ec = R.rlhf_engine_cfg(cfg.page_tokens, self.pool_pages * page_bytes(cfg, ly), self.n, self.max_ctx,
                                self.max_active,
-                               max(self.max_ctx, max_batch_tokens or 0), cfg.eos_id, int(stop_on_eos), corun_decode_cus, int(optimistic), None, None)
+                               max(self.max_ctx, max_batch_tokens or 0), cfg.eos_id, int(stop_on_eos), corun_decode_cus, int(optimistic), None, None,
+                               int(half_weight_copies))
         self.dev_weights = [{k: v.to("cuda").contiguous() for k, v in w.items()} for w in inp["weights"]]
         self.ctx = R.rlhf_create(mc, ec)
         for role, w in enumerate(self.dev_weights):

@@ -32,7 +32,7 @@ def test_binding_structs_match_header_sizes():
     would corrupt arguments silently)."""
     import paper_2409_13221_amd.binding as B
     assert ctypes.sizeof(B.rlhf_model_cfg) == 8 * 4 + 2 * 4
-    assert ctypes.sizeof(B.rlhf_engine_cfg) == 4 + 4 + 8 + 8 * 4 + 2 * 8      # padding after page_tokens
+    assert ctypes.sizeof(B.rlhf_engine_cfg) == 4 + 4 + 8 + 8 * 4 + 2 * 8 + 8  # padding after page_tokens and at the end
     assert ctypes.sizeof(B.rlhf_weights) == 9 * 8
     assert ctypes.sizeof(B.rlhf_step_info) == 6 * 4
     assert ctypes.sizeof(B.rlhf_stage_opts) == 4 * 4 + 5 * 8 + 8

@@ -254,3 +254,84 @@ def test_gemm_rope_fused(half_act, M, K, Hq, Hkv, hd, with_pool):
     else:
         close(k, want_k)
         close(v, want_v)
+
+
+@pytest.mark.parametrize("M,N,K", [(200, 12288, 4096), (256, 4096, 11008), (129, 22016, 4096)])
+def test_gemm_mid_rows_take_the_tall_tiling_with_split_k(M, N, K):
+    """129..256 rows of a large matrix run as one row of 256 x 256 tiles with K split over the
+    compute units (the split the stage itself chooses); uneven last split included."""
+    R = _R()
+    r = np.random.default_rng(M + N)
+    A = torch.from_numpy(r.normal(size=(M, K)).astype(np.float32)).half().cuda()
+    W = _bf16_round(r.normal(size=(N, K)) * 0.02).cuda()
+    ns = R.rlhf_op_gemm_nsplit(R.RLHF_BF16, M, N, K, 16)
+    assert ns > 1 and -(-N // 256) * ns <= 256
+    want = A.double().cpu().numpy() @ W.double().cpu().numpy().T
+    out = torch.full((ns, M, N), float("nan"), device="cuda")
+    R.rlhf_op_gemm(A, W, out, ns)
+    torch.cuda.synchronize()
+    got = out.double().sum(0).cpu().numpy()
+    np.testing.assert_allclose(got, want, rtol=0, atol=3e-5 * np.sqrt(K))
+
+
+# ------------------------------------------- half copies of the weights (both operands direct to LDS)
+
+def test_half_weight_copies_give_bit_identical_tall_gemms():
+    """With an IEEE-half copy of the bf16 matrix (the library's own conversion) the tall kernels load
+    both operands global -> LDS directly; plain, split-K, SwiGLU, rotary and LM-head epilogues must
+    reproduce the bf16-weight path bit for bit (same half values, same accumulation order) and so
+    match float64 like it does."""
+    R = _R()
+    r = np.random.default_rng(77)
+    M, K = 700, 512
+    A = torch.from_numpy(r.normal(size=(M, K)).astype(np.float32)).half().cuda()
+    # a share of tiny weights exercises half's subnormal range in the conversion
+    w = r.normal(size=(1300, K)) * 0.02
+    w[::7] *= 1e-4
+    W = _bf16_round(w).cuda()
+    Wh = R.rlhf_op_bf16_to_half(W)
+    torch.cuda.synchronize()
+    wd, whd = W.double().cpu().numpy(), Wh.double().cpu().numpy()
+    big = np.abs(wd) >= 2.0 ** -14
+    np.testing.assert_array_equal(whd[big], wd[big])                         # exact in the normal range
+    assert np.all(np.abs(whd - wd) < 2.0 ** -24) and np.all(np.abs(whd) <= np.abs(wd))   # toward zero below it
+    # plain, one split and three
+    for ns in (1, 3):
+        a = torch.full((ns, M, 1300), float("nan"), device="cuda")
+        b = torch.full((ns, M, 1300), float("nan"), device="cuda")
+        R.rlhf_op_gemm(A, W, a, ns, 7)
+        R.rlhf_op_gemm(A, Wh, b, ns)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b)
+        np.testing.assert_allclose(b.double().sum(0).cpu().numpy(), A.double().cpu().numpy() @ whd.T, rtol=0, atol=3e-5)
+    # SwiGLU epilogue (648 output columns: a ragged last tile)
+    act_a = torch.full((M, 648), float("nan"), dtype=torch.float16, device="cuda")
+    act_b = torch.full_like(act_a, float("nan"))
+    R.rlhf_op_gemm_swiglu(A, W[:1296].contiguous(), act_a)
+    R.rlhf_op_gemm_swiglu(A, Wh[:1296].contiguous(), act_b)
+    # rotary epilogue: 6 query + 2 x 2 KV heads of 128 -> 1280 rows of W
+    Hq, Hkv, hd = 6, 2, 128
+    pos = torch.from_numpy(r.integers(0, 300, size=M).astype(np.int32)).cuda()
+    ang = np.arange(300)[:, None] * 10000.0 ** (-2.0 * np.arange(hd // 2) / hd)[None, :]
+    table = torch.from_numpy(np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32)).cuda()
+    outs = []
+    for Wx in (W[:1280].contiguous(), Wh[:1280].contiguous()):
+        q = torch.full((M, Hq * hd), float("nan"), dtype=torch.float16, device="cuda")
+        k = torch.full((M, Hkv * hd), float("nan"), dtype=torch.float16, device="cuda")
+        v = torch.full_like(k, float("nan"))
+        R.rlhf_op_gemm_rope(A, Wx, pos, table, q, k, v, None, None, 0, 1, Hq, Hkv, hd)
+        outs.append((q, k, v))
+    # LM head fused with the log-softmax gather over a vocabulary of 1300
+    tokens = torch.from_numpy(r.integers(0, 1300, size=M).astype(np.int32)).cuda()
+    idx = torch.arange(M, dtype=torch.int32, device="cuda")
+    lp_a, lp_b = torch.zeros(M, device="cuda"), torch.zeros(M, device="cuda")
+    keep = [R.rlhf_op_lm_head_logprob(A, W, tokens, idx, lp_a, idx), R.rlhf_op_lm_head_logprob(A, Wh, tokens, idx, lp_b, idx)]
+    torch.cuda.synchronize()
+    del keep
+    assert torch.equal(act_a, act_b) and torch.isfinite(act_b).all()
+    for x, y in zip(*outs):
+        assert torch.equal(x, y) and torch.isfinite(y).all()
+    assert torch.equal(lp_a, lp_b)
+    z = A.double().cpu().numpy() @ whd.T
+    want = OT.log_softmax_rows(z)[np.arange(M), tokens.cpu().numpy()]
+    np.testing.assert_allclose(lp_b.cpu().numpy(), want, rtol=0, atol=1e-4)

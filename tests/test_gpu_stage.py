@@ -431,3 +431,15 @@ def test_auto_plan_picks_serial_for_launch_bound_models(tiny_ref, gpt2s_ref):
             assert stats.fused_used == 0
             assert g.snapshot()["batches"] == model.batches
             H.compare_stage(cfg, ref, g.results())
+
+
+def test_half_weight_copies_do_not_change_results(gpt2s_ref):
+    """The engine option that keeps IEEE-half copies of the matrices for prefill / scoring passes:
+    the whole GPT-2-small-shape stage (prefill passes of more than 512 rows included) gives
+    bit-identical outputs with and without it, and they match the oracle."""
+    cfg, ref = gpt2s_ref
+    a = H.run_gpu_stage(cfg, ref, fused=True, R_t=7, chunk_tokens=600)
+    b = H.run_gpu_stage(cfg, ref, fused=True, R_t=7, chunk_tokens=600, half_weight_copies=True)
+    H.compare_stage(cfg, ref, b)
+    for k in ("tokens", "lp_actor", "lp_ref", "values", "reward", "lp_actor_rescored"):
+        np.testing.assert_array_equal(a[k], b[k])

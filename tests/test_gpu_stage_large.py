@@ -127,9 +127,10 @@ def test_7b_full_config_properties(optimistic):
     inp = H.make_inputs(cfg, weight_device="cuda")
     print("[7b full] weights ready", flush=True)
     free_b, _ = torch.cuda.mem_get_info()
-    pool_pages = int((free_b - (24 << 30)) // H.page_bytes(cfg))
+    # as bench.py: half copies of the four roles' matrices live beside the pool
+    pool_pages = int((free_b - (24 << 30) - 4 * cfg.model.decode_weight_bytes()) // H.page_bytes(cfg))
     with H.GpuStage(cfg, inp, pool_pages=pool_pages, max_new_cap=cfg.length_cap, max_batch_tokens=8192,
-                    optimistic=optimistic) as g:
+                    optimistic=optimistic, half_weight_copies=True) as g:
         assert g.pool_pages < int(np.ceil((g.plen + g.max_new) / 16).sum())      # cap reservations would not fit
         g.submit(None)
         model = H.scheduler_model_for(g)
