@@ -173,12 +173,14 @@ def rooflines(prof, dtype, steps):
 
 
 def micro(args):
-    """Kernel-level cases at the 7B layer shapes through the ops ABI, for rocprofv3 counter runs:
-    a 1 GiB device copy (calibration of FETCH_SIZE / WRITE_SIZE), the four projections of a
-    scoring pass (M = --micro_rows, half activations, rotary fused into QKV and SwiGLU into gate||up as
-    in the stage),
-    the same four in the decode regime (M = 8), and paged decode attention (32 samples x 1024
-    cached tokens, 32 heads x 128, half)."""
+    """Kernel-level cases at the 7B layer shapes through the ops ABI, for rocprofv3 counter runs and
+    per-kernel timings.  In dispatch order: a 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE);
+    the four projections of a scoring pass at M = --micro_rows (half activations, half copies of the
+    weights, rotary fused into QKV and SwiGLU into gate||up, as the stage runs them) and the LM head
+    fused with the log-softmax gather at M = 2048; the four projections in the decode regime at
+    M = 8, 32, 64, 128, 256 (the five tilings of a decode step); paged decode attention (32 samples x
+    1024 cached tokens, 32 heads x 128, half).  Each case launches exactly one GEMM / attention /
+    copy kernel per call, 1 + --micro_reps calls."""
     import torch
 
     import paper_2409_13221_amd as R
@@ -197,7 +199,7 @@ def micro(args):
         torch.cuda.synchronize()
         us = e0.elapsed_time(e1) / reps * 1e3
         out.append({"case": name, "us": round(us, 1), "GBps": round(bytes_ / us / 1e3, 1),
-                    "TFLOPs": round(flops / us / 1e6, 1), "alg_bytes": bytes_})
+                    "TFLOPs": round(flops / us / 1e6, 1), "alg_bytes": bytes_, "alg_flops": flops})
         log(f"[micro] {name}: {us:.1f} us, {bytes_ / us / 1e3:.0f} GB/s, {flops / us / 1e6:.0f} TFLOP/s")
 
     src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -205,30 +207,49 @@ def micro(args):
     timed("copy_1GiB", lambda: dst.copy_(src), 2.0 * src.numel() * 4, 0)
     del src, dst
     shapes = [("qkv", 12288, 4096), ("o", 4096, 4096), ("gate_up", 22016, 4096), ("down", 4096, 11008)]
-    for M in (args.micro_rows, 8):
+    half_w = bool(args.half_weight_copies)
+    M = args.micro_rows
+    for name, N, K in shapes:
+        A = torch.randn(M, K, device=dev).to(torch.float16)
+        W = (torch.randn(N, K, device=dev) * 0.02).to(torch.bfloat16)
+        Wx = R.rlhf_op_bf16_to_half(W) if half_w else W
+        if name == "gate_up":          # as the stage runs it: SwiGLU in the epilogue
+            act = torch.empty(M, N // 2, device=dev, dtype=torch.float16)
+            timed(f"gemm_{name}_swiglu_M{M}", lambda: R.rlhf_op_gemm_swiglu(A, Wx, act),
+                  (N * K + M * K) * 2.0 + M * (N // 2) * 2.0, 2.0 * M * N * K)
+        elif name == "qkv":            # as the stage runs it: rotary and the q / k / v scatter in the epilogue
+            Hq, hd = 32, 128
+            pos = torch.randint(0, 2048, (M,), device=dev, dtype=torch.int32)
+            ang = torch.arange(2048, device=dev)[:, None] * 10000.0 ** (-2.0 * torch.arange(hd // 2, device=dev) / hd)[None, :]
+            tab = torch.stack([torch.cos(ang), torch.sin(ang)], dim=-1).float().contiguous()
+            q, k, v = (torch.empty(M, Hq * hd, device=dev, dtype=torch.float16) for _ in range(3))
+            timed(f"gemm_{name}_rope_M{M}", lambda: R.rlhf_op_gemm_rope(A, Wx, pos, tab, q, k, v, n_q_heads=Hq,
+                                                                        n_kv_heads=Hq, head_dim=hd, check_indices=False),
+                  (N * K + M * K) * 2.0 + M * N * 2.0, 2.0 * M * N * K)
+        else:
+            C = torch.empty(1, M, N, device=dev)
+            timed(f"gemm_{name}_M{M}", lambda: R.rlhf_op_gemm(A, Wx, C, 1, 0 if half_w else 7),
+                  (N * K + M * K) * 2.0 + M * N * 4.0, 2.0 * M * N * K)
+    # LM head of a scoring pass fused with the log-softmax gather
+    Mh, V, K = 2048, 32000, 4096
+    A = torch.randn(Mh, K, device=dev).to(torch.float16)
+    W = (torch.randn(V, K, device=dev) * 0.02).to(torch.bfloat16)
+    Wx = R.rlhf_op_bf16_to_half(W) if half_w else W
+    toks = torch.randint(0, V, (Mh,), device=dev, dtype=torch.int32)
+    idx = torch.arange(Mh, device=dev, dtype=torch.int32)
+    lp = torch.empty(Mh, device=dev)
+    scratch = torch.empty(int(R.lib().rlhf_op_lm_head_logprob_scratch_floats(Mh, V)), device=dev)
+    timed(f"gemm_lm_head_logprob_M{Mh}", lambda: R.rlhf_op_lm_head_logprob(A, Wx, toks, idx, lp, idx, scratch),
+          (V * K + Mh * K) * 2.0 + scratch.numel() * 4.0, 2.0 * Mh * V * K)
+    del A, W, Wx
+    for M in (8, 32, 64, 128, 256):
         for name, N, K in shapes:
             A = torch.randn(M, K, device=dev).to(torch.float16)
             W = (torch.randn(N, K, device=dev) * 0.02).to(torch.bfloat16)
-            if name == "gate_up" and M >= 512:       # as the stage runs it: SwiGLU in the epilogue
-                act = torch.empty(M, N // 2, device=dev, dtype=torch.float16)
-                timed(f"gemm_{name}_swiglu_M{M}", lambda: R.rlhf_op_gemm_swiglu(A, W, act),
-                      (N * K + M * K) * 2.0 + M * (N // 2) * 2.0, 2.0 * M * N * K)
-                continue
-            if name == "qkv" and M >= 512:           # as the stage runs it: rotary and q/k/v scatter in the epilogue
-                Hq, hd = 32, 128
-                pos = torch.randint(0, 2048, (M,), device=dev, dtype=torch.int32)
-                ang = torch.arange(2048, device=dev)[:, None] * 10000.0 ** (-2.0 * torch.arange(hd // 2, device=dev) / hd)[None, :]
-                tab = torch.stack([torch.cos(ang), torch.sin(ang)], dim=-1).float().contiguous()
-                q, k, v = (torch.empty(M, Hq * hd, device=dev, dtype=torch.float16) for _ in range(3))
-                timed(f"gemm_{name}_rope_M{M}", lambda: R.rlhf_op_gemm_rope(A, W, pos, tab, q, k, v, n_q_heads=Hq,
-                                                                            n_kv_heads=Hq, head_dim=hd,
-                                                                            check_indices=False),
-                      (N * K + M * K) * 2.0 + M * N * 2.0, 2.0 * M * N * K)
-                continue
             ns = R.rlhf_op_gemm_nsplit(R.RLHF_BF16, M, N, K, 16)
             C = torch.empty(ns, M, N, device=dev)
             timed(f"gemm_{name}_M{M}", lambda: R.rlhf_op_gemm(A, W, C, ns),
-                  (N * K + M * K) * 2.0 + M * N * 4.0, 2.0 * M * N * K)
+                  (N * K + M * K) * 2.0 + ns * M * N * 4.0, 2.0 * M * N * K)
     rows, ctx, Hq, hd, Ly = 32, 1024, 32, 128, 1
     n_pages = rows * ctx // 16
     pool = torch.randn(n_pages, Ly, 2, Hq, 16, hd, device=dev).to(torch.float16)

@@ -40,7 +40,9 @@ int rlhf_op_gemm(int dtype, int act_half, const void* A, const void* W, float* C
 /* Gate||up projection of the SwiGLU MLP with the activation fused into the epilogue, as the
  * stage runs it in prefill / scoring passes: act[m][c] = silu(<A[m], W[c]>) * <A[m], W[ffn + c]>.
  * W_gate_up bf16 [2*ffn, K] (gate rows, then up rows); A and act IEEE half (act_half != 0) or
- * bf16, [M, K] and [M, ffn].  Needs M >= 512, ffn and K multiples of 8 (else RLHF_EINVAL). */
+ * bf16, [M, K] and [M, ffn].  Needs M >= 512, ffn and K multiples of 8 (else RLHF_EINVAL); or
+ * 1 <= M <= 16 and K a multiple of 256: the few-row kernel of decode steps, whose workgroups walk
+ * the whole K range (no split) so that SwiGLU can ride in the epilogue there too. */
 int rlhf_op_gemm_swiglu(int act_half, const void* A, const void* W_gate_up, void* act, int M, int ffn, int K,
                         void* stream);
 
@@ -52,7 +54,9 @@ int rlhf_op_gemm_swiglu(int act_half, const void* A, const void* W_gate_up, void
  * table, float32 [max position][head_dim/2][cos, sin]); results are rounded to A's type and
  * written to q [M, n_q_heads*head_dim] and, where non-NULL, to k, v [M, n_kv_heads*head_dim] and
  * to the paged pool (layout as in rlhf_op_paged_decode_attention) at token slot kv_dst[m] =
- * page*16 + offset.  Needs M >= 512, K a multiple of 64, head_dim 64 or 128 (else RLHF_EINVAL). */
+ * page*16 + offset.  Needs M >= 512, K a multiple of 64, head_dim 64 or 128 (else RLHF_EINVAL); or
+ * 1 <= M <= 16 and K a multiple of 256: the few-row kernel of decode steps (no K split, rotary and
+ * the KV-cache append in its epilogue). */
 int rlhf_op_gemm_rope(int act_half, const void* A, const void* W_qkv, const int32_t* pos, const int32_t* kv_dst,
                       const float* table, void* q, void* k, void* v, void* pool, int M, int K, int layer,
                       int n_layers, int n_q_heads, int n_kv_heads, int head_dim, void* stream);

@@ -361,7 +361,26 @@ int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const RoleWeights
         HIPCK(c, launch_rmsnorm(st, adt, ws.h, ws.part, pns, pstride, nullptr, w.g_attn + (size_t)l * d,
                                 ws.xn, rows, d, m.rms_eps));
         int ns = 0;
-        if (mode == kModeBatch && gemm_rope_supported(dt, adt, rows, d, c->dm)) {
+        const bool few = gemm_rows16_supported(dt, adt, rows, d) && (m.head_dim == 64 || m.head_dim == 128);
+        if (few) {
+            // up to 16 rows: the projection walks the whole K range, rotary + KV append ride in its epilogue
+            RowsEpi ep;
+            ep.ro.pos = pm.pos;
+            ep.ro.kv_dst = pm.kv_dst;
+            ep.ro.table = c->d_rope;
+            ep.ro.q = ws.q;
+            ep.ro.k = mode == kModeBatch ? ws.k : nullptr;
+            ep.ro.v = mode == kModeBatch ? ws.v : nullptr;
+            ep.ro.pool = pm.kv_dst ? c->pool : nullptr;
+            ep.ro.layer = l; ep.ro.n_layers = m.n_layers;
+            ep.ro.n_q_heads = m.n_q_heads; ep.ro.n_kv_heads = m.n_kv_heads; ep.ro.head_dim = m.head_dim;
+            ep.ro.page_tokens = c->ec.page_tokens;
+            const double bytes = ((double)qkv_w * d + (double)rows * d) * es + (double)rows * qkv_w * es;
+            const void* wq = layer_ptr(w.wqkv, l, qkv_w, d, es);
+            HIPCK(c, profiled(c, st, gcls, bytes, 2.0 * rows * qkv_w * d, [&] {
+                return launch_gemm_rows16(st, dt, adt, 2, ws.xn, wq, nullptr, rows, qkv_w, d, ep);
+            }));
+        } else if (mode == kModeBatch && gemm_rope_supported(dt, adt, rows, d, c->dm)) {
             // tall pass: rotary, rounding and the q / k / v / pool scatter ride in the GEMM's epilogue
             RopeOut ro;
             ro.pos = pm.pos;
@@ -408,7 +427,16 @@ int forward_layers(rlhf_ctx* c, hipStream_t st, Workspace& ws, const RoleWeights
         }
         HIPCK(c, launch_rmsnorm(st, adt, ws.h, ws.part, ns, (size_t)rows * d, nullptr,
                                 w.g_mlp + (size_t)l * d, ws.xn, rows, d, m.rms_eps));
-        if (gemm_swiglu_supported(dt, adt, rows, f, d)) {
+        if (few && f % 8 == 0) {
+            RowsEpi ep;
+            ep.act = ws.act;
+            ep.ffn = f;
+            const void* wgu = layer_ptr(w.w_gate_up, l, 2 * (size_t)f, d, es);
+            const double bytes = (2.0 * f * d + (double)rows * d) * es + (double)rows * f * es;
+            HIPCK(c, profiled(c, st, gcls, bytes, 4.0 * rows * f * d, [&] {
+                return launch_gemm_rows16(st, dt, adt, 1, ws.xn, wgu, nullptr, rows, 2 * f, d, ep);
+            }));
+        } else if (gemm_swiglu_supported(dt, adt, rows, f, d)) {
             const bool hw = wh.w_gate_up && adt == kF16 && d % 64 == 0;
             const void* wgu = layer_ptr(hw ? wh.w_gate_up : w.w_gate_up, l, 2 * (size_t)f, d, es);
             const double bytes = (2.0 * f * d + (double)rows * d) * es + (double)rows * f * es;

@@ -100,8 +100,12 @@ __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int& 
 // BDMA: W is IEEE half in memory (a copy of the bf16 matrix made when the weights were bound) and
 // takes the same direct global -> LDS path as the activations: no staging registers, no
 // conversion, no LDS stores in the loop.  Needs ADMA's conditions and half activations.
+//
+// RING (> 1, register-staged tiles only): that many K tiles are kept in flight in registers, so that a
+// workgroup which streams its weights over the whole K range (no split) still has enough bytes on
+// their way to keep HBM busy.
 template <int TM, int TN, int TK, int WM, int WN, bool AF16, bool XCD, bool SWIGLU, bool ADMA = false, int ROPE = 0,
-          bool LSE = false, bool BDMA = false>
+          bool LSE = false, bool BDMA = false, int RING = 1>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __restrict__ A,
                                                            const bf16_t* __restrict__ W,
                                                            float* __restrict__ C, int M, int N, int K,
@@ -297,17 +301,41 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
                     acc[i][j] = Mfma<AF16>::run(fb[j], fa[i], acc[i][j]);
         }
     };
-    if (nk > 0) {
-        gload(0, ra, rb);
-        sstore(0, ra, rb);
-    }
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) gload(kt + 1, ra, rb);
-        compute(buf);
-        if (kt + 1 < nk) sstore(buf ^ 1, ra, rb);
+    if constexpr (RING > 1) {
+        static_assert(RING == 1 || (!ADMA && !BDMA && RING % 2 == 0), "the register ring holds register-staged tiles");
+        // ring slot j holds tile kt with kt % RING == j; the slot of the tile that has just gone to LDS
+        // is refilled with the tile RING steps ahead (the waits for a slot's loads follow from its use)
+        uint4 qa[RING][A_IT], qb[RING][B_IT];
+#pragma unroll
+        for (int j = 0; j < RING; ++j)
+            if (j < nk) gload(j, qa[j], qb[j]);
+        if (nk > 0) sstore(0, qa[0], qb[0]);
         __syncthreads();
+        for (int kt0 = 0; kt0 < nk; kt0 += RING) {
+#pragma unroll
+            for (int j = 0; j < RING; ++j) {
+                const int kt = kt0 + j;
+                if (kt < nk) {
+                    gload(kt + RING, qa[j], qb[j]);      // past the range every lane's guard is off: nothing is loaded
+                    compute(j & 1);
+                    if (kt + 1 < nk) sstore((j + 1) & 1, qa[(j + 1) % RING], qb[(j + 1) % RING]);
+                    __syncthreads();
+                }
+            }
+        }
+    } else {
+        if (nk > 0) {
+            gload(0, ra, rb);
+            sstore(0, ra, rb);
+        }
+        __syncthreads();
+        for (int kt = 0; kt < nk; ++kt) {
+            const int buf = kt & 1;
+            if (kt + 1 < nk) gload(kt + 1, ra, rb);
+            compute(buf);
+            if (kt + 1 < nk) sstore(buf ^ 1, ra, rb);
+            __syncthreads();
+        }
     }
 
     if (SWIGLU) {
@@ -497,6 +525,201 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
     }
 }
 
+// ------------------------------------------------------- few rows, whole K range per workgroup
+// Up to 16 activation rows against 64 weight rows per workgroup, the workgroup walking the WHOLE K
+// range (no split, so the result is final and an epilogue can finish the layer's next step).  With
+// few workgroups per compute unit the bytes in flight have to come from depth instead: a ring of
+// RING K tiles per thread in registers.  The loop is free of branches around the loads (rows past
+// M or N are clamped and discarded at the store, K is a whole number of tiles), because the
+// compiler otherwise waits for ALL outstanding loads at every tile and the ring is worth nothing.
+// Tiles pass through LDS as in k_gemm_bf16 (same swizzle, weights converted to half on the way).
+//   MODE 0: C[m][n] float, one plane.
+//   MODE 1 (SwiGLU): W = gate||up [2f, K]; the workgroup's 64 rows are 32 gate rows and the matching
+//           32 up rows; act[m][c] = silu(gate) * up, 16-bit, [M, f].
+//   MODE 2 (rotary + KV append): W = QKV; the 64 rows are columns [c, c+32) and [c+half, c+half+32) of
+//           one head (half = head_dim / 2), so both members of every rotary pair meet in the workgroup;
+//           query heads go to q, key / value heads to the paged pool (and k / v if given).
+// (Measured on the 7B shapes at 8 rows: QKV 21.6 us and gate||up 39.6 us with a ring of 8, against
+// 20.2 and 34.3 us for the split-K kernel, whose consumers then cost a launch each; a ring of 16
+// and two wave groups on alternate tiles were both slower; without the ring, 57 and 60 us.)
+template <int RING, int MODE, bool AF16>
+__global__ __launch_bounds__(256) void k_gemm_rows16(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+                                                     float* __restrict__ C, int M, int N, int K, const RowsEpi ep) {
+    constexpr int TM = 16, TN = 64, TK = 64;
+    __shared__ __attribute__((aligned(16))) bf16_t sA[2][TM * TK];
+    __shared__ __attribute__((aligned(16))) bf16_t sB[2][TN * TK];
+    __shared__ float sx[TM][TN + 1];                       // epilogue exchange (MODE 1, 2)
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int fr = lane & 15, fq = lane >> 4;
+    const int nk = K / TK / (int)gridDim.y;                // mode 0 may split K over blockIdx.y (float planes)
+    const int blk = blockIdx.x;
+    A += (size_t)blockIdx.y * nk * TK;
+    W += (size_t)blockIdx.y * nk * TK;
+    C += (size_t)blockIdx.y * M * N;
+
+    // weight row of tile row r
+    auto wrow = [&](int r) -> int {
+        if (MODE == 1) {                                   // rows 0..31: gate columns blk*32 + r; 32..63: the up rows
+            const int c = min(blk * 32 + (r & 31), ep.ffn - 1);
+            return (r >> 5) * ep.ffn + c;
+        }
+        if (MODE == 2) {
+            const int hd = ep.ro.head_dim, half = hd >> 1, per_head = half / 32;
+            const int head = blk / per_head, c = (blk - head * per_head) * 32;
+            return head * hd + (r >> 5) * half + c + (r & 31);
+        }
+        return min(blk * TN + r, N - 1);
+    };
+    // loader: one 16-byte chunk of A for the first 128 threads, two of W for everybody
+    const int ar = (t >> 3) & 15, ac = t & 7;              // A: row 0..15 (threads 128.. duplicate 0..127), chunk
+    const bf16_t* pa = A + (size_t)min(ar, M - 1) * K + ac * 8;
+    const bf16_t* pb[2];
+    int br[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        br[i] = (t + i * 256) >> 3;
+        pb[i] = W + (size_t)wrow(br[i]) * K + ac * 8;
+    }
+    const int a_dst = ar * TK + swz<TK>(ar, ac) * 8;
+    int b_dst[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) b_dst[i] = br[i] * TK + swz<TK>(br[i], ac) * 8;
+
+    // The ring lives in registers: every index below is a compile-time constant after unrolling
+    // (macros, not lambdas taking an index: an array indexed through a lambda parameter is put in
+    // scratch memory, whose reloads wait for every outstanding load).  Threads 128..255 carry a
+    // duplicate of the activation chunk of thread t - 128 and store it to the same place.
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // a vector type, not a struct: stays in registers
+    u32x4_t qa[RING], qb0[RING], qb1[RING];
+#define RLHF_ROWS_GLOAD(KT, J)                                                            \
+    do {                                                                                  \
+        qa[J] = *reinterpret_cast<const u32x4_t*>(pa + (size_t)(KT) * TK);                \
+        qb0[J] = *reinterpret_cast<const u32x4_t*>(pb[0] + (size_t)(KT) * TK);            \
+        qb1[J] = *reinterpret_cast<const u32x4_t*>(pb[1] + (size_t)(KT) * TK);            \
+    } while (0)
+#define RLHF_ROWS_CVT(R)                                                                  \
+    do {                                                                                  \
+        if (AF16) {                                                                       \
+            R[0] = bf16x2_to_f16x2(R[0]); R[1] = bf16x2_to_f16x2(R[1]);                   \
+            R[2] = bf16x2_to_f16x2(R[2]); R[3] = bf16x2_to_f16x2(R[3]);                   \
+        }                                                                                 \
+    } while (0)
+#define RLHF_ROWS_SSTORE(BUF, J)                                                          \
+    do {                                                                                  \
+        *reinterpret_cast<u32x4_t*>(&sA[BUF][a_dst]) = qa[J];                             \
+        u32x4_t r0_ = qb0[J], r1_ = qb1[J];                                               \
+        RLHF_ROWS_CVT(r0_);                                                               \
+        RLHF_ROWS_CVT(r1_);                                                               \
+        *reinterpret_cast<u32x4_t*>(&sB[BUF][b_dst[0]]) = r0_;                            \
+        *reinterpret_cast<u32x4_t*>(&sB[BUF][b_dst[1]]) = r1_;                            \
+    } while (0)
+    f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const int rb_ = w * 16 + fr;
+    const int fa_off0 = fr * TK + swz<TK>(fr, fq) * 8, fa_off1 = fr * TK + swz<TK>(fr, 4 + fq) * 8;
+    const int fb_off0 = rb_ * TK + swz<TK>(rb_, fq) * 8, fb_off1 = rb_ * TK + swz<TK>(rb_, 4 + fq) * 8;
+    typedef typename Mfma<AF16>::frag frag_t;
+#define RLHF_ROWS_COMPUTE(BUF)                                                            \
+    do {                                                                                  \
+        const frag_t fa0_ = *reinterpret_cast<const frag_t*>(&sA[BUF][fa_off0]);          \
+        const frag_t fb0_ = *reinterpret_cast<const frag_t*>(&sB[BUF][fb_off0]);          \
+        const frag_t fa1_ = *reinterpret_cast<const frag_t*>(&sA[BUF][fa_off1]);          \
+        const frag_t fb1_ = *reinterpret_cast<const frag_t*>(&sB[BUF][fb_off1]);          \
+        acc = Mfma<AF16>::run(fb0_, fa0_, acc);                                           \
+        acc = Mfma<AF16>::run(fb1_, fa1_, acc);                                           \
+    } while (0)
+#pragma unroll
+    for (int j = 0; j < RING; ++j) RLHF_ROWS_GLOAD(j, j);  // nk >= RING (checked by the launcher)
+    RLHF_ROWS_SSTORE(0, 0);
+    __syncthreads();
+    int kt0 = 0;
+    for (; kt0 + RING < nk; kt0 += RING) {
+#pragma unroll
+        for (int j = 0; j < RING; ++j) {
+            RLHF_ROWS_GLOAD(kt0 + j + RING, j);
+            RLHF_ROWS_COMPUTE(j & 1);
+            RLHF_ROWS_SSTORE((j + 1) & 1, (j + 1) % RING);
+            __syncthreads();
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < RING; ++j) {                       // the last RING tiles: nothing left to load
+        RLHF_ROWS_COMPUTE(j & 1);
+        if (j + 1 < RING) RLHF_ROWS_SSTORE((j + 1) & 1, j + 1);
+        __syncthreads();
+    }
+#undef RLHF_ROWS_GLOAD
+#undef RLHF_ROWS_CVT
+#undef RLHF_ROWS_SSTORE
+#undef RLHF_ROWS_COMPUTE
+    // the lane holds row m = fr, tile columns w*16 + fq*4 + e
+    if (MODE == 0) {
+        const int n = blk * TN + w * 16 + fq * 4;
+        if (fr < M && n + 3 < N)
+            *reinterpret_cast<float4*>(C + (size_t)fr * N + n) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        else if (fr < M)
+            for (int e = 0; e < 4; ++e)
+                if (n + e < N) C[(size_t)fr * N + n + e] = acc[e];
+        return;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) sx[fr][w * 16 + fq * 4 + e] = acc[e];
+    __syncthreads();
+    typedef typename std::conditional<AF16, f16_t, bf16_t>::type TO;
+    if (MODE == 1) {
+        TO* act = reinterpret_cast<TO*>(ep.act);
+        for (int i = t; i < TM * 32; i += 256) {
+            const int m = i >> 5, c = i & 31, oc = blk * 32 + c;
+            if (m < M && oc < ep.ffn) {
+                const float g = sx[m][c], u = sx[m][32 + c];
+                act[(size_t)m * ep.ffn + oc] = from_f32<TO>(g / (1.f + __expf(-g)) * u);
+            }
+        }
+        return;
+    }
+    if (MODE == 2) {
+        const RopeOut& ro = ep.ro;
+        const int hd = ro.head_dim, half = hd >> 1, per_head = half / 32;
+        const int head = blk / per_head, c0 = (blk - head * per_head) * 32;
+        const int Hq = ro.n_q_heads, Hkv = ro.n_kv_heads;
+        TO* q_out = reinterpret_cast<TO*>(ro.q);
+        TO* k_out = reinterpret_cast<TO*>(ro.k);
+        TO* v_out = reinterpret_cast<TO*>(ro.v);
+        TO* pool = reinterpret_cast<TO*>(ro.pool);
+        for (int i = t; i < TM * 32; i += 256) {
+            const int m = i >> 5, c = i & 31;
+            if (m >= M) continue;
+            float a = sx[m][c], b = sx[m][32 + c];           // dims c0 + c and c0 + c + half of the head
+            if (head < Hq + Hkv) {
+                const float* tab = ro.table + ((size_t)ro.pos[m] * half + c0 + c) * 2;
+                const float cs = tab[0], sn = tab[1];
+                const float fa_ = a * cs - b * sn, fb_ = a * sn + b * cs;
+                a = fa_; b = fb_;
+            }
+            const int d0 = c0 + c, d1 = c0 + c + half;
+            if (head < Hq) {
+                TO* dst = q_out + ((size_t)m * Hq + head) * hd;
+                dst[d0] = from_f32<TO>(a);
+                dst[d1] = from_f32<TO>(b);
+            } else {
+                const bool is_k = head < Hq + Hkv;
+                const int kh = is_k ? head - Hq : head - Hq - Hkv;
+                TO* lin = is_k ? k_out : v_out;
+                if (lin) {
+                    lin[((size_t)m * Hkv + kh) * hd + d0] = from_f32<TO>(a);
+                    lin[((size_t)m * Hkv + kh) * hd + d1] = from_f32<TO>(b);
+                }
+                if (pool) {
+                    const int slot = ro.kv_dst[m], pt = ro.page_tokens;
+                    TO* dst = pool + ((size_t)(slot / pt) * ro.n_layers + ro.layer) * 2 * (size_t)Hkv * pt * hd +
+                              (size_t)(is_k ? 0 : Hkv) * pt * hd + (size_t)kh * pt * hd + (size_t)(slot % pt) * hd;
+                    dst[d0] = from_f32<TO>(a);
+                    dst[d1] = from_f32<TO>(b);
+                }
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------ fp32 path
 // 64x64 tile, K step 16, 256 threads each computing a 4x4 block.
 __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A,
@@ -565,6 +788,7 @@ constexpr TileCfg kCfgs[] = {
     {0, 0, 0, 0, false},
     {1, 16, 64, 64, false}, {2, 32, 64, 64, false}, {3, 64, 64, 64, false}, {4, 128, 128, 64, false},
     {5, 128, 128, 64, true}, {6, 256, 128, 32, true}, {7, 256, 256, 64, true},
+    {8, 16, 64, 64, false},      // k_gemm_rows16: up to 16 rows, whole K range per workgroup (no split)
 };
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
@@ -661,6 +885,45 @@ int gemm_choose_nsplit(int wdt, int M, int N, int K, int max_split) {
     return ns;
 }
 
+bool gemm_rows16_supported(int wdt, int adt, int M, int K) {
+    return wdt == kBF16 && (adt == kF16 || adt == kBF16) && M >= 1 && M <= 16 && K % 64 == 0 && (K / 64) % 4 == 0;
+}
+
+// mode 0: plain (C float [M, N]); 1: SwiGLU (ep.act, ep.ffn; N = 2 * ffn); 2: rotary + KV append (ep.ro)
+hipError_t launch_gemm_rows16(hipStream_t st, int wdt, int adt, int mode, const void* A, const void* W, float* C,
+                              int M, int N, int K, const RowsEpi& ep, int nsplit) {
+    if (!gemm_rows16_supported(wdt, adt, M, K) || mode < 0 || mode > 2 || nsplit < 1) return hipErrorInvalidValue;
+    if (nsplit > 1 && (mode != 0 || (K / 64) % (4 * nsplit))) return hipErrorInvalidValue;
+    int blocks = (N + 63) / 64;
+    if (mode == 1) {
+        if (!ep.act || ep.ffn <= 0 || N != 2 * ep.ffn) return hipErrorInvalidValue;
+        blocks = (ep.ffn + 31) / 32;
+    }
+    if (mode == 2) {
+        const RopeOut& ro = ep.ro;
+        if ((ro.head_dim != 64 && ro.head_dim != 128) || !ro.pos || !ro.table || !ro.q || (ro.pool && !ro.kv_dst) ||
+            N != (ro.n_q_heads + 2 * ro.n_kv_heads) * ro.head_dim)
+            return hipErrorInvalidValue;
+        blocks = N / 64;
+    }
+    const bf16_t* a = (const bf16_t*)A;
+    const bf16_t* w = (const bf16_t*)W;
+    const bool r8 = (K / 64 / nsplit) % 8 == 0;         // a split's K tiles must be a multiple of the ring depth
+    const dim3 grid(blocks, nsplit);
+#define RLHF_ROWS(MODE_, AF_)                                                                          \
+    do {                                                                                               \
+        if (r8) k_gemm_rows16<8, MODE_, AF_><<<grid, 256, 0, st>>>(a, w, C, M, N, K, ep);              \
+        else k_gemm_rows16<4, MODE_, AF_><<<grid, 256, 0, st>>>(a, w, C, M, N, K, ep);                 \
+    } while (0)
+    if (adt == kF16) {
+        if (mode == 0) RLHF_ROWS(0, true); else if (mode == 1) RLHF_ROWS(1, true); else RLHF_ROWS(2, true);
+    } else {
+        if (mode == 0) RLHF_ROWS(0, false); else if (mode == 1) RLHF_ROWS(1, false); else RLHF_ROWS(2, false);
+    }
+#undef RLHF_ROWS
+    return hipGetLastError();
+}
+
 template <bool AF16>
 static hipError_t launch_bf16(hipStream_t st, int variant, const bf16_t* a, const bf16_t* w, float* C, int M,
                               int N, int K, int nsplit) {
@@ -678,6 +941,10 @@ static hipError_t launch_bf16(hipStream_t st, int variant, const bf16_t* a, cons
         case 2: RLHF_GEMM(32, 64, 64, 1, 4, false); break;
         case 3: RLHF_GEMM(64, 64, 64, 2, 2, false); break;
         case 4: RLHF_GEMM(128, 128, 64, 2, 2, false); break;
+        case 8: {
+            if (!gemm_rows16_supported(kBF16, AF16 ? kF16 : kBF16, M, K)) return hipErrorInvalidValue;
+            return launch_gemm_rows16(st, kBF16, AF16 ? kF16 : kBF16, 0, a, w, C, M, N, K, RowsEpi{}, nsplit);
+        }
         case 5: RLHF_GEMM(128, 128, 64, 2, 2, true); break;
         case 6: RLHF_GEMM(256, 128, 32, 2, 2, true); break;
         case 7:                                                  // eight waves, wave tile 64 x 128

@@ -55,6 +55,21 @@ bool gemm_rope_supported(int wdt, int adt, int M, int K, const Dims& dm);
 hipError_t launch_gemm_rope(hipStream_t st, int wdt, int adt, const void* A, const void* Wqkv, int M, int K,
                             const RopeOut& ro);
 
+// Few rows (1..16), bf16 weights: a kernel whose workgroups walk the whole K range (no split), so that
+// the step that consumes the projection rides in its epilogue and needs no launch of its own.
+// mode 0: C float [M, N]; mode 1: gate||up with SwiGLU, act [M, ffn] of type adt (N = 2 ffn);
+// mode 2: QKV with rotary embedding and the q / k / v / paged-pool scatter (ep.ro as in launch_gemm_rope).
+// K must be a multiple of 256.  Mode 0 may also split K (nsplit float planes, (K / 64) a multiple of
+// 4 * nsplit).
+struct RowsEpi {
+    void* act = nullptr;       // mode 1
+    int ffn = 0;
+    RopeOut ro;                // mode 2
+};
+bool gemm_rows16_supported(int wdt, int adt, int M, int K);
+hipError_t launch_gemm_rows16(hipStream_t st, int wdt, int adt, int mode, const void* A, const void* W, float* C,
+                              int M, int N, int K, const RowsEpi& ep, int nsplit = 1);
+
 // LM head of a scoring pass fused with the log-softmax gather: the logits stay in registers.  Per
 // row m the GEMM leaves n_part = gemm_lse_partials(N) pairs (max, sum of exp(z - max)), one per 128
 // columns (a pair whose columns all lie beyond N is (-inf, 0)), and the logit of the row's target

@@ -140,6 +140,13 @@ extern "C" int rlhf_op_gemm_swiglu(int act_half, const void* A, const void* W_ga
                                    int K, void* stream) {
     if (!A || !W_gate_up || !act) return RLHF_EINVAL;
     const int adt = act_half ? kF16 : kBF16, wdt = act_half == 2 ? kF16 : kBF16;
+    if (M >= 1 && M <= 16) {            // the few-row kernel of decode steps (no K split, SwiGLU in its epilogue)
+        if (!gemm_rows16_supported(wdt, adt, M, K) || ffn <= 0 || ffn % 8) return RLHF_EINVAL;
+        RowsEpi ep;
+        ep.act = act;
+        ep.ffn = ffn;
+        return status_of(launch_gemm_rows16((hipStream_t)stream, wdt, adt, 1, A, W_gate_up, nullptr, M, 2 * ffn, K, ep));
+    }
     if (!gemm_swiglu_supported(wdt, adt, M, ffn, K)) return RLHF_EINVAL;
     return status_of(launch_gemm_swiglu((hipStream_t)stream, wdt, adt, A, W_gate_up, act, M, ffn, K));
 }
@@ -153,12 +160,19 @@ extern "C" int rlhf_op_gemm_rope(int act_half, const void* A, const void* W_qkv,
         return RLHF_EINVAL;
     const int adt = act_half ? kF16 : kBF16, wdt = act_half == 2 ? kF16 : kBF16;
     Dims dm{n_layers, K, n_q_heads, n_kv_heads, head_dim, 0, 0, 16};
-    if (!gemm_rope_supported(wdt, adt, M, K, dm)) return RLHF_EINVAL;
     RopeOut ro;
     ro.pos = pos; ro.kv_dst = kv_dst; ro.table = table;
     ro.q = q; ro.k = k; ro.v = v; ro.pool = pool;
     ro.layer = layer; ro.n_layers = n_layers;
     ro.n_q_heads = n_q_heads; ro.n_kv_heads = n_kv_heads; ro.head_dim = head_dim;
+    if (M >= 1 && M <= 16) {            // the few-row kernel of decode steps (no K split, rotary in its epilogue)
+        if (!gemm_rows16_supported(wdt, adt, M, K) || (head_dim != 64 && head_dim != 128)) return RLHF_EINVAL;
+        RowsEpi ep;
+        ep.ro = ro;
+        return status_of(launch_gemm_rows16((hipStream_t)stream, wdt, adt, 2, A, W_qkv, nullptr, M,
+                                            (n_q_heads + 2 * n_kv_heads) * head_dim, K, ep));
+    }
+    if (!gemm_rope_supported(wdt, adt, M, K, dm)) return RLHF_EINVAL;
     return status_of(launch_gemm_rope((hipStream_t)stream, wdt, adt, A, W_qkv, M, K, ro));
 }
 

@@ -335,3 +335,89 @@ def test_half_weight_copies_give_bit_identical_tall_gemms():
     z = A.double().cpu().numpy() @ whd.T
     want = OT.log_softmax_rows(z)[np.arange(M), tokens.cpu().numpy()]
     np.testing.assert_allclose(lp_b.cpu().numpy(), want, rtol=0, atol=1e-4)
+
+
+# ------------------------------------------- few rows, no K split, the consumer in the epilogue
+
+@pytest.mark.parametrize("half_act", [True, False])
+@pytest.mark.parametrize("M,f,K", [(1, 688, 256), (7, 1000, 768), (16, 11008, 4096), (9, 40, 512)])
+def test_few_row_gate_up_with_swiglu_epilogue(half_act, M, f, K):
+    """Decode-step gate||up projection: up to 16 rows, every workgroup walks the whole K range
+    through its register ring (depth 8 or 4), SwiGLU in the epilogue; ragged last column block."""
+    R = _R()
+    r = np.random.default_rng(f + M)
+    a, w = r.normal(size=(M, K)), r.normal(size=(2 * f, K)) * 0.06
+    A = torch.from_numpy(a.astype(np.float32)).half().cuda() if half_act else _bf16_round(a).cuda()
+    W = _bf16_round(w).cuda()
+    z = A.double().cpu().numpy() @ W.double().cpu().numpy().T
+    want = OT.silu(z[:, :f]) * z[:, f:]
+    act = torch.full((M, f), float("nan"), dtype=A.dtype, device="cuda")
+    R.rlhf_op_gemm_swiglu(A, W, act)
+    torch.cuda.synchronize()
+    got = act.double().cpu().numpy()
+    assert np.isfinite(got).all()
+    tol = (2 ** -11 if half_act else 2 ** -8) * np.maximum(np.abs(want), 1e-2) + 1e-4
+    assert np.all(np.abs(got - want) <= tol), np.abs(got - want).max()
+
+
+@pytest.mark.parametrize("half_act", [True, False])
+@pytest.mark.parametrize("M,K,Hq,Hkv,hd,with_pool", [(1, 256, 4, 4, 64, True), (5, 768, 5, 1, 64, False),
+                                                     (16, 4096, 8, 2, 128, True), (11, 512, 3, 3, 128, True)])
+def test_few_row_qkv_with_rotary_epilogue(half_act, M, K, Hq, Hkv, hd, with_pool):
+    """Decode-step QKV projection: rotary embedding and the q / paged-pool (or k, v) scatter in the
+    epilogue of the no-split kernel; both head sizes, grouped heads."""
+    R = _R()
+    r = np.random.default_rng(M + K)
+    base, n_layers, layer, max_pos = 10000.0, 2, 1, 300
+    N = (Hq + 2 * Hkv) * hd
+    a, w = r.normal(size=(M, K)), r.normal(size=(N, K)) * 0.06
+    A = torch.from_numpy(a.astype(np.float32)).half().cuda() if half_act else _bf16_round(a).cuda()
+    W = _bf16_round(w).cuda()
+    pos = r.integers(0, max_pos, size=M).astype(np.int32)
+    ang = np.arange(max_pos)[:, None] * base ** (-2.0 * np.arange(hd // 2) / hd)[None, :]
+    table = torch.from_numpy(np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32)).cuda()
+    z = A.double().cpu().numpy() @ W.double().cpu().numpy().T
+    want_q = OT.rope(z[:, :Hq * hd].reshape(M, Hq, hd), pos, base).reshape(M, -1)
+    want_k = OT.rope(z[:, Hq * hd:(Hq + Hkv) * hd].reshape(M, Hkv, hd), pos, base).reshape(M, -1)
+    want_v = z[:, (Hq + Hkv) * hd:]
+    nan = lambda *s: torch.full(s, float("nan"), dtype=A.dtype, device="cuda")
+    q, k, v = nan(M, Hq * hd), nan(M, Hkv * hd), nan(M, Hkv * hd)
+    n_pages = 4
+    pool = nan(n_pages, n_layers, 2, Hkv, 16, hd) if with_pool else None
+    slots = r.permutation(n_pages * 16)[:M].astype(np.int32)
+    R.rlhf_op_gemm_rope(A, W, torch.from_numpy(pos).cuda(), table, q, k if not with_pool else None,
+                        v if not with_pool else None, pool, torch.from_numpy(slots).cuda() if with_pool else None,
+                        layer, n_layers, Hq, Hkv, hd)
+    torch.cuda.synchronize()
+    eps = 2 ** -11 if half_act else 2 ** -8
+
+    def close(got, want):
+        got = got.double().cpu().numpy()
+        assert np.isfinite(got).all()
+        assert np.all(np.abs(got - want) <= eps * np.maximum(np.abs(want), 1e-2) + 1e-4), np.abs(got - want).max()
+
+    close(q, want_q)
+    if with_pool:
+        p = pool.double().cpu().numpy()
+        got = p[slots // 16, layer, :, :, slots % 16, :]
+        close(torch.from_numpy(got[:, 0].reshape(M, -1)), want_k)
+        close(torch.from_numpy(got[:, 1].reshape(M, -1)), want_v)
+        p[slots // 16, layer, :, :, slots % 16, :] = np.nan
+        assert np.isnan(p).all()
+        assert torch.isnan(k).all() and torch.isnan(v).all()
+    else:
+        close(k, want_k)
+        close(v, want_v)
+
+
+@pytest.mark.parametrize("M,N,K", [(3, 200, 256), (16, 4100, 1024), (8, 12288, 4096)])
+def test_few_row_gemm_without_k_split(M, N, K):
+    R = _R()
+    r = np.random.default_rng(N)
+    A = torch.from_numpy(r.normal(size=(M, K)).astype(np.float32)).half().cuda()
+    W = _bf16_round(r.normal(size=(N, K)) * 0.02).cuda()
+    want = A.double().cpu().numpy() @ W.double().cpu().numpy().T
+    out = torch.full((1, M, N), float("nan"), device="cuda")
+    R.rlhf_op_gemm(A, W, out, 1, 8)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out[0].double().cpu().numpy(), want, rtol=0, atol=3e-5 * np.sqrt(K))
