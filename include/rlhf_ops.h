@@ -37,6 +37,14 @@ int rlhf_op_gemm_nsplit(int dtype, int M, int N, int K, int max_split);
 int rlhf_op_gemm(int dtype, int act_half, const void* A, const void* W, float* C, int M, int N, int K,
                  int nsplit, int variant, void* stream);
 
+/* Host-side copy of the workgroup -> tile mapping of the compute-bound (256 x 256) launches, for
+ * tests of that mapping: rlhf_op_gemm_tall_grid is the number of workgroups launched for a grid of
+ * tiles_m x tiles_n tiles; rlhf_op_gemm_tall_tile returns 1 and the tile (*tm, *tn) workgroup bid
+ * computes, 0 if it has none, RLHF_EINVAL on bad arguments.  The 8 XCDs (bid modulo 8) walk the same
+ * panel of 8 tile rows at the same time, each over a contiguous group of tile columns of its own. */
+int rlhf_op_gemm_tall_grid(int tiles_m, int tiles_n);
+int rlhf_op_gemm_tall_tile(int bid, int tiles_m, int tiles_n, int* tm, int* tn);
+
 /* Gate||up projection of the SwiGLU MLP with the activation fused into the epilogue, as the
  * stage runs it in prefill / scoring passes: act[m][c] = silu(<A[m], W[c]>) * <A[m], W[ffn + c]>.
  * W_gate_up bf16 [2*ffn, K] (gate rows, then up rows); A and act IEEE half (act_half != 0) or

@@ -140,6 +140,10 @@ def lib() -> C.CDLL:
         L.rlhf_op_lm_head_logprob_scratch_floats.restype = i64
         L.rlhf_op_lm_head_logprob.argtypes = [C.c_int] + [vp] * 7 + [C.c_int] * 3 + [vp]
         L.rlhf_op_lm_head_logprob.restype = C.c_int
+        L.rlhf_op_gemm_tall_grid.argtypes = [C.c_int, C.c_int]
+        L.rlhf_op_gemm_tall_grid.restype = C.c_int
+        L.rlhf_op_gemm_tall_tile.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+        L.rlhf_op_gemm_tall_tile.restype = C.c_int
         L.rlhf_op_bf16_to_half.argtypes = [vp, vp, i64, vp]
         L.rlhf_op_bf16_to_half.restype = C.c_int
         for name in ("rlhf_op_rmsnorm", "rlhf_op_rope_kv", "rlhf_op_swiglu", "rlhf_op_pick", "rlhf_op_gather_lp",
@@ -551,3 +555,16 @@ def rlhf_op_lm_head_logprob(A, W_head, tokens, target_idx, out, out_dst, scratch
                                             tokens.data_ptr(), target_idx.data_ptr(), out.data_ptr(), out_dst.data_ptr(),
                                             scratch.data_ptr(), M, vocab, K, _stream_ptr()), "rlhf_op_lm_head_logprob")
     return scratch
+
+
+def rlhf_op_gemm_tall_grid(tiles_m: int, tiles_n: int) -> int:
+    return lib().rlhf_op_gemm_tall_grid(tiles_m, tiles_n)
+
+
+def rlhf_op_gemm_tall_tile(bid: int, tiles_m: int, tiles_n: int):
+    """(tm, tn) of workgroup bid, or None if it has no tile."""
+    tm, tn = C.c_int(), C.c_int()
+    rc = lib().rlhf_op_gemm_tall_tile(bid, tiles_m, tiles_n, C.byref(tm), C.byref(tn))
+    if rc < 0:
+        raise RlhfError(rc, "rlhf_op_gemm_tall_tile")
+    return (tm.value, tn.value) if rc == 1 else None

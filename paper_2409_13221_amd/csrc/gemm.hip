@@ -42,30 +42,45 @@ template <> struct Mfma<true> {
 
 // Tile index of a workgroup.  Few-row launches (XCD == false) walk the N tiles in order, the
 // row tiles of a column tile next to each other so that its weights are fetched once.
-// Compute-bound launches (XCD == true): tiles are numbered in panels of kGroupM tile rows,
-// column by column inside a panel, and each of the 8 XCDs (workgroup id modulo 8, the order in
-// which the dispatcher deals workgroups to XCDs) walks its own contiguous eighth of that
-// numbering.  The workgroups resident on one XCD at a time then cover a compact block of the
-// output, so its L2 re-serves the A rows and W rows they share, and every XCD gets the same
-// number of tiles whatever the shape.
+// Compute-bound launches (XCD == true): the tile grid is cut into panels of kGroupM tile rows.
+// Inside a panel the tile columns are dealt to the 8 XCDs (workgroup id modulo 8, the order in
+// which the dispatcher deals workgroups to XCDs) in contiguous groups, and an XCD walks its
+// group column by column.  Two things follow.  The workgroups resident on one XCD at a time
+// cover a compact block of kGroupM x 4 tiles, so its L2 re-serves the A rows and W rows they
+// share.  And all XCDs work on the SAME panel of A rows at the same time, each on W columns of
+// its own: an A panel is requested by the eight L2s within a short time of each other (one
+// fetch from HBM, the others from the memory-side cache even while a decode stream sweeps its
+// weights through that cache) and every W column is fetched by one XCD only, once per panel.
+// (Before, each XCD walked its own contiguous eighth of the panel-ordered tile list; the
+// eight of them then sat on up to four different A panels and up to eight W ranges, and with the
+// memory-side cache swept by the decode stream the scoring GEMMs pulled several times their
+// operands from HBM.)
 constexpr int kGroupM = 8;
+__host__ __device__ inline int xcd_cols(int tiles_n) { return (tiles_n + 7) >> 3; }   // tile columns per XCD
+inline int xcd_grid(int tiles_m, int tiles_n) { return 8 * tiles_m * xcd_cols(tiles_n); }
 template <bool XCD>
-__device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
+__host__ __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
     if (!XCD) {           // the (at most two) row tiles of one column tile run side by side
         tn = bid / tiles_m;
         tm = bid - tn * tiles_m;
         return true;
     }
-    const int total = tiles_m * tiles_n;
-    const int per_xcd = (total + 7) >> 3;
-    const int pid = (bid & 7) * per_xcd + (bid >> 3);
-    if ((bid >> 3) >= per_xcd || pid >= total) return false;
-    const int in_panel = kGroupM * tiles_n;
-    const int panel = pid / in_panel, r = pid - panel * in_panel;
-    const int first = panel * kGroupM;
-    const int rows = min(tiles_m - first, kGroupM);
-    tm = first + r % rows;
-    tn = r / rows;
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int cx = xcd_cols(tiles_n);
+    const int c_lo = xcd * cx;
+    const int c_n = min(tiles_n, c_lo + cx) - c_lo;          // this XCD's columns (may be <= 0 at the end)
+    if (c_n <= 0) return false;
+    const int per_panel = kGroupM * c_n;
+    const int full = tiles_m / kGroupM;
+    int panel = slot / per_panel, r = slot - panel * per_panel, rows = kGroupM;
+    if (panel >= full) {                                     // the last, shorter panel
+        panel = full;
+        r = slot - full * per_panel;
+        rows = tiles_m - full * kGroupM;
+        if (rows <= 0 || r >= rows * c_n) return false;
+    }
+    tm = panel * kGroupM + r % rows;
+    tn = c_lo + r / rows;
     return true;
 }
 
@@ -831,6 +846,12 @@ constexpr int kTargetBlocks = 1024;      // about four workgroups per compute un
 
 // True when launch_gemm would run the 256 x 256 tiling for this shape and split (the shapes for
 // which a half copy of the weights, if there is one, is the better operand).
+// The tile a workgroup of a compute-bound launch takes (host copy of the device mapping, for tests).
+int gemm_tall_grid(int tiles_m, int tiles_n) { return xcd_grid(tiles_m, tiles_n); }
+bool gemm_tall_tile(int bid, int tiles_m, int tiles_n, int* tm, int* tn) {
+    return tile_of<true>(bid, tiles_m, tiles_n, *tm, *tn);
+}
+
 bool gemm_is_tall(int M, int N, int K, int nsplit) { return K % 64 == 0 && kCfgs[pick_variant(M, N, K, nsplit)].xcd; }
 
 // bf16 -> IEEE half, element by element (round toward zero; exact in half's normal range, values
@@ -931,7 +952,7 @@ static hipError_t launch_bf16(hipStream_t st, int variant, const bf16_t* a, cons
     const int tiles_m = (M + c.tm - 1) / c.tm, tiles_n = (N + c.tn - 1) / c.tn;
     const int kchunk = ((K + nsplit - 1) / nsplit + c.tk - 1) / c.tk * c.tk;
     int blocks = tiles_m * tiles_n;
-    if (c.xcd) blocks = (blocks + 7) / 8 * 8;
+    if (c.xcd) blocks = xcd_grid(tiles_m, tiles_n);
     dim3 grid(blocks, nsplit);
 #define RLHF_GEMM(TM, TN, TK, WM, WN, XCD)                                                            \
     k_gemm_bf16<TM, TN, TK, WM, WN, AF16, XCD, false><<<grid, WM * WN * 64, 0, st>>>(a, w, C, M, N, K, kchunk, \
@@ -974,7 +995,7 @@ hipError_t launch_gemm_swiglu(hipStream_t st, int wdt, int adt, const void* A, c
     constexpr int TM = 256, TN = 256;
     const int N = 2 * ffn;
     const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
-    dim3 grid((tiles_m * tiles_n + 7) / 8 * 8, 1);
+    dim3 grid(xcd_grid(tiles_m, tiles_n), 1);
     const int kchunk = (K + 63) / 64 * 64;
 #define RLHF_SWIGLU(AF, DMA)                                               \
     k_gemm_bf16<TM, TN, 64, 4, 2, AF, true, true, DMA><<<grid, 512, 0, st>>>( \
@@ -1003,7 +1024,7 @@ hipError_t launch_gemm_rope(hipStream_t st, int wdt, int adt, const void* A, con
     constexpr int TM = 256, TN = 256;
     const int N = (ro.n_q_heads + 2 * ro.n_kv_heads) * ro.head_dim;
     const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
-    dim3 grid((tiles_m * tiles_n + 7) / 8 * 8, 1);
+    dim3 grid(xcd_grid(tiles_m, tiles_n), 1);
     const bf16_t* a = (const bf16_t*)A;
     const bf16_t* w = (const bf16_t*)Wqkv;
 #define RLHF_ROPE(AF, HD)                                                                             \
@@ -1034,7 +1055,7 @@ hipError_t launch_gemm_lse(hipStream_t st, int wdt, int adt, const void* A, cons
         return hipErrorInvalidValue;
     constexpr int TM = 256, TN = 256;
     const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
-    dim3 grid((tiles_m * tiles_n + 7) / 8 * 8, 1);
+    dim3 grid(xcd_grid(tiles_m, tiles_n), 1);
     const bf16_t* a = (const bf16_t*)A;
     const bf16_t* w = (const bf16_t*)W_head;
     if (wdt == kF16)
@@ -1059,7 +1080,7 @@ hipError_t launch_gemm(hipStream_t st, int wdt, int adt, const void* A, const vo
         const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
         const int kchunk = ((K + nsplit - 1) / nsplit + 63) / 64 * 64;
         if ((long)(nsplit - 1) * kchunk >= K) return hipErrorInvalidValue;
-        dim3 grid((tiles_m * tiles_n + 7) / 8 * 8, nsplit);
+        dim3 grid(xcd_grid(tiles_m, tiles_n), nsplit);
         k_gemm_bf16<256, 256, 64, 4, 2, true, true, false, true, 0, false, true><<<grid, 512, 0, st>>>(
             (const bf16_t*)A, (const bf16_t*)W, C, M, N, K, kchunk, tiles_m, tiles_n);
         return hipGetLastError();

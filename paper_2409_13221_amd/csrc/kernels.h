@@ -27,6 +27,8 @@ int gemm_choose_nsplit(int wdt, int M, int N, int K, int max_split);
 // launch_bf16_to_half; the 256 x 256 tiling then loads both operands global -> LDS directly.  The
 // fused-epilogue launchers below accept it too.  gemm_is_tall: the shapes launch_gemm runs with that tiling.
 bool gemm_is_tall(int M, int N, int K, int nsplit);
+int gemm_tall_grid(int tiles_m, int tiles_n);                                  // workgroups launched for a tile grid
+bool gemm_tall_tile(int bid, int tiles_m, int tiles_n, int* tm, int* tn);      // false: the workgroup has no tile
 hipError_t launch_bf16_to_half(hipStream_t st, const void* src, void* dst, size_t n_elements);
 // variant 0 = the tiling chosen from M; > 0 forces one (tuning / benchmarks).
 hipError_t launch_gemm(hipStream_t st, int wdt, int adt, const void* A, const void* W, float* C,

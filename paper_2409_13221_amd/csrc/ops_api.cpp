@@ -270,3 +270,12 @@ extern "C" int rlhf_op_bf16_to_half(const void* src, void* dst, int64_t n, void*
     if (!src || !dst || n < 0 || n % 2) return RLHF_EINVAL;
     return status_of(launch_bf16_to_half((hipStream_t)stream, src, dst, (size_t)n));
 }
+
+extern "C" int rlhf_op_gemm_tall_grid(int tiles_m, int tiles_n) {
+    return tiles_m > 0 && tiles_n > 0 ? gemm_tall_grid(tiles_m, tiles_n) : 0;
+}
+
+extern "C" int rlhf_op_gemm_tall_tile(int bid, int tiles_m, int tiles_n, int* tm, int* tn) {
+    if (bid < 0 || tiles_m <= 0 || tiles_n <= 0 || !tm || !tn) return RLHF_EINVAL;
+    return gemm_tall_tile(bid, tiles_m, tiles_n, tm, tn) ? 1 : 0;
+}

@@ -60,3 +60,29 @@ def test_create_rejects_bad_arguments_without_a_gpu():
         raise AssertionError("expected RLHF_EINVAL")
     except R.RlhfError as e:
         assert e.code == R.RLHF_EINVAL and "attention shape" in str(e)
+
+
+def test_tall_gemm_tile_walk_covers_every_tile_once_and_keeps_xcds_on_one_panel():
+    """Host copy of the workgroup -> tile mapping of the 256 x 256 launches (no GPU): a bijection
+    onto the tile grid for ragged and tiny grids; the workgroups that the 8 XCDs run at the same
+    position of their walks sit on the same panel of 8 tile rows; an XCD's columns are its own."""
+    import paper_2409_13221_amd as R
+    for tiles_m, tiles_n in [(24, 48), (24, 16), (24, 86), (3, 17), (1, 125), (9, 125), (11, 3), (1, 1), (33, 9)]:
+        grid = R.rlhf_op_gemm_tall_grid(tiles_m, tiles_n)
+        assert grid % 8 == 0
+        seen, cols_of = {}, {}
+        for bid in range(grid):
+            t = R.rlhf_op_gemm_tall_tile(bid, tiles_m, tiles_n)
+            if t is None:
+                continue
+            assert 0 <= t[0] < tiles_m and 0 <= t[1] < tiles_n and t not in seen
+            seen[t] = bid
+            cols_of.setdefault(bid & 7, set()).add(t[1])
+        assert len(seen) == tiles_m * tiles_n
+        owners = [x for x, cs in cols_of.items() for _ in cs]
+        assert len(owners) == tiles_n                      # every tile column belongs to exactly one XCD
+        if tiles_n >= 8:
+            for slot in range(0, grid // 8, 5):
+                panels = {R.rlhf_op_gemm_tall_tile(slot * 8 + x, tiles_m, tiles_n) for x in range(8)}
+                panels = {t[0] // 8 for t in panels if t is not None}
+                assert len(panels) <= (1 if tiles_n % 8 == 0 else 2)
