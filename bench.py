@@ -368,7 +368,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="7b")
     ap.add_argument("--R_t", type=int, default=-1, help="scoring trigger; -1 = n_samples + 1 (always on)")
-    ap.add_argument("--score_chunk_tokens", type=int, default=6144)
+    ap.add_argument("--score_chunk_tokens", type=int, default=8192)
     ap.add_argument("--max_batch_tokens", type=int, default=8192)
     ap.add_argument("--max_active", type=int, default=256)
     ap.add_argument("--role_mask", type=int, default=ROLE_MASK_DEFAULT)
@@ -389,7 +389,7 @@ def main():
                          "(both GEMM operands direct to LDS); 0: bf16 weights converted on the fly")
     ap.add_argument("--weights", choices=["seeded", "normal"], default="seeded",
                     help="seeded: the workload's counter-based generator; normal: torch's (profiler runs only)")
-    ap.add_argument("--micro_rows", type=int, default=6144, help="rows of the scoring-pass cases of --micro")
+    ap.add_argument("--micro_rows", type=int, default=8192, help="rows of the scoring-pass cases of --micro")
     ap.add_argument("--migrate_probe", action="store_true", help="cost of migration by re-prefill vs moving the KV cache")
     ap.add_argument("--migrate_ctx", default="512,1024,2048", help="contexts of --migrate_probe")
     ap.add_argument("--bs_list", default="1,2,4,8,16,32,64,128,256", help="batch sizes of --bs_curve")

@@ -150,8 +150,11 @@ typedef struct rlhf_stage_opts {
     int32_t R_t;                   /* Section 4.2 trigger: scoring is enabled once the number
                                       of samples still in generation is below R_t.  R_t >
                                       n_samples enables it from the first retirement          */
-    int32_t score_chunk_tokens;    /* a scoring batch closes when the queued retired samples
-                                      hold at least this many prompt+response tokens          */
+    int32_t score_chunk_tokens;    /* a scoring batch holds at most this many prompt+response
+                                      tokens (and at least one sample): it closes when the next
+                                      retired sample would not fit, or when generation ends.
+                                      A multiple of 256 close to max_batch_tokens keeps the
+                                      passes' 256-row GEMM tiles full                         */
     uint32_t role_mask;            /* roles to score: bits REF, CRITIC, REWARD, and ACTOR to
                                       re-score the Actor's log-probs by a full forward        */
     int32_t* trace_active;         /* optional host arrays, trace_cap entries: per step the   */

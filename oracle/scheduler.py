@@ -41,9 +41,12 @@ rules below are this build's reading, stated so that every integer is determined
   (the pool holds any one sample at its cap), so every step decodes at least one token.
 * Scoring batches: after each step's retire, if scoring is enabled (fused mode and
   remaining = waiting + active < R_t, or generation is over) the un-scored part of the
-  retired FIFO is cut, from its head, into consecutive batches each reaching at least
-  `score_chunk_tokens` prompt+response tokens; when generation is over the remainder is
-  flushed as a last, smaller batch.  Sequential mode (fused = 0) applies the same cut only
+  retired FIFO is cut, from its head, into consecutive batches of at most
+  `score_chunk_tokens` prompt+response tokens: a batch closes when the next retired sample
+  would take it past that bound (a single longer sample is a batch of its own); when
+  generation is over the remainder is flushed as a last batch.  (The paper's Section 4.2
+  leaves the size of the scoring batches to the implementation; a bound from above lets a
+  caller pick the pass size that fills its compute tiles.)  Sequential mode (fused = 0) applies the same cut only
   after the last step.
 """
 from dataclasses import dataclass, field
@@ -204,16 +207,21 @@ class SchedulerModel:
         return self.P[i] + self.target[i]
 
     def form_batches(self, chunk_tokens: int) -> List[List[int]]:
-        """Cut the un-scored FIFO into batches of >= chunk_tokens; flush when generation is
-        over.  Returns the batches closed by this call."""
+        """Cut the un-scored FIFO into batches of <= chunk_tokens (at least one sample each): a
+        batch closes once the next retired sample would not fit; flush when generation is over.
+        Returns the batches closed by this call."""
         chunk = max(1, int(chunk_tokens))
         new = []
         while True:
             k, tok = self.n_scored, 0
-            while k < len(self.retired) and tok < chunk:
-                tok += self.seq_tokens(self.retired[k])
+            while k < len(self.retired):
+                t = self.seq_tokens(self.retired[k])
+                if k > self.n_scored and tok + t > chunk:
+                    break
+                tok += t
                 k += 1
-            if tok >= chunk or (self.generation_done() and k > self.n_scored):
+            full = k < len(self.retired)          # the next sample is there and does not fit
+            if k > self.n_scored and (full or self.generation_done()):
                 new.append(self.retired[self.n_scored:k])
                 self.n_scored = k
             else:

@@ -1372,21 +1372,25 @@ int score_ids(rlhf_ctx* c, const int* ids, int n, uint32_t role_mask, bool on_sc
     return RLHF_OK;
 }
 
-// Cut the un-scored part of the retired FIFO into batches of >= chunk tokens; flush the rest
-// when generation is over.  Returns the number of batches closed.
+// Cut the un-scored part of the retired FIFO into batches of <= chunk tokens (at least one sample
+// each): a batch closes once the next retired sample would not fit.  Flush the rest when
+// generation is over.  Returns the number of batches closed.
 int form_batches(rlhf_ctx* c, int chunk_tokens) {
-    const int chunk = std::max(1, chunk_tokens);
+    const long chunk = std::max(1, chunk_tokens);
     const bool done = c->waiting.empty() && c->active.empty();
     int closed = 0;
     for (;;) {
         size_t k = c->n_scored;
         long tok = 0;
-        while (k < c->retired.size() && tok < chunk) {
+        while (k < c->retired.size()) {
             const Sample& s = c->smp[c->retired[k]];
-            tok += s.P + s.gen_len;
+            const long t = s.P + s.gen_len;
+            if (k > c->n_scored && tok + t > chunk) break;
+            tok += t;
             ++k;
         }
-        if (tok >= chunk || (done && k > c->n_scored)) {
+        const bool full = k < c->retired.size();      // the next sample is there and does not fit
+        if (k > c->n_scored && (full || done)) {
             c->n_scored = k;
             c->batch_offsets.push_back((int)k);
             c->batch_step.push_back(c->step - 1);

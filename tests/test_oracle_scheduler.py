@@ -39,12 +39,14 @@ def test_hand_worked_three_samples():
 
 
 @pytest.mark.parametrize("fused,R_t,chunk,want,want_steps", [
-    (True, 4, 10, [[1, 0], [2]], [1, 3]),     # 5 tok after step 0; 5+8 >= 10 after step 1
-    (True, 2, 10, [[1, 0], [2]], [1, 3]),     # remaining (1 waiting + 1 active) < 2 only after step 1
-    (True, 1, 10, [[1, 0], [2]], [3, 3]),     # remaining < 1 only when generation is over
-    (False, 4, 10, [[1, 0], [2]], [3, 3]),    # sequential: same cut, all after the last step
-    (True, 4, 1, [[1], [0], [2]], [0, 1, 3]),  # chunk 1: every sample alone, as it retires
-    (True, 4, 100, [[1, 0, 2]], [3]),         # never reaches the chunk: flushed at the end
+    # retire order 1 (5 tokens, step 0), 0 (8 tokens, step 1), 2 (10 tokens, step 3)
+    (True, 4, 10, [[1], [0], [2]], [1, 3, 3]),   # 5 + 8 > 10: [1] closes when 0 arrives; 8 + 10 > 10: [0] when 2 arrives
+    (True, 4, 13, [[1, 0], [2]], [3, 3]),        # 5 + 8 fits exactly and stays open until 2 (13 + 10 > 13) arrives
+    (True, 2, 10, [[1], [0], [2]], [1, 3, 3]),   # remaining (1 waiting + 1 active) < 2 only after step 1
+    (True, 1, 10, [[1], [0], [2]], [3, 3, 3]),   # remaining < 1 only when generation is over
+    (False, 4, 13, [[1, 0], [2]], [3, 3]),       # sequential: same cut, all after the last step
+    (True, 4, 1, [[1], [0], [2]], [1, 3, 3]),    # bound below every sample: each alone, closed by its successor
+    (True, 4, 100, [[1, 0, 2]], [3]),            # everything fits: flushed at the end
 ])
 def test_hand_worked_batches(fused, R_t, chunk, want, want_steps):
     m = _hand_model()
@@ -126,9 +128,13 @@ def test_invariants_random(seed):
         assert m.gen_len[i] == L[i] and m.ctx[i] == P[i] + L[i] - 1
     assert m.step == max(finish.values()) + 1
     assert [i for b in m.batches for i in b] == m.retired        # batches tile the FIFO in order
+    flat = m.retired
+    pos = 0
     for b in m.batches[:-1]:
-        tok = [m.seq_tokens(i) for i in b]
-        assert sum(tok) >= chunk and sum(tok[:-1]) < chunk       # minimal prefix reaching the chunk
+        tok = sum(m.seq_tokens(i) for i in b)
+        pos += len(b)
+        assert tok <= chunk or len(b) == 1                       # bounded from above (one sample always goes)
+        assert tok + m.seq_tokens(flat[pos]) > chunk             # and maximal: the next sample did not fit
     # waiting samples are admitted in order
     adm = [m.admit_step[i] for i in range(N)]
     assert adm == sorted(adm)
