@@ -27,12 +27,19 @@ template <> struct Chunk<bf16_t> { uint4 r; };
 template <> struct Chunk<f16_t> { uint4 r; };
 template <> struct Chunk<float> { float4 a, b; };
 
+// A decode step reads every cached K and V once: the loads are non-temporal (evict first), so that
+// the KV stream does not push out of the L2 what a GEMM on the other stream keeps there.
+typedef uint32_t u32x4_nt_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld_stream16(const void* p) {
+    const u32x4_nt_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt_t*>(p));
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
 template <typename T> __device__ __forceinline__ Chunk<T> ld_chunk(const T* p);
 template <> __device__ __forceinline__ Chunk<bf16_t> ld_chunk<bf16_t>(const bf16_t* p) {
-    Chunk<bf16_t> c; c.r = *reinterpret_cast<const uint4*>(p); return c;
+    Chunk<bf16_t> c; c.r = ld_stream16(p); return c;
 }
 template <> __device__ __forceinline__ Chunk<f16_t> ld_chunk<f16_t>(const f16_t* p) {
-    Chunk<f16_t> c; c.r = *reinterpret_cast<const uint4*>(p); return c;
+    Chunk<f16_t> c; c.r = ld_stream16(p); return c;
 }
 template <> __device__ __forceinline__ Chunk<float> ld_chunk<float>(const float* p) {
     Chunk<float> c;
@@ -331,12 +338,12 @@ __global__ __launch_bounds__(256) void k_decode_attn_gqa(const f16_t* __restrict
         f16x8_t ka[4];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
-            ka[ks] = *reinterpret_cast<const f16x8_t*>(kt + (size_t)tk * HD + ks * 32 + tg * 8);
+            ka[ks] = __builtin_nontemporal_load(reinterpret_cast<const f16x8_t*>(kt + (size_t)tk * HD + ks * 32 + tg * 8));
         uint2 vr[4][2];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int tok = i * 4 + tg;
-            const uint4 x = *reinterpret_cast<const uint4*>(vt + (size_t)(tok < n_valid ? tok : 0) * HD + head * 8);
+            const uint4 x = ld_stream16(vt + (size_t)(tok < n_valid ? tok : 0) * HD + head * 8);
             vr[i][0] = make_uint2(x.x, x.y);
             vr[i][1] = make_uint2(x.z, x.w);
         }

@@ -218,8 +218,17 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
             }
             const int gk = k0 + c * 8;
             rb[i] = make_uint4(0, 0, 0, 0);
-            if (idx < B_CH && ok && gk < kend)
-                rb[i] = *reinterpret_cast<const uint4*>(W + (size_t)gn * K + gk);
+            if (idx < B_CH && ok && gk < kend) {
+                if (XCD) {
+                    rb[i] = *reinterpret_cast<const uint4*>(W + (size_t)gn * K + gk);
+                } else {
+                    // few-row launches read every weight once: stream them past the caches (evict first), so
+                    // that a tall GEMM on the other stream keeps its tiles in the L2 they share
+                    typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+                    const u32x4v v = __builtin_nontemporal_load(reinterpret_cast<const u32x4v*>(W + (size_t)gn * K + gk));
+                    rb[i] = make_uint4(v[0], v[1], v[2], v[3]);
+                }
+            }
         }
     };
     auto sstore = [&](int buf, uint4* ra, uint4* rb) {
@@ -609,8 +618,8 @@ __global__ __launch_bounds__(256) void k_gemm_rows16(const bf16_t* __restrict__ 
 #define RLHF_ROWS_GLOAD(KT, J)                                                            \
     do {                                                                                  \
         qa[J] = *reinterpret_cast<const u32x4_t*>(pa + (size_t)(KT) * TK);                \
-        qb0[J] = *reinterpret_cast<const u32x4_t*>(pb[0] + (size_t)(KT) * TK);            \
-        qb1[J] = *reinterpret_cast<const u32x4_t*>(pb[1] + (size_t)(KT) * TK);            \
+        qb0[J] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(pb[0] + (size_t)(KT) * TK)); \
+        qb1[J] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(pb[1] + (size_t)(KT) * TK)); \
     } while (0)
 #define RLHF_ROWS_CVT(R)                                                                  \
     do {                                                                                  \
