@@ -143,10 +143,11 @@ CLASS_BOUND = {"gemm_decode": "hbm", "attn_decode": "hbm", "gemm_batch": "mfma",
 
 def rooflines(prof, dtype, steps):
     """One roofline object per kernel class.  Clock: HIP events on the stream the kernel runs on,
-    around every sample_every-th launch of the class over ALL timed stages (rlhf_profile_*); the
-    median bracket of an empty kernel (launch + signalling latency, measured on the same stream when
-    profiling starts) is taken off each bracket, which is what makes the average comparable with
-    the kernel durations rocprofv3 reports.  achieved = algorithmic bytes (or flops) of the sampled
+    around every sample_every-th launch of the class over ALL timed stages (rlhf_profile_*); what a
+    bracket costs beyond its kernels (launch + signalling latency: twice the median bracket of one
+    empty kernel minus that of two, measured on the same stream when profiling starts) is taken off
+    each bracket, which is what makes the average comparable with the kernel durations rocprofv3
+    reports (within about 2 us either way).  achieved = algorithmic bytes (or flops) of the sampled
     launches / their corrected time."""
     out = {}
     for k, v in prof.items():
@@ -525,7 +526,7 @@ def main():
            "roofline": roof, "cpu_baseline": cpu, "fused_vs_sequential": seq, "roofline_all": roofs,
            "roofline_clock": "HIP events on the kernel's own stream around every "
                              f"{args.sample_every}th launch of a class over all {args.steps} timed stages, minus the "
-                             "median bracket of an empty kernel",
+                             "bracket's own cost (2 x median bracket of one empty kernel - that of two)",
            "long_tail": lens}
     print(json.dumps(out), flush=True)
 

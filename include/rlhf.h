@@ -315,9 +315,10 @@ typedef struct rlhf_kernel_profile {
     double total_flops;
     int64_t dropped;               /* launches due for timing that found every event pair of the
                                       running stage in use (65536 per stage): raise sample_every */
-    double bracket_overhead_ms;    /* median event bracket of an EMPTY kernel on the decode stream,
-                                      measured by rlhf_profile_begin: launch and signalling latency
-                                      that every bracket contains besides its kernel's run time  */
+    double bracket_overhead_ms;    /* what an event bracket costs beyond the kernels inside it
+                                      (launch and signalling latency), measured by
+                                      rlhf_profile_begin on the decode stream: twice the median
+                                      bracket of one empty kernel minus that of two             */
 } rlhf_kernel_profile;
 int rlhf_profile_begin(rlhf_ctx* ctx, int32_t sample_every);
 int rlhf_profile_end(rlhf_ctx* ctx, rlhf_kernel_profile* out /* [4] */);

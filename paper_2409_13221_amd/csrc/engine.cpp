@@ -121,7 +121,7 @@ struct Profiler {
     int64_t launches[kClassCount] = {};
     double tot_bytes[kClassCount] = {}, tot_flops[kClassCount] = {};
     int64_t sampled[kClassCount] = {}, dropped[kClassCount] = {};
-    double bracket_overhead_ms = 0;        // median event bracket of an empty kernel, measured at begin
+    double bracket_overhead_ms = 0;        // cost of an event bracket beyond its kernels, measured at begin
     double s_ms[kClassCount] = {}, s_bytes[kClassCount] = {}, s_flops[kClassCount] = {};
 };
 
@@ -1696,20 +1696,25 @@ extern "C" int rlhf_profile_begin(rlhf_ctx* c, int32_t sample_every) {
         p.launches[k] = p.sampled[k] = p.dropped[k] = 0;
         p.tot_bytes[k] = p.tot_flops[k] = p.s_ms[k] = p.s_bytes[k] = p.s_flops[k] = 0;
     }
-    {   // what a bracket costs beyond the kernel inside it: 33 brackets around an empty kernel, median
+    {   // What a bracket costs beyond the kernels inside it.  A bracket around one empty kernel takes
+        // overhead + d, around two of them overhead + 2 d (d = an empty kernel with its dispatch gap), so
+        // overhead = 2 t1 - t2, from the medians of 33 brackets of each kind, taken alternately.
         constexpr int kCal = 33;
-        hipEvent_t ev[2 * kCal];
+        hipEvent_t ev[4 * kCal];
         for (hipEvent_t& e : ev) HIPCK(c, hipEventCreate(&e));
-        for (int i = 0; i < kCal; ++i) {
+        for (int i = 0; i < 2 * kCal; ++i) {
             HIPCK(c, hipEventRecord(ev[2 * i], c->sd));
             HIPCK(c, launch_noop(c->sd));
+            if (i & 1) HIPCK(c, launch_noop(c->sd));
             HIPCK(c, hipEventRecord(ev[2 * i + 1], c->sd));
         }
         HIPCK(c, hipStreamSynchronize(c->sd));
-        float ms[kCal];
-        for (int i = 0; i < kCal; ++i) HIPCK(c, hipEventElapsedTime(&ms[i], ev[2 * i], ev[2 * i + 1]));
-        std::sort(ms, ms + kCal);
-        p.bracket_overhead_ms = ms[kCal / 2];
+        float one[kCal], two[kCal];
+        for (int i = 0; i < 2 * kCal; ++i)
+            HIPCK(c, hipEventElapsedTime((i & 1) ? &two[i / 2] : &one[i / 2], ev[2 * i], ev[2 * i + 1]));
+        std::sort(one, one + kCal);
+        std::sort(two, two + kCal);
+        p.bracket_overhead_ms = std::max(0.0, 2.0 * one[kCal / 2] - two[kCal / 2]);
         for (hipEvent_t e : ev) (void)hipEventDestroy(e);
     }
     return RLHF_OK;
