@@ -143,7 +143,9 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
     const int kend = min(K, kbeg + kchunk);
     const int nk = (kend - kbeg + TK - 1) / TK;
 
-    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    // the wave index as a scalar: the wave's tile origin and the LDS destinations of its direct loads
+    // then live in scalar registers
+    const int t = threadIdx.x, lane = t & 63, w = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = w / WN, wn = w - wm * WN;
 
     // direct path: wave w fills the 1 KB blocks w * D_IT .. of the A tile (1024 / (2 TK) rows each)
@@ -178,23 +180,42 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(const bf16_t* __rest
     }
     typedef __attribute__((address_space(3))) void* lds_ptr_t;
     typedef const __attribute__((address_space(1))) void* glb_ptr_t;
+    // BDMA: both operands come in through buffer loads (buffer_load_dwordx4 ... lds): the lane's 32-bit byte
+    // offset never changes, the walk along K is a scalar offset, so a direct load costs no vector ALU work
+    // and half the address traffic of a 64-bit global load.
+    uint32_t oa[D_IT], ob[DB_IT];
+#if defined(__HIP_DEVICE_COMPILE__)          // the buffer resource type exists in the device pass only
+    __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, BDMA ? -1 : 0, 0x00020000);
+    __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)W, 0, BDMA ? -1 : 0, 0x00020000);
+#endif
+    if (BDMA) {
+#pragma unroll
+        for (int i = 0; i < D_IT; ++i) oa[i] = (uint32_t)(da[i] * 2);
+#pragma unroll
+        for (int i = 0; i < DB_IT; ++i) ob[i] = (uint32_t)(db[i] * 2);
+    }
 
     uint4 ra[ADMA ? 1 : A_IT], rb[BDMA ? 1 : B_IT];
     auto gload = [&](int kt, uint4* ra, uint4* rb) {
         const int k0 = kbeg + kt * TK;
-        if (ADMA) {
+        if (BDMA) {
+#if defined(__HIP_DEVICE_COMPILE__)
+#pragma unroll
+            for (int i = 0; i < D_IT; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)&sA[kt & 1][(w * D_IT + i) * 512], 16, oa[i],
+                                                         k0 * 2, 0, 0);
+#pragma unroll
+            for (int i = 0; i < DB_IT; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w, (lds_ptr_t)&sB[kt & 1][(w * DB_IT + i) * 512], 16, ob[i],
+                                                         k0 * 2, 0, 0);
+#endif
+        } else if (ADMA) {
             // issued first: the wait the compiler places before the next LDS reads then covers
             // these and leaves the weight loads below in flight
 #pragma unroll
             for (int i = 0; i < D_IT; ++i)
                 __builtin_amdgcn_global_load_lds((glb_ptr_t)(A + da[i] + k0),
                                                  (lds_ptr_t)&sA[kt & 1][(w * D_IT + i) * 512], 16, 0, 0);
-        }
-        if (BDMA) {
-#pragma unroll
-            for (int i = 0; i < DB_IT; ++i)
-                __builtin_amdgcn_global_load_lds((glb_ptr_t)(W + db[i] + k0),
-                                                 (lds_ptr_t)&sB[kt & 1][(w * DB_IT + i) * 512], 16, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < (ADMA ? 0 : A_IT); ++i) {
@@ -992,6 +1013,10 @@ static hipError_t launch_bf16(hipStream_t st, int variant, const bf16_t* a, cons
 
 // wdt == kF16: the matrix is a half copy of the bf16 weights and goes global -> LDS directly.
 static bool half_weights_ok(int wdt, int adt, int K) { return wdt != kF16 || (adt == kF16 && K % 64 == 0); }
+// the half-weight kernels address both operands with 32-bit byte offsets per lane
+static bool half_offsets_ok(int wdt, long M, long N, long K) {
+    return wdt != kF16 || ((M > N ? M : N) * K * 2 < (1L << 32));
+}
 
 bool gemm_swiglu_supported(int wdt, int adt, int M, int ffn, int K) {
     return (wdt == kBF16 || wdt == kF16) && half_weights_ok(wdt, adt, K) && (adt == kF16 || adt == kBF16) && M >= 512 &&
@@ -1000,7 +1025,7 @@ bool gemm_swiglu_supported(int wdt, int adt, int M, int ffn, int K) {
 
 hipError_t launch_gemm_swiglu(hipStream_t st, int wdt, int adt, const void* A, const void* W_gate_up,
                               void* act, int M, int ffn, int K) {
-    if (!gemm_swiglu_supported(wdt, adt, M, ffn, K)) return hipErrorInvalidValue;
+    if (!gemm_swiglu_supported(wdt, adt, M, ffn, K) || !half_offsets_ok(wdt, M, 2L * ffn, K)) return hipErrorInvalidValue;
     constexpr int TM = 256, TN = 256;
     const int N = 2 * ffn;
     const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
@@ -1032,6 +1057,7 @@ hipError_t launch_gemm_rope(hipStream_t st, int wdt, int adt, const void* A, con
         return hipErrorInvalidValue;
     constexpr int TM = 256, TN = 256;
     const int N = (ro.n_q_heads + 2 * ro.n_kv_heads) * ro.head_dim;
+    if (!half_offsets_ok(wdt, M, N, K)) return hipErrorInvalidValue;
     const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
     dim3 grid(xcd_grid(tiles_m, tiles_n), 1);
     const bf16_t* a = (const bf16_t*)A;
@@ -1060,7 +1086,7 @@ hipError_t launch_gemm_lse(hipStream_t st, int wdt, int adt, const void* A, cons
                            const LseOut& lo) {
     if (M <= 0) return hipSuccess;
     if (!gemm_lse_supported(wdt, adt, K) || N <= 0 || !lo.tokens || !lo.target_idx || !lo.part_max || !lo.part_sum ||
-        !lo.tgt || lo.n_part != gemm_lse_partials(N))
+        !lo.tgt || lo.n_part != gemm_lse_partials(N) || !half_offsets_ok(wdt, M, N, K))
         return hipErrorInvalidValue;
     constexpr int TM = 256, TN = 256;
     const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
@@ -1085,7 +1111,8 @@ hipError_t launch_gemm(hipStream_t st, int wdt, int adt, const void* A, const vo
     if (nsplit < 1 || K <= 0) return hipErrorInvalidValue;
     if (wdt == kF16) {
         // half copy of a bf16 matrix: the tall tiling with both operands global -> LDS directly
-        if (adt != kF16 || K % 64 || (variant != 0 && variant != 7)) return hipErrorInvalidValue;
+        if (adt != kF16 || K % 64 || (variant != 0 && variant != 7) || !half_offsets_ok(wdt, M, N, K))
+            return hipErrorInvalidValue;
         const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
         const int kchunk = ((K + nsplit - 1) / nsplit + 63) / 64 * 64;
         if ((long)(nsplit - 1) * kchunk >= K) return hipErrorInvalidValue;
