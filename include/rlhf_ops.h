@@ -29,8 +29,9 @@ extern "C" {
  * way the kernels do on the fly (exact for magnitudes >= 2^-14, toward zero on half's subnormal
  * grid below).  With such a copy as W, rlhf_op_gemm takes dtype = 2 (A must be half, K a multiple
  * of 64; the 256 x 256 tiling with both operands loaded global -> LDS directly, any nsplit whose
- * ranges are non-empty), and rlhf_op_gemm_swiglu / rlhf_op_gemm_rope / rlhf_op_lm_head_logprob take
- * act_half = 2.  This is what the stage runs in prefill / scoring passes when the engine option
+ * ranges are non-empty; A and W each smaller than 4 GiB, since the loads address them with 32-bit
+ * byte offsets, else RLHF_EINVAL), and rlhf_op_gemm_swiglu / rlhf_op_gemm_rope /
+ * rlhf_op_lm_head_logprob take act_half = 2 under the same conditions.  This is what the stage runs in prefill / scoring passes when the engine option
  * half_weight_copies is set; results are bit-identical to the bf16-weight path. */
 int rlhf_op_bf16_to_half(const void* src, void* dst, int64_t n, void* stream);
 int rlhf_op_gemm_nsplit(int dtype, int M, int N, int K, int max_split);

@@ -648,16 +648,20 @@ extern "C" int rlhf_load_weights(rlhf_ctx* c, int role, const rlhf_weights* w) {
         const rlhf_model_cfg& m = c->mc;
         const size_t d = m.d_model, qd = (size_t)m.n_q_heads * m.head_dim, kvd = (size_t)m.n_kv_heads * m.head_dim;
         const size_t L = m.n_layers, f = m.ffn;
-        struct Item { const void* src; const void** dst; size_t n; };
+        struct Item { const void* src; const void** dst; size_t n, per_matrix; };
         const Item items[] = {
-            {w->wqkv, &rw.h16.wqkv, L * (qd + 2 * kvd) * d},
-            {w->wo, &rw.h16.wo, L * d * qd},
-            {w->w_gate_up, &rw.h16.w_gate_up, L * 2 * f * d},
-            {w->w_down, &rw.h16.w_down, L * d * f},
-            {w->head, &rw.h16.head, (role == RLHF_ACTOR || role == RLHF_REF) ? (size_t)m.vocab * d : 0},
+            {w->wqkv, &rw.h16.wqkv, L * (qd + 2 * kvd) * d, (qd + 2 * kvd) * d},
+            {w->wo, &rw.h16.wo, L * d * qd, d * qd},
+            {w->w_gate_up, &rw.h16.w_gate_up, L * 2 * f * d, 2 * f * d},
+            {w->w_down, &rw.h16.w_down, L * d * f, d * f},
+            {w->head, &rw.h16.head, (role == RLHF_ACTOR || role == RLHF_REF) ? (size_t)m.vocab * d : 0, (size_t)m.vocab * d},
         };
+        // the kernels that take the copies address an operand with 32-bit byte offsets: a matrix, or a pass's
+        // activations, of 4 GiB or more stays on the bf16-weight path
+        const size_t lim = (size_t)1 << 32;
+        const bool acts_fit = (size_t)c->ec.max_batch_tokens * std::max(d, f) * 2 < lim;
         for (const Item& it : items) {
-            if (it.n == 0 || !it.src) continue;
+            if (it.n == 0 || !it.src || !acts_fit || it.per_matrix * 2 >= lim) continue;
             void* p = nullptr;
             if (hipMalloc(&p, it.n * 2) != hipSuccess) {
                 (void)hipGetLastError();
