@@ -113,8 +113,11 @@ __host__ __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles
 // A small merge kernel turns the partials into log_softmax(z)[target] (k_lse_merge).
 //
 // BDMA: W is IEEE half in memory (a copy of the bf16 matrix made when the weights were bound) and
-// takes the same direct global -> LDS path as the activations: no staging registers, no
-// conversion, no LDS stores in the loop.  Needs ADMA's conditions and half activations.
+// goes global -> LDS directly like the activations: no staging registers, no conversion, no LDS
+// stores in the loop.  Both operands then come in as buffer loads (buffer_load_dwordx4 ... lds):
+// a lane's 32-bit byte offset is fixed for the whole K walk, which is the instruction's scalar
+// offset, so issuing a load costs one scalar add for M0 and no vector work (operands < 4 GiB).
+// Needs ADMA's conditions and half activations.
 //
 // RING (> 1, register-staged tiles only): that many K tiles are kept in flight in registers, so that a
 // workgroup which streams its weights over the whole K range (no split) still has enough bytes on
