@@ -276,6 +276,26 @@ def test_gemm_mid_rows_take_the_tall_tiling_with_split_k(M, N, K):
 
 # ------------------------------------------- half copies of the weights (both operands direct to LDS)
 
+def test_half_weight_gemm_rejects_operands_of_4_gib():
+    """The half-weight kernels address an operand with 32-bit byte offsets: an A of 4 GiB is refused with
+    an error before anything is launched (nothing in it is read, so it need not be initialised)."""
+    R = _R()
+    K, N, M = 2048, 256, 1 << 20                       # M * K * 2 bytes = 4 GiB
+    A = torch.empty(M, K, dtype=torch.float16, device="cuda")
+    Wh = R.rlhf_op_bf16_to_half(_bf16_round(np.zeros((N, K)) + 0.01).cuda())
+    C = torch.empty(1, M, N, device="cuda")
+    with pytest.raises(Exception) as err:
+        R.rlhf_op_gemm(A, Wh, C, 1)
+    assert "rlhf_op_gemm" in str(err.value) or "EINVAL" in str(err.value)
+    del A, C
+    # one row less fits
+    A = torch.zeros(M - 1, K, dtype=torch.float16, device="cuda")
+    C = torch.empty(1, M - 1, N, device="cuda")
+    R.rlhf_op_gemm(A, Wh, C, 1)
+    torch.cuda.synchronize()
+    assert float(C.abs().max()) == 0.0
+
+
 def test_half_weight_copies_give_bit_identical_tall_gemms():
     """With an IEEE-half copy of the bf16 matrix (the library's own conversion) the tall kernels load
     both operands global -> LDS directly; plain, split-K, SwiGLU, rotary and LM-head epilogues must
